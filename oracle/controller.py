@@ -1,0 +1,181 @@
+"""CPU checker for the batch-size controller.  TEST INFRASTRUCTURE ONLY (see
+oracle/network.py): the product path never imports this.
+
+The controller is a heuristic iteration, so this file follows the paper's
+steps in the paper's order and notation (Section "Proportional-Control Based
+Dynamic Policy", Eq. 4 and Eq. 5, and the four-step summary that closes the
+subsection "Control stability"):
+
+  1. smoothed iteration times mu_k (an EWMA over the iterations since the last
+     readjustment; the caller keeps that state and passes mu as `t`);
+  2. error tau_k = t_k - tbar, throughput X_k = b_k / t_k,
+     Delta(b_k) = -X_k tau_k, b_k' = b_k + Delta(b_k);
+  3. bounds b_min <= b_k' <= b_max;
+  4. dead-band: all workers are resized if max_k |Delta b_k| / b_k exceeds the
+     threshold, otherwise nothing changes.
+
+Where the paper is silent this file takes these readings:
+  * tbar is the unweighted arithmetic mean, summed in worker order;
+  * a scalar gain kp multiplies Delta (kp = 1 is the paper's rule);
+  * the proportional rule does not conserve sum_k b_k, while the paper keeps
+    the global batch fixed: after the bounds the real-valued sizes are
+    rescaled to the global batch G, turned into integers by the
+    largest-remainder method (ties to the lowest worker index), and entries
+    that rescaling/rounding pushed outside the bounds are moved back one
+    sample at a time (taking from the largest / giving to the smallest entry,
+    ties to the lowest index);
+  * the dead-band compares the final integer candidates with the old sizes,
+    relative to the old size, in absolute value, strictly greater-than;
+    a worker that had b_k = 0 and would receive samples always exceeds it.
+
+All arithmetic is IEEE double, one rounding per operation, in exactly the
+order written here (Python floats never fuse a multiply with an add).
+
+Pins (tests/test_oracle_controller.py): the closed form b' = b tbar / t of the
+paper, the sign rule, the throughput-proportional fixed point on synthetic
+speed profiles, a hand-worked two-worker example, brute-force invariants on
+all small integer inputs, and the dead-band/noise behaviour.  The rescaling
+and integer rounding are this build's reading (parity unpinned by the paper;
+pinned by sum(b_next) = G and the bounds).
+"""
+from __future__ import annotations
+
+import math
+
+
+class ControllerError(ValueError):
+    pass
+
+
+def proportional_step(t, b, kp=1.0):
+    """Eq. 4 and Eq. 5, real-valued: r_k = b_k + kp * (-X_k tau_k)."""
+    K = len(b)
+    s = 0.0
+    for k in range(K):
+        s = s + float(t[k])
+    tbar = s / float(K)
+    r = []
+    for k in range(K):
+        bk = float(b[k])
+        tk = float(t[k])
+        X = bk / tk
+        tau = tk - tbar
+        delta = -((kp * X) * tau)
+        r.append(bk + delta)
+    return r
+
+
+def largest_remainder(q, total):
+    """Integers f_k >= 0 with sum = total, f_k in {floor(q_k), floor(q_k)+1}."""
+    K = len(q)
+    f = [int(math.floor(v)) for v in q]
+    frac = [q[k] - float(f[k]) for k in range(K)]
+    rem = total - sum(f)
+    taken = [False] * K
+    while rem > 0:
+        best = -1
+        for k in range(K):
+            if not taken[k] and (best < 0 or frac[k] > frac[best]):
+                best = k
+        if best < 0:                      # more than K left over: start another round
+            taken = [False] * K
+            continue
+        f[best] += 1
+        taken[best] = True
+        rem -= 1
+    while rem < 0:                        # cannot happen for sum(q) ~ total; kept for safety
+        best = -1
+        for k in range(K):
+            if f[k] > 0 and (best < 0 or frac[k] < frac[best]):
+                best = k
+        f[best] -= 1
+        frac[best] = 2.0
+        rem += 1
+    return f
+
+
+def enforce_bounds_integer(c, total, b_min, b_max):
+    """Move integer sizes back inside [b_min, b_max] while keeping their sum."""
+    K = len(c)
+    c = [min(max(v, b_min), b_max) for v in c]
+    s = sum(c)
+    while s > total:
+        best = -1
+        for k in range(K):
+            if c[k] > b_min and (best < 0 or c[k] > c[best]):
+                best = k
+        c[best] -= 1
+        s -= 1
+    while s < total:
+        best = -1
+        for k in range(K):
+            if c[k] < b_max and (best < 0 or c[k] < c[best]):
+                best = k
+        c[best] += 1
+        s += 1
+    return c
+
+
+def controller_step(t, b, global_batch, kp=1.0, deadband=0.05, b_min=1, b_max=None,
+                    **_unused):
+    """One controller invocation: (smoothed) times t[K], sizes b[K] -> new integer sizes."""
+    K = len(b)
+    G = int(global_batch)
+    if b_max is None:
+        b_max = G
+    if K < 1 or len(t) != K:
+        raise ControllerError("K < 1 or length mismatch")
+    if any(int(v) < 0 for v in b) or sum(int(v) for v in b) != G:
+        raise ControllerError("b must be non-negative and sum to the global batch")
+    if any((not math.isfinite(v)) or v <= 0.0 for v in t):
+        raise ControllerError("iteration times must be finite and positive")
+    if b_min < 0 or b_max < b_min or K * b_min > G or K * b_max < G:
+        raise ControllerError("bounds cannot hold the global batch")
+    if not (math.isfinite(kp) and math.isfinite(deadband)) or deadband < 0.0:
+        raise ControllerError("bad gains")
+
+    r = proportional_step(t, b, kp)                                   # step 2
+    lo, hi = float(b_min), float(b_max)
+    r = [lo if v < lo else (hi if v > hi else v) for v in r]          # step 3
+    S = 0.0
+    for v in r:
+        S = S + v
+    if not (S > 0.0):
+        return [int(v) for v in b]
+    q = [(v * float(G)) / S for v in r]                               # keep sum_k b_k = G
+    cand = largest_remainder(q, G)
+    cand = enforce_bounds_integer(cand, G, int(b_min), int(b_max))
+
+    worst = 0.0                                                       # step 4
+    for k in range(K):
+        d = abs(cand[k] - int(b[k]))
+        if d == 0:
+            continue
+        rel = math.inf if int(b[k]) == 0 else float(d) / float(int(b[k]))
+        if rel > worst:
+            worst = rel
+    if worst > deadband:
+        return cand
+    return [int(v) for v in b]
+
+
+def ewma_update(mu, t, alpha, reset):
+    """Step 1: mu_k <- t_k on the first iteration after a readjustment, else
+    mu_k <- alpha t_k + (1 - alpha) mu_k."""
+    if reset:
+        return [float(v) for v in t]
+    return [alpha * float(t[k]) + (1.0 - alpha) * float(mu[k]) for k in range(len(t))]
+
+
+def static_allocation(X, b0):
+    """Open-loop sizes proportional to the throughput estimates X_k with the
+    global batch K*b0 kept (Section "Static Mini-batch Allocation Policy"; the
+    printed formula lacks the factor K that its own invariant sum_k b_k = K b0
+    requires).  Integers by the largest-remainder method."""
+    K = len(X)
+    G = K * int(b0)
+    S = 0.0
+    for v in X:
+        S = S + float(v)
+    q = [(float(v) * float(G)) / S for v in X]
+    return largest_remainder(q, G)

@@ -1,0 +1,223 @@
+"""CPU checker for the per-worker gradient, its weighted aggregation and the
+SGD update.  TEST INFRASTRUCTURE ONLY: nothing in the product path may import
+this package; it exists so that the GPU kernels can be compared with a plain,
+slow, obviously-correct computation.
+
+Everything is float64 numpy, written as the textbook definition:
+
+* per-worker gradient  grad f(x_{b_k,t})  (Section "Key Idea: Variable
+  Mini-Batch Sizes"): the gradient of the mean softmax-cross-entropy loss over
+  the worker's own b_k samples, by hand-written back-propagation;
+* lambda_k = b_k / sum_i b_i and the weighted average sum_k lambda_k grad_k
+  (same section, the lambda definition and Eq. 2);
+* x_{t+1} = x_t - eta * sum_k lambda_k grad_k (Eq. 3, with the stray 1/K read
+  as a typo: with sum_k lambda_k = 1 the update must reduce to Eq. 1 when all
+  b_k are equal), and heavy-ball momentum for the workload that names it.
+
+Pins (tests/test_oracle_network.py): central finite differences, a pure
+Python loop convolution, closed forms for softmax regression, the delta-image
+convolution, and the split-invariance of the weighted average.
+
+`emulate_bf16=True` additionally rounds to bfloat16 (round-to-nearest-even)
+the quantities a bf16 implementation stores in 16 bits: the weights (not the
+biases), the input, every stored hidden activation and every stored
+activation-gradient.  Accumulation stays float64.  This switch has no pin of
+its own beyond "rounding moves a value by at most 2^-9 relative" (parity
+unpinned for the rounding emulation itself; the un-rounded path is pinned).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+# --------------------------------------------------------------------------
+# bfloat16 rounding emulation
+# --------------------------------------------------------------------------
+def round_bf16(a):
+    """Round float values to the nearest bfloat16 (ties to even); returns float64."""
+    f = np.ascontiguousarray(a, dtype=np.float32)
+    u = f.view(np.uint32).astype(np.uint64)
+    lsb = (u >> np.uint64(16)) & np.uint64(1)
+    r = (u + np.uint64(0x7FFF) + lsb) & np.uint64(0xFFFF0000)
+    out = r.astype(np.uint32).view(np.float32).astype(np.float64)
+    nan = np.isnan(f)
+    if nan.any():
+        out[nan] = np.nan
+    return out.reshape(np.shape(a))
+
+
+def _q(a, emulate):
+    return round_bf16(a) if emulate else a
+
+
+# --------------------------------------------------------------------------
+# layers (forward and backward), float64
+# --------------------------------------------------------------------------
+def conv3x3_forward(x, W, bias, stride):
+    """x [n,H,W,Cin] (NHWC), W [3,3,Cin,Cout], zero padding 1 -> [n,Ho,Wo,Cout]."""
+    n, H, Wd, _ = x.shape
+    Ho = (H + 2 - 3) // stride + 1
+    Wo = (Wd + 2 - 3) // stride + 1
+    xp = np.pad(x, ((0, 0), (1, 1), (1, 1), (0, 0)))
+    out = np.zeros((n, Ho, Wo, W.shape[3])) + bias
+    for kh in range(3):
+        for kw in range(3):
+            patch = xp[:, kh:kh + stride * (Ho - 1) + 1:stride,
+                       kw:kw + stride * (Wo - 1) + 1:stride, :]
+            out += patch @ W[kh, kw]
+    return out
+
+
+def conv3x3_backward(x, W, dy, stride, need_dx=True):
+    """Gradients of conv3x3_forward wrt W, bias and (optionally) x."""
+    n, H, Wd, _ = x.shape
+    _, Ho, Wo, _ = dy.shape
+    xp = np.pad(x, ((0, 0), (1, 1), (1, 1), (0, 0)))
+    dW = np.zeros_like(W)
+    dxp = np.zeros_like(xp)
+    for kh in range(3):
+        for kw in range(3):
+            sl = (slice(None), slice(kh, kh + stride * (Ho - 1) + 1, stride),
+                  slice(kw, kw + stride * (Wo - 1) + 1, stride), slice(None))
+            patch = xp[sl]
+            dW[kh, kw] = np.tensordot(patch, dy, axes=([0, 1, 2], [0, 1, 2]))
+            if need_dx:
+                dxp[sl] += dy @ W[kh, kw].T
+    db = dy.sum(axis=(0, 1, 2))
+    dx = dxp[:, 1:-1, 1:-1, :] if need_dx else None
+    return dW, db, dx
+
+
+def softmax_xent(z, y):
+    """Mean cross-entropy over the rows of z and its gradient wrt z.
+
+    p = softmax(z) (max-subtracted), loss = -(1/n) sum_i log p[i, y_i],
+    dz = (p - onehot(y)) / n.
+    """
+    n = z.shape[0]
+    zs = z - z.max(axis=1, keepdims=True)
+    e = np.exp(zs)
+    p = e / e.sum(axis=1, keepdims=True)
+    loss = -np.mean(np.log(p[np.arange(n), y]))
+    dz = p.copy()
+    dz[np.arange(n), y] -= 1.0
+    return loss, dz / n
+
+
+def _f64_params(params, emulate):
+    return [(_q(np.asarray(W, np.float64), emulate), np.asarray(b, np.float64))
+            for W, b in params]
+
+
+def forward(spec, params, x, emulate_bf16=False):
+    """Logits [n, classes] and the list of stored layer inputs (for backward)."""
+    P = _f64_params(params, emulate_bf16)
+    a = _q(np.asarray(x, np.float64), emulate_bf16)
+    stored, pi = [], 0
+    n_layers = len(spec["layers"])
+    for li, L in enumerate(spec["layers"]):
+        last = li == n_layers - 1
+        stored.append(a)
+        if L["kind"] == "dense":
+            W, b = P[pi]; pi += 1
+            a = a.reshape(a.shape[0], -1) @ W + b
+        elif L["kind"] == "conv3x3":
+            W, b = P[pi]; pi += 1
+            a = conv3x3_forward(a, W, b, L["stride"])
+        elif L["kind"] == "gap":
+            a = a.mean(axis=(1, 2))
+        else:
+            raise ValueError(L["kind"])
+        if L.get("relu"):
+            a = np.maximum(a, 0.0)
+        if not last:
+            a = _q(a, emulate_bf16)          # stored hidden activation
+    stored.append(a)                          # logits (kept in full precision)
+    return a, stored
+
+
+def loss_and_gradient(spec, params, x, y, emulate_bf16=False):
+    """Mean loss over the given samples and its gradient as [(dW, dbias)].
+
+    This is grad f(x_{b_k,t}) for one worker when (x, y) is that worker's
+    mini-batch.  An empty mini-batch yields loss 0 and a zero gradient.
+    """
+    n = int(np.shape(x)[0])
+    if n == 0:
+        return 0.0, [(np.zeros(np.shape(W)), np.zeros(np.shape(b))) for W, b in params]
+    P = _f64_params(params, emulate_bf16)
+    z, stored = forward(spec, params, x, emulate_bf16)
+    loss, dz = softmax_xent(z, np.asarray(y, np.int64))
+    da = _q(dz, emulate_bf16)                 # stored dlogits
+    grads = [None] * len(P)
+    pi = len(P)
+    first_param_layer = next(i for i, L in enumerate(spec["layers"])
+                             if L["kind"] in ("dense", "conv3x3"))
+    for li in range(len(spec["layers"]) - 1, -1, -1):
+        L = spec["layers"][li]
+        a_in, a_out = stored[li], stored[li + 1]
+        if L.get("relu"):
+            da = da * (a_out > 0.0)           # relu'(0) = 0; exact, needs no re-rounding
+        need_dx = li > first_param_layer
+        if L["kind"] == "dense":
+            pi -= 1
+            W, _ = P[pi]
+            a2 = a_in.reshape(a_in.shape[0], -1)
+            grads[pi] = (a2.T @ da, da.sum(axis=0))
+            if need_dx:
+                da = _q((da @ W.T).reshape(a_in.shape), emulate_bf16)
+        elif L["kind"] == "conv3x3":
+            pi -= 1
+            W, _ = P[pi]
+            dW, db, dx = conv3x3_backward(a_in, W, da, L["stride"], need_dx)
+            grads[pi] = (dW, db)
+            if need_dx:
+                da = _q(dx, emulate_bf16)
+        elif L["kind"] == "gap":
+            _, H, Wd, _ = a_in.shape
+            da = _q(np.broadcast_to(da[:, None, None, :] / (H * Wd), a_in.shape), emulate_bf16)
+    return loss, grads
+
+
+def worker_gradients(spec, params, x, y, b, emulate_bf16=False):
+    """Per-worker losses and gradients: worker k owns rows [off_k, off_k + b_k)."""
+    losses, grads, off = [], [], 0
+    for bk in b:
+        l, g = loss_and_gradient(spec, params, x[off:off + bk], y[off:off + bk], emulate_bf16)
+        losses.append(l); grads.append(g); off += bk
+    assert off == np.shape(x)[0], "sum(b) must equal the number of rows"
+    return losses, grads
+
+
+# --------------------------------------------------------------------------
+# aggregation and update
+# --------------------------------------------------------------------------
+def weighted_aggregate(worker_grads, b):
+    """sum_k lambda_k g_k with lambda_k = b_k / sum_i b_i (fixed k order)."""
+    total = float(sum(b))
+    out = None
+    for bk, g in zip(b, worker_grads):
+        lam = float(bk) / total
+        if out is None:
+            out = [(lam * dW, lam * db) for dW, db in g]
+        else:
+            out = [(oW + lam * dW, ob + lam * db) for (oW, ob), (dW, db) in zip(out, g)]
+    return out
+
+
+def sgd_update(params, g, lr):
+    """x <- x - eta * g."""
+    return [(np.asarray(W, np.float64) - lr * gW, np.asarray(b, np.float64) - lr * gb)
+            for (W, b), (gW, gb) in zip(params, g)]
+
+
+def momentum_update(params, velocity, g, lr, mu):
+    """Heavy ball: v <- mu v + g ; x <- x - eta v.  Returns (params, velocity)."""
+    v = [(mu * vW + gW, mu * vb + gb) for (vW, vb), (gW, gb) in zip(velocity, g)]
+    p = [(np.asarray(W, np.float64) - lr * vW, np.asarray(b, np.float64) - lr * vb)
+         for (W, b), (vW, vb) in zip(params, v)]
+    return p, v
+
+
+def zeros_like_params(params):
+    return [(np.zeros(np.shape(W)), np.zeros(np.shape(b))) for W, b in params]

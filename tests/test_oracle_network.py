@@ -1,0 +1,237 @@
+"""Pins for oracle/network.py against things other than itself."""
+import itertools
+
+import numpy as np
+import pytest
+import scipy.signal
+import scipy.special
+import torch
+
+from oracle import network as on
+from paper_2305_12213_amd import synth
+
+
+def tiny_mlp():
+    return synth.mlp_spec([5, 4, 4, 3], "f32")
+
+
+def tiny_cnn():
+    return {"dtype": "f32", "input": (6, 6, 2), "classes": 3,
+            "layers": [synth.conv3x3(2, 3, 1), synth.conv3x3(3, 4, 2), synth.gap(),
+                       synth.dense(4, 3, relu=False)]}
+
+
+def rand_params(spec, seed, bias=True):
+    rng = np.random.default_rng(seed)
+    out = []
+    for ws, bs in synth.param_shapes(spec):
+        out.append((rng.standard_normal(ws) * 0.5,
+                    rng.standard_normal(bs) * (0.3 if bias else 0.0)))
+    return out
+
+
+def mean_loss(spec, params, x, y):
+    z, _ = on.forward(spec, params, x)
+    lse = scipy.special.logsumexp(z, axis=1)
+    return float(np.mean(lse - z[np.arange(len(y)), y]))
+
+
+@pytest.mark.parametrize("make_spec", [tiny_mlp, tiny_cnn])
+def test_gradient_matches_central_finite_differences(make_spec):
+    spec = make_spec()
+    rng = np.random.default_rng(3)
+    params = rand_params(spec, 5)
+    n = 3
+    x = rng.standard_normal((n,) + tuple(spec["input"]))
+    y = rng.integers(0, spec["classes"], n)
+    loss, grads = on.loss_and_gradient(spec, params, x, y)
+    assert abs(loss - mean_loss(spec, params, x, y)) < 1e-12
+    h = 1e-6
+    worst = 0.0
+    for li, (W, b) in enumerate(params):
+        for which, arr in enumerate((W, b)):
+            flat = arr.reshape(-1)
+            g = grads[li][which].reshape(-1)
+            for i in range(flat.size):
+                old = flat[i]
+                flat[i] = old + h; lp = mean_loss(spec, params, x, y)
+                flat[i] = old - h; lm = mean_loss(spec, params, x, y)
+                flat[i] = old
+                fd = (lp - lm) / (2 * h)
+                worst = max(worst, abs(fd - g[i]) / max(1e-3, abs(fd)))
+    assert worst < 2e-6, worst
+
+
+def conv_loops(x, W, bias, stride):
+    n, H, Wd, Cin = x.shape
+    Cout = W.shape[3]
+    Ho, Wo = (H - 1) // stride + 1, (Wd - 1) // stride + 1
+    out = np.zeros((n, Ho, Wo, Cout))
+    for i, ho, wo, co in itertools.product(range(n), range(Ho), range(Wo), range(Cout)):
+        acc = bias[co]
+        for kh, kw, ci in itertools.product(range(3), range(3), range(Cin)):
+            h, w = ho * stride + kh - 1, wo * stride + kw - 1
+            if 0 <= h < H and 0 <= w < Wd:
+                acc += x[i, h, w, ci] * W[kh, kw, ci, co]
+        out[i, ho, wo, co] = acc
+    return out
+
+
+@pytest.mark.parametrize("stride,H,Wd", [(1, 5, 4), (2, 6, 6), (2, 5, 7)])
+def test_conv_forward_matches_brute_force_loops(stride, H, Wd):
+    rng = np.random.default_rng(stride * 10 + H)
+    x = rng.standard_normal((2, H, Wd, 3))
+    W = rng.standard_normal((3, 3, 3, 2))
+    bias = rng.standard_normal(2)
+    np.testing.assert_allclose(on.conv3x3_forward(x, W, bias, stride),
+                               conv_loops(x, W, bias, stride), atol=1e-12)
+
+
+def test_conv_single_channel_is_scipy_correlate2d():
+    rng = np.random.default_rng(11)
+    img = rng.standard_normal((7, 9))
+    ker = rng.standard_normal((3, 3))
+    got = on.conv3x3_forward(img[None, :, :, None], ker[:, :, None, None], np.zeros(1), 1)
+    want = scipy.signal.correlate2d(img, ker, mode="same", boundary="fill")
+    np.testing.assert_allclose(got[0, :, :, 0], want, atol=1e-12)
+
+
+def test_conv_of_delta_image_returns_flipped_kernel():
+    ker = np.arange(9.0).reshape(3, 3) + 1
+    img = np.zeros((5, 5)); img[2, 2] = 1.0
+    out = on.conv3x3_forward(img[None, :, :, None], ker[:, :, None, None], np.zeros(1), 1)
+    np.testing.assert_array_equal(out[0, 1:4, 1:4, 0], ker[::-1, ::-1])
+
+
+def test_centre_tap_conv_is_a_dense_layer_per_pixel():
+    rng = np.random.default_rng(2)
+    x = rng.standard_normal((2, 4, 4, 3))
+    M = rng.standard_normal((3, 5))
+    W = np.zeros((3, 3, 3, 5)); W[1, 1] = M
+    b = rng.standard_normal(5)
+    np.testing.assert_allclose(on.conv3x3_forward(x, W, b, 1), x @ M + b, atol=1e-12)
+
+
+def test_conv_backward_is_the_adjoint_of_forward():
+    # <conv(x; W), dy> has gradient dW wrt W and dx wrt x: check both inner products.
+    rng = np.random.default_rng(8)
+    for stride in (1, 2):
+        x = rng.standard_normal((2, 6, 6, 3)); W = rng.standard_normal((3, 3, 3, 4))
+        y = on.conv3x3_forward(x, W, np.zeros(4), stride)
+        dy = rng.standard_normal(y.shape)
+        dW, db, dx = on.conv3x3_backward(x, W, dy, stride)
+        x2 = rng.standard_normal(x.shape); W2 = rng.standard_normal(W.shape)
+        lhs = np.sum(on.conv3x3_forward(x2, W, np.zeros(4), stride) * dy)
+        assert abs(lhs - np.sum(x2 * dx)) < 1e-9
+        lhs = np.sum(on.conv3x3_forward(x, W2, np.zeros(4), stride) * dy)
+        assert abs(lhs - np.sum(W2 * dW)) < 1e-9
+        np.testing.assert_allclose(db, dy.reshape(-1, 4).sum(0), atol=1e-12)
+
+
+def test_softmax_regression_closed_form():
+    # one linear layer: dW = X^T (P - Y) / b, dbias = colsum(P - Y) / b
+    spec = synth.mlp_spec([6, 4], "f32")
+    rng = np.random.default_rng(4)
+    X = rng.standard_normal((7, 6)); y = rng.integers(0, 4, 7)
+    params = rand_params(spec, 1)
+    W, b = params[0]
+    Pm = scipy.special.softmax(X @ W + b, axis=1)
+    Y = np.eye(4)[y]
+    _, g = on.loss_and_gradient(spec, params, X, y)
+    np.testing.assert_allclose(g[0][0], X.T @ (Pm - Y) / 7, atol=1e-13)
+    np.testing.assert_allclose(g[0][1], (Pm - Y).sum(0) / 7, atol=1e-13)
+
+
+def test_dlogits_rows_sum_to_zero_and_probabilities_to_one():
+    rng = np.random.default_rng(0)
+    z = rng.standard_normal((5, 9)) * 30
+    y = rng.integers(0, 9, 5)
+    loss, dz = on.softmax_xent(z, y)
+    assert np.all(np.abs(dz.sum(axis=1)) < 1e-15)
+    assert np.isfinite(loss)
+    want = -np.mean(scipy.special.log_softmax(z, axis=1)[np.arange(5), y])
+    assert abs(loss - want) < 1e-12
+
+
+def test_relu_derivative_at_zero_is_zero():
+    spec = synth.mlp_spec([2, 2, 2], "f32")
+    params = [(np.eye(2), np.zeros(2)), (np.ones((2, 2)), np.zeros(2))]
+    x = np.array([[0.0, 1.0]])           # first hidden unit sits exactly at 0
+    _, g = on.loss_and_gradient(spec, params, x, np.array([0]))
+    assert np.all(g[0][0][:, 0] == 0.0) and g[0][1][0] == 0.0
+
+
+@pytest.mark.parametrize("make_spec", [tiny_mlp, tiny_cnn])
+def test_weighted_average_over_any_split_is_the_full_batch_gradient(make_spec):
+    spec = make_spec()
+    rng = np.random.default_rng(9)
+    params = rand_params(spec, 2)
+    n = 12
+    x = rng.standard_normal((n,) + tuple(spec["input"])); y = rng.integers(0, 3, n)
+    _, full = on.loss_and_gradient(spec, params, x, y)
+    for b in ([12], [6, 6], [1, 11], [5, 0, 7], [1, 1, 1, 9], [3, 3, 3, 3], [0, 12, 0]):
+        _, gk = on.worker_gradients(spec, params, x, y, b)
+        agg = on.weighted_aggregate(gk, b)
+        for (aW, ab), (fW, fb) in zip(agg, full):
+            np.testing.assert_allclose(aW, fW, atol=1e-12)
+            np.testing.assert_allclose(ab, fb, atol=1e-12)
+
+
+def test_equal_split_reduces_to_the_plain_mean_of_eq1():
+    spec = tiny_mlp()
+    rng = np.random.default_rng(1)
+    params = rand_params(spec, 3)
+    x = rng.standard_normal((8, 5)); y = rng.integers(0, 3, 8)
+    _, gk = on.worker_gradients(spec, params, x, y, [2, 2, 2, 2])
+    agg = on.weighted_aggregate(gk, [2, 2, 2, 2])
+    for li in range(len(params)):
+        np.testing.assert_allclose(agg[li][0], sum(g[li][0] for g in gk) / 4, atol=1e-14)
+    # Eq. 1 is written with per-worker gradient *sums*: (1/K)(1/b) sum_k sum_i grad_i
+    sums = [[(2 * dW, 2 * db) for dW, db in g] for g in gk]
+    for li in range(len(params)):
+        eq1 = sum(s[li][0] for s in sums) / 4 / 2
+        np.testing.assert_allclose(agg[li][0], eq1, atol=1e-14)
+
+
+def test_lambda_sums_to_one_via_constant_gradients():
+    g = [[(np.ones((2, 2)), np.ones(2))] for _ in range(3)]
+    agg = on.weighted_aggregate(g, [5, 1, 10])
+    np.testing.assert_allclose(agg[0][0], 1.0, atol=1e-15)
+
+
+def test_sgd_and_momentum_closed_forms():
+    p = [(np.zeros((2, 2)), np.zeros(2))]
+    g = [(np.ones((2, 2)), np.ones(2))]
+    q = on.sgd_update(p, g, 0.1)
+    np.testing.assert_allclose(q[0][0], -0.1); np.testing.assert_allclose(q[0][1], -0.1)
+    v = on.zeros_like_params(p)
+    mu, lr = 0.9, 0.05
+    x_expected = 0.0
+    for n in range(1, 8):
+        p, v = on.momentum_update(p, v, g, lr, mu)
+        vn = (1 - mu ** n) / (1 - mu)              # v_n = g (1 - mu^n) / (1 - mu)
+        np.testing.assert_allclose(v[0][0], vn, rtol=1e-13)
+        x_expected -= lr * vn
+        np.testing.assert_allclose(p[0][0], x_expected, rtol=1e-12)
+
+
+def test_bf16_rounding_matches_torch_and_ties_go_to_even():
+    vals = np.array([1.0, 1 + 2.0 ** -8, 1 + 2.0 ** -8 + 2.0 ** -16, 1 + 3 * 2.0 ** -8,
+                     -0.1, 3.14159, 1e-30, 65504.0, 0.0], np.float32)
+    want = np.array([1.0, 1.0, 1.0078125, 1.015625], np.float64)
+    got = on.round_bf16(vals)
+    np.testing.assert_array_equal(got[:4], want)
+    rng = np.random.default_rng(0)
+    r = (rng.standard_normal(10000) * 10.0 ** rng.integers(-5, 5, 10000)).astype(np.float32)
+    t = torch.from_numpy(r).to(torch.bfloat16).to(torch.float64).numpy()
+    np.testing.assert_array_equal(on.round_bf16(r), t)
+
+
+def test_bf16_emulation_stays_close_to_the_exact_gradient():
+    spec = synth.mlp_spec([32, 16, 16, 5], "bf16")
+    params = synth.init_params(spec, "he", 3)
+    x, y = synth.make_batch(spec, "normal", 24, 3, 0)
+    _, g = on.loss_and_gradient(spec, params, x, y)
+    _, ge = on.loss_and_gradient(spec, params, x, y, emulate_bf16=True)
+    for (a, _), (e, _) in zip(g, ge):
+        assert np.max(np.abs(a - e)) / np.max(np.abs(a)) < 2e-2
