@@ -1,0 +1,197 @@
+/*
+ * dynb -- data-parallel hot path of dynamic mini-batching on one MI355X (gfx950).
+ *
+ * K simulated workers each compute the gradient of the mean loss over their own
+ * variable-sized mini-batch b_k (paper, Section "Key Idea: Variable Mini-Batch
+ * Sizes"); the gradients are combined with weights lambda_k = b_k / sum_i b_i
+ * (Eq. 2), applied by SGD (Eq. 3), and a host-side proportional controller
+ * resizes the b_k so that iteration times equalise (Section
+ * "Proportional-Control Based Dynamic Policy", Eq. 4 and Eq. 5, and the
+ * four-step summary at the end of "Control stability").
+ *
+ * Conventions for every call
+ *   - plain C ABI; every function returns DYNB_OK (0) or a negative error code and
+ *     never throws; dynb_last_error() returns a thread-local message for the last
+ *     failure on the calling thread.
+ *   - "device" pointers are HIP device memory owned by the caller; the library
+ *     allocates no device memory.  "host" pointers are ordinary host memory, read
+ *     or written before the call returns.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Device
+ *     work is enqueued on it and the call returns without synchronising.
+ *   - b[K] is a HOST array of non-negative batch sizes; worker k owns the rows
+ *     [off_k, off_k + b_k) of the global batch, off_k = sum_{j<k} b_j.  b_k = 0 is
+ *     legal: that worker's gradient is all zeros and its weight lambda_k is 0.
+ *   - Flat parameter layout (params, grads, aggregated gradient, velocity): for each
+ *     layer that has parameters, in model order, its weight in C order (dense:
+ *     [n_in][n_out]; conv3x3: [3][3][c_in][c_out]) followed by its bias [n_out].
+ *     P = number of parameters; P_pad = P rounded up to a multiple of 256 floats.
+ *     Vectors have P_pad elements; the tail beyond P is ignored on input and written
+ *     as zero.
+ */
+#ifndef DYNB_H
+#define DYNB_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DYNB_MAX_WORKERS 64
+#define DYNB_MAX_LAYERS 16
+
+enum {
+  DYNB_OK = 0,
+  DYNB_ERR_BADARG = -1,      /* null pointer, K out of range, sum(b) mismatch, bad value */
+  DYNB_ERR_UNSUPPORTED = -2, /* a model or size this build has no kernel for */
+  DYNB_ERR_HIP = -3,         /* a HIP runtime call failed */
+  DYNB_ERR_STATE = -4        /* call order violated (e.g. model not bound) */
+};
+
+enum { DYNB_F32 = 0, DYNB_BF16 = 1 };
+enum { DYNB_LAYER_DENSE = 0, DYNB_LAYER_CONV3X3 = 1, DYNB_LAYER_GAP = 2 };
+
+/* One layer.  DENSE: n_in -> n_out.  CONV3X3: c_in = n_in, c_out = n_out, 3x3 kernel,
+ * zero padding 1, `stride` 1 or 2, NHWC.  GAP: global average pool over H x W (n_in,
+ * n_out, stride ignored).  relu != 0 applies max(., 0) to the layer output. */
+typedef struct {
+  int32_t kind;
+  int32_t n_in;
+  int32_t n_out;
+  int32_t stride;
+  int32_t relu;
+} dynb_layer_desc;
+
+/* dtype DYNB_F32: fp32 storage and arithmetic.  DYNB_BF16: weights (not biases),
+ * the input, stored activations and stored activation-gradients are rounded to
+ * bfloat16 (nearest-even); products accumulate in fp32; biases, logits, softmax,
+ * gradients and master parameters are fp32.  The input is [n][in_h][in_w][in_c]
+ * (a dense-only model uses in_h = in_w = 1, in_c = features).  The last layer must
+ * produce n_classes logits. */
+typedef struct {
+  int32_t dtype;
+  int32_t in_h, in_w, in_c;
+  int32_t n_classes;
+  int32_t n_layers;
+  const dynb_layer_desc* layers; /* host, copied by dynb_model_create */
+} dynb_model_desc;
+
+/* Controller constants.  kp = 1 is the paper's rule (gain = measured throughput);
+ * deadband is the paper's Delta_min(b) (0.05 in its evaluation); b_min/b_max are the
+ * per-worker size bounds; ewma_alpha is the smoothing constant of dynb_ewma_update. */
+typedef struct {
+  double kp;
+  double deadband;
+  double ewma_alpha;
+  int32_t b_min;
+  int32_t b_max;
+} dynb_gains;
+
+typedef struct dynb_model dynb_model;
+
+const char* dynb_last_error(void);
+
+/* ---- model handle (host bookkeeping only) ------------------------------------- */
+
+/* Validates the description and builds the layer plan.  *m is owned by the caller
+ * and released with dynb_model_destroy. */
+int dynb_model_create(const dynb_model_desc* desc, dynb_model** m);
+void dynb_model_destroy(dynb_model* m);
+int64_t dynb_model_num_params(const dynb_model* m);    /* P     */
+int64_t dynb_model_padded_params(const dynb_model* m); /* P_pad */
+
+/* Bytes of device workspace needed for global batches up to max_global_batch split
+ * over up to max_workers workers (activations, activation-gradients, 16-bit weight
+ * copies, logits, losses).  Returns 0 on bad arguments. */
+size_t dynb_model_workspace_bytes(const dynb_model* m, int32_t max_global_batch,
+                                  int32_t max_workers);
+
+/* Attaches caller-owned device memory: params = fp32 master parameters [P_pad];
+ * workspace of at least dynb_model_workspace_bytes(...) bytes, 256-byte aligned.  The
+ * workspace is cleared and the weight copies are derived from params on `stream`. */
+int dynb_model_bind(dynb_model* m, float* params, void* workspace, size_t workspace_bytes,
+                    int32_t max_global_batch, int32_t max_workers, void* stream);
+
+/* Re-derives the weight copies used by the kernels from the bound master parameters.
+ * Call after writing params by any means other than dynb_model_sgd_update. */
+int dynb_model_sync_weights(dynb_model* m, void* stream);
+
+/* Device pointer to float[max_workers]: mean loss of each worker's mini-batch from the
+ * most recent dynb_forward_backward (0 for an idle worker). */
+const float* dynb_model_worker_loss(const dynb_model* m);
+
+/* Copies those K losses to host_loss[K] (host): enqueues the copy behind the work already
+ * on `stream` and waits for it.  The only call of this library that blocks on the device. */
+int dynb_model_read_worker_loss(const dynb_model* m, float* host_loss, int32_t K, void* stream);
+
+/* ---- the hot path -------------------------------------------------------------- */
+
+/* Per-worker gradient grad f(x_{b_k,t}): for every worker k, forward pass, mean
+ * softmax-cross-entropy loss over its own b_k samples, and backward pass; writes
+ * grads[k][0..P_pad) (device, fp32, row stride P_pad).
+ *   x : device fp32 [sum(b)][in_h][in_w][in_c];  y : device int32 [sum(b)], labels in
+ *   [0, n_classes);  b : host int32 [K], 1 <= K <= max_workers, sum(b) <= max_global_batch. */
+int dynb_forward_backward(dynb_model* m, const float* x, const int32_t* y, const int32_t* b,
+                          int32_t K, float* grads, void* stream);
+
+/* Weighted average of Eq. 2: out[p] = sum_k (b_k / sum_i b_i) * grads[k*n + p], summed in
+ * worker order.  grads device fp32 [K][n]; out device fp32 [n]; n % 4 == 0; both 16-byte
+ * aligned.  sum(b) must be > 0. */
+int dynb_weighted_aggregate(const float* grads, const int32_t* b, int32_t K, int64_t n, float* out,
+                            void* stream);
+
+/* Eq. 3 (read without its stray 1/K): params[p] -= lr * g[p] for p < n. */
+int dynb_sgd_update(float* params, const float* g, int64_t n, float lr, void* stream);
+
+/* Heavy-ball momentum: v = mu * v + g ; params -= lr * v. */
+int dynb_sgd_momentum_update(float* params, float* velocity, const float* g, int64_t n, float lr,
+                             float mu, void* stream);
+
+/* The update on the model's bound parameters followed by a refresh of the weight copies
+ * the next dynb_forward_backward reads.  velocity == NULL selects plain SGD (mu ignored). */
+int dynb_model_sgd_update(dynb_model* m, const float* g, float lr, float mu, float* velocity,
+                          void* stream);
+
+/* ---- controller (host only) ---------------------------------------------------- */
+
+/* One controller invocation (four-step summary of "Control stability"): from the
+ * (smoothed) iteration times t[K] > 0 and the current sizes b[K] (sum = global_batch)
+ * compute b_next[K]:
+ *   tbar = mean_k t_k;  X_k = b_k / t_k;  r_k = b_k - kp * X_k * (t_k - tbar)   (Eq. 4, 5)
+ *   clamp r_k to [b_min, b_max]; rescale to sum global_batch; largest-remainder rounding
+ *   (ties to the lowest k); move entries back inside the bounds one sample at a time;
+ *   if max_k |b_next_k - b_k| / b_k > deadband take the new sizes, else keep b.
+ * IEEE double arithmetic in a fixed order: results are reproducible bit for bit.
+ * Errors (DYNB_ERR_BADARG): null pointer, K outside [1, DYNB_MAX_WORKERS], b_k < 0,
+ * sum(b) != global_batch, t_k not finite or <= 0, K*b_min > global_batch,
+ * K*b_max < global_batch, non-finite gains, deadband < 0. */
+int dynb_controller_step(const double* iter_times, const int32_t* b, int32_t K,
+                         int32_t global_batch, const dynb_gains* gains, int32_t* b_next);
+
+/* Exponentially weighted moving average of iteration times since the last
+ * readjustment ("Exponential Smoothing"): reset != 0 sets mu = t, otherwise
+ * mu_k = alpha * t_k + (1 - alpha) * mu_k.  mu is caller-owned state. */
+int dynb_ewma_update(double* mu, const double* t, int32_t K, double alpha, int32_t reset);
+
+/* Open-loop sizes proportional to throughput estimates X[K] > 0 with the global batch
+ * K * b0 kept ("Static Mini-batch Allocation Policy"), largest-remainder rounding. */
+int dynb_static_allocate(const double* X, int32_t K, int32_t b0, int32_t* b_out);
+
+/* ---- per-kernel timing (measurement aid) ---------------------------------------- */
+
+/* When enabled, every kernel launch is bracketed by HIP events on its stream and
+ * accumulated per kernel class.  dynb_profile_collect synchronises and folds pending
+ * events into the totals.  Classes: see dynb_profile_name. */
+int dynb_profile_enable(int32_t on);
+int dynb_profile_reset(void);
+int dynb_profile_collect(void);
+int32_t dynb_profile_num_classes(void);
+const char* dynb_profile_name(int32_t cls);
+int dynb_profile_get(int32_t cls, double* total_ms, int64_t* launches, double* flops,
+                     double* bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DYNB_H */

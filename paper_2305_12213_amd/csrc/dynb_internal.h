@@ -1,0 +1,111 @@
+// Internal declarations shared by the library's translation units (not part of the ABI).
+#ifndef DYNB_INTERNAL_H
+#define DYNB_INTERNAL_H
+
+#include <cstddef>
+#include <cstdint>
+
+#include "../../include/dynb.h"
+
+namespace dynb {
+
+// Records a thread-local message and returns `code`.
+int fail(int code, const char* fmt, ...);
+
+constexpr int ROW_PAD = 8;    // every worker's row segment is padded to a multiple of this
+constexpr int COL_PAD = 64;   // leading dimensions are padded to a multiple of this
+
+inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
+
+// Row segments of the K workers, passed to kernels by value.
+//   off[k]  : first row of worker k in the caller's (dense) batch, off[K] = sum(b)
+//   poff[k] : first row of worker k in the padded row space, poff[k+1]-poff[k] = round_up(b_k, 8)
+struct Segs {
+  int K;
+  int off[DYNB_MAX_WORKERS + 1];
+  int poff[DYNB_MAX_WORKERS + 1];
+};
+
+struct Lambdas {
+  int K;
+  float w[DYNB_MAX_WORKERS];
+};
+
+// Kernel classes for the timing aid.
+enum KClass {
+  KC_GEMM_FWD = 0,
+  KC_GEMM_DGRAD,
+  KC_GEMM_WGRAD,
+  KC_PACK,
+  KC_TRANSPOSE,
+  KC_SOFTMAX,
+  KC_BIAS_GRAD,
+  KC_FINALIZE,
+  KC_AGGREGATE,
+  KC_UPDATE,
+  KC_WEIGHT_CAST,
+  KC_CONV_AUX,
+  KC_COUNT
+};
+
+// Brackets one launch with events when timing is on.  flops/bytes are the algorithmic
+// work of the launch (accumulated per class).
+struct Timed {
+  Timed(KClass cls, void* stream, double flops, double bytes);
+  ~Timed();
+  int slot;
+  void* stream;
+};
+
+enum { MODE_FWD = 0, MODE_DGRAD = 1, MODE_WGRAD = 2 };
+
+// C'[i][j] = sum_k A[i][k] * B[j][k]; both operands are k-contiguous with 16-byte aligned
+// rows.  Meaning of (i, j) and of the outputs depends on `mode`:
+//   FWD   : i = batch row, j = output feature.  v = acc + bias[j], optional ReLU;
+//           C[i*ldc + j] = T(v) if C; Cf[i*ldcf + j] = v if Cf.
+//   DGRAD : i = batch row, j = input feature.  v = mask[i*ldmask + j] > 0 ? acc : 0 (mask
+//           optional); C[i*ldc + j] = T(v).
+//   WGRAD : one group per worker g: operands start at column poff[g], depth
+//           poff[g+1]-poff[g]; i = output feature, j = input feature;
+//           Cf[g*group_stride + j*ldcf + i] = acc.
+struct GemmArgs {
+  const void* A; int64_t lda; int M;   // rows of A  (i)
+  const void* B; int64_t ldb; int N;   // rows of B  (j)
+  int K;                               // reduction length (FWD/DGRAD), multiple of 8
+  int mode;
+  const float* bias; int relu;
+  void* C; int64_t ldc;
+  float* Cf; int64_t ldcf;
+  const void* mask; int64_t ldmask;
+  int64_t group_stride;
+};
+
+int launch_gemm(int dtype, const GemmArgs& a, const Segs& s, void* stream);
+
+// x fp32 [rows][D] (dense rows) -> out T [padded rows][ld]; pad rows are written as zero.
+int launch_pack_rows(int dtype, const float* x, int D, void* out, int64_t ld, const Segs& s,
+                     void* stream);
+// in T [R][ldi] -> out T [C][ldo] (out[c][r] = in[r][c])
+int launch_transpose(int dtype, const void* in, int64_t ldi, int R, int C, void* out, int64_t ldo,
+                     void* stream);
+// logits fp32 [Mp][ldz] -> dz T [Mp][ldd] (pad rows and pad columns zero), rowloss[Mp]
+int launch_softmax_xent(int dtype, const float* logits, int64_t ldz, const int32_t* y, int C,
+                        void* dz, int64_t ldd, int ld_cols, float* rowloss, const Segs& s,
+                        void* stream);
+// grads[g*group_stride + n] = sum over worker g's rows of dyT[n][row]
+int launch_bias_grad(int dtype, const void* dyT, int64_t ld, int N, float* grads,
+                     int64_t group_stride, const Segs& s, void* stream);
+// loss[g] = mean of rowloss over worker g's rows; grads[g][P..P_pad) = 0
+int launch_finalize(const float* rowloss, float* loss, float* grads, int64_t P, int64_t P_pad,
+                    const Segs& s, void* stream);
+int launch_aggregate(const float* grads, const Lambdas& lam, int64_t n, float* out, void* stream);
+int launch_sgd(float* params, const float* g, int64_t n, float lr, void* stream);
+int launch_momentum(float* params, float* v, const float* g, int64_t n, float lr, float mu,
+                    void* stream);
+// W fp32 [R][C] (dense) -> Wn T [R][ldn] and Wt T [C][ldt]
+int launch_weight_cast(int dtype, const float* W, int R, int C, void* Wn, int64_t ldn, void* Wt,
+                       int64_t ldt, void* stream);
+
+}  // namespace dynb
+
+#endif

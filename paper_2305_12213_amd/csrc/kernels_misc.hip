@@ -1,0 +1,237 @@
+// Small kernels around the GEMMs: input packing into the padded row space, transposes,
+// softmax cross-entropy with the per-worker 1/b_k, bias gradients, loss reduction and the
+// 16-bit weight copies.
+#include <hip/hip_runtime.h>
+
+#include "dynb_internal.h"
+
+namespace dynb {
+namespace {
+
+typedef __bf16 bf16;
+
+template <typename T> __device__ inline T from_float(float v) { return (T)v; }
+template <typename T> __device__ inline float to_float(T v) { return (float)v; }
+
+// Padded row -> (worker, row inside the worker's segment).
+__device__ inline void locate(const Segs& s, int prow, int& k, int& r) {
+  k = 0;
+  while (k + 1 < s.K && prow >= s.poff[k + 1]) ++k;
+  r = prow - s.poff[k];
+}
+
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ inline float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// ---- pack: dense fp32 rows -> padded rows of T --------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void pack_rows_kernel(const float* __restrict__ x, int D,
+                                                        T* __restrict__ out, int64_t ld, Segs s) {
+  const int prow = blockIdx.y;
+  int k, r;
+  locate(s, prow, k, r);
+  const bool live = r < s.off[k + 1] - s.off[k];
+  const float* src = x + (int64_t)(s.off[k] + r) * D;
+  T* dst = out + (int64_t)prow * ld;
+  for (int c = blockIdx.x * 256 + threadIdx.x; c < D; c += gridDim.x * 256)
+    dst[c] = from_float<T>(live ? src[c] : 0.f);
+}
+
+// ---- transpose: out[c][r] = in[r][c] ----------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void transpose_kernel(const T* __restrict__ in, int64_t ldi,
+                                                        int R, int C, T* __restrict__ out,
+                                                        int64_t ldo) {
+  __shared__ T tile[64][66];
+  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (int i = ty; i < 64; i += 4) {
+    const int r = r0 + i, c = c0 + tx;
+    tile[i][tx] = (r < R && c < C) ? in[(int64_t)r * ldi + c] : from_float<T>(0.f);
+  }
+  __syncthreads();
+  for (int i = ty; i < 64; i += 4) {
+    const int c = c0 + i, r = r0 + tx;
+    if (c < C && r < R) out[(int64_t)c * ldo + r] = tile[tx][i];
+  }
+}
+
+// ---- softmax cross-entropy, one wavefront per padded row --------------------------------
+// dz = (softmax(z) - onehot(y)) / b_k for live rows; zero for pad rows and pad columns.
+template <typename T>
+__global__ __launch_bounds__(256) void softmax_xent_kernel(const float* __restrict__ z, int64_t ldz,
+                                                           const int32_t* __restrict__ y, int C,
+                                                           T* __restrict__ dz, int64_t ldd,
+                                                           int ld_cols, float* __restrict__ rowloss,
+                                                           Segs s) {
+  const int lane = threadIdx.x & 63;
+  const int prow = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (prow >= s.poff[s.K]) return;
+  int k, r;
+  locate(s, prow, k, r);
+  const int bk = s.off[k + 1] - s.off[k];
+  T* drow = dz + (int64_t)prow * ldd;
+  if (r >= bk) {
+    for (int c = lane; c < ld_cols; c += 64) drow[c] = from_float<T>(0.f);
+    if (lane == 0) rowloss[prow] = 0.f;
+    return;
+  }
+  const float* zr = z + (int64_t)prow * ldz;
+  int label = y[s.off[k] + r];
+  label = label < 0 ? 0 : (label >= C ? C - 1 : label);   // keeps the read in bounds
+  float m = -INFINITY;
+  for (int c = lane; c < C; c += 64) m = fmaxf(m, zr[c]);
+  m = wave_max(m);
+  float sum = 0.f;
+  for (int c = lane; c < C; c += 64) sum += expf(zr[c] - m);
+  sum = wave_sum(sum);
+  const float inv = 1.f / sum;
+  const float scale = 1.f / (float)bk;
+  for (int c = lane; c < ld_cols; c += 64) {
+    float v = 0.f;
+    if (c < C) v = (expf(zr[c] - m) * inv - (c == label ? 1.f : 0.f)) * scale;
+    drow[c] = from_float<T>(v);
+  }
+  if (lane == 0) rowloss[prow] = logf(sum) - (zr[label] - m);
+}
+
+// ---- bias gradient: one wavefront per (output feature, worker) --------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void bias_grad_kernel(const T* __restrict__ dyT, int64_t ld,
+                                                        int N, float* __restrict__ grads,
+                                                        int64_t group_stride, Segs s) {
+  const int lane = threadIdx.x & 63;
+  const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int g = blockIdx.y;
+  if (n >= N) return;
+  const int bk = s.off[g + 1] - s.off[g];
+  const T* row = dyT + (int64_t)n * ld + s.poff[g];
+  float acc = 0.f;
+  for (int i = lane; i < bk; i += 64) acc += to_float<T>(row[i]);
+  acc = wave_sum(acc);
+  if (lane == 0) grads[(int64_t)g * group_stride + n] = acc;
+}
+
+// ---- per-worker mean loss, and zero tail of each worker's gradient vector ----------------
+__global__ __launch_bounds__(64) void finalize_kernel(const float* __restrict__ rowloss,
+                                                      float* __restrict__ loss,
+                                                      float* __restrict__ grads, int64_t P,
+                                                      int64_t P_pad, Segs s) {
+  const int g = blockIdx.x, lane = threadIdx.x;
+  const int bk = s.off[g + 1] - s.off[g];
+  float acc = 0.f;
+  for (int i = lane; i < bk; i += 64) acc += rowloss[s.poff[g] + i];
+  acc = wave_sum(acc);
+  if (lane == 0) loss[g] = bk > 0 ? acc / (float)bk : 0.f;
+  if (grads)
+    for (int64_t p = P + lane; p < P_pad; p += 64) grads[(int64_t)g * P_pad + p] = 0.f;
+}
+
+// ---- weight copies: Wn[r][c] = T(W[r][c]),  Wt[c][r] = T(W[r][c]) ----------------------
+template <typename T>
+__global__ __launch_bounds__(256) void weight_cast_kernel(const float* __restrict__ W, int R, int C,
+                                                          T* __restrict__ Wn, int64_t ldn,
+                                                          T* __restrict__ Wt, int64_t ldt) {
+  __shared__ float tile[64][65];
+  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (int i = ty; i < 64; i += 4) {
+    const int r = r0 + i, c = c0 + tx;
+    float v = 0.f;
+    if (r < R && c < C) {
+      v = W[(int64_t)r * C + c];
+      Wn[(int64_t)r * ldn + c] = from_float<T>(v);
+    }
+    tile[i][tx] = v;
+  }
+  __syncthreads();
+  for (int i = ty; i < 64; i += 4) {
+    const int c = c0 + i, r = r0 + tx;
+    if (c < C && r < R) Wt[(int64_t)c * ldt + r] = from_float<T>(tile[tx][i]);
+  }
+}
+
+inline int ok(const char* what) {
+  return hipGetLastError() == hipSuccess ? DYNB_OK : fail(DYNB_ERR_HIP, "%s: launch failed", what);
+}
+
+}  // namespace
+
+#define DISPATCH_T(dtype, CALL)                              \
+  do {                                                       \
+    if ((dtype) == DYNB_BF16) { typedef bf16 T; CALL; }      \
+    else { typedef float T; CALL; }                          \
+  } while (0)
+
+int launch_pack_rows(int dtype, const float* x, int D, void* out, int64_t ld, const Segs& s,
+                     void* stream) {
+  const int rows = s.poff[s.K];
+  if (rows == 0) return DYNB_OK;
+  const int es = dtype == DYNB_BF16 ? 2 : 4;
+  Timed t(KC_PACK, stream, 0, (double)s.off[s.K] * D * (4 + es));
+  dim3 grid((D + 255) / 256 > 8 ? 8 : (D + 255) / 256, rows);
+  DISPATCH_T(dtype, hipLaunchKernelGGL(pack_rows_kernel<T>, grid, dim3(256), 0,
+                                       (hipStream_t)stream, x, D, (T*)out, ld, s));
+  return ok("pack_rows");
+}
+
+int launch_transpose(int dtype, const void* in, int64_t ldi, int R, int C, void* out, int64_t ldo,
+                     void* stream) {
+  if (R == 0 || C == 0) return DYNB_OK;
+  const int es = dtype == DYNB_BF16 ? 2 : 4;
+  Timed t(KC_TRANSPOSE, stream, 0, 2.0 * R * C * es);
+  dim3 grid((C + 63) / 64, (R + 63) / 64);
+  DISPATCH_T(dtype, hipLaunchKernelGGL(transpose_kernel<T>, grid, dim3(256), 0,
+                                       (hipStream_t)stream, (const T*)in, ldi, R, C, (T*)out, ldo));
+  return ok("transpose");
+}
+
+int launch_softmax_xent(int dtype, const float* logits, int64_t ldz, const int32_t* y, int C,
+                        void* dz, int64_t ldd, int ld_cols, float* rowloss, const Segs& s,
+                        void* stream) {
+  const int rows = s.poff[s.K];
+  if (rows == 0) return DYNB_OK;
+  Timed t(KC_SOFTMAX, stream, 0, (double)rows * C * 6);
+  DISPATCH_T(dtype, hipLaunchKernelGGL(softmax_xent_kernel<T>, dim3((rows + 3) / 4), dim3(256), 0,
+                                       (hipStream_t)stream, logits, ldz, y, C, (T*)dz, ldd,
+                                       ld_cols, rowloss, s));
+  return ok("softmax_xent");
+}
+
+int launch_bias_grad(int dtype, const void* dyT, int64_t ld, int N, float* grads,
+                     int64_t group_stride, const Segs& s, void* stream) {
+  const int es = dtype == DYNB_BF16 ? 2 : 4;
+  Timed t(KC_BIAS_GRAD, stream, 0, (double)s.off[s.K] * N * es);
+  DISPATCH_T(dtype, hipLaunchKernelGGL(bias_grad_kernel<T>, dim3((N + 3) / 4, s.K), dim3(256), 0,
+                                       (hipStream_t)stream, (const T*)dyT, ld, N, grads,
+                                       group_stride, s));
+  return ok("bias_grad");
+}
+
+int launch_finalize(const float* rowloss, float* loss, float* grads, int64_t P, int64_t P_pad,
+                    const Segs& s, void* stream) {
+  Timed t(KC_FINALIZE, stream, 0, 0);
+  hipLaunchKernelGGL(finalize_kernel, dim3(s.K), dim3(64), 0, (hipStream_t)stream, rowloss, loss,
+                     grads, P, P_pad, s);
+  return ok("finalize");
+}
+
+int launch_weight_cast(int dtype, const float* W, int R, int C, void* Wn, int64_t ldn, void* Wt,
+                       int64_t ldt, void* stream) {
+  const int es = dtype == DYNB_BF16 ? 2 : 4;
+  Timed t(KC_WEIGHT_CAST, stream, 0, (double)R * C * (4 + 2 * es));
+  dim3 grid((C + 63) / 64, (R + 63) / 64);
+  DISPATCH_T(dtype, hipLaunchKernelGGL(weight_cast_kernel<T>, grid, dim3(256), 0,
+                                       (hipStream_t)stream, W, R, C, (T*)Wn, ldn, (T*)Wt, ldt));
+  return ok("weight_cast");
+}
+
+}  // namespace dynb

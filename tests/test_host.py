@@ -1,0 +1,142 @@
+"""CPU-side checks of the C library: exported symbols, controller parity (bit-exact),
+argument validation.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import controller as oc
+from paper_2305_12213_amd import binding, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "dynb.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dynb_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = binding.load()
+    names = declared_symbols()
+    assert len(names) >= 20
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(binding.SYMBOLS) == names
+
+
+def run_trace(step_fn, cfg, steps):
+    b = list(cfg["b0"])
+    trace = [b]
+    for _ in range(steps):
+        t = synth.iteration_times(b, cfg["speeds"])
+        b = step_fn(t, b, cfg["global_batch"], cfg["gains"])
+        trace.append(b)
+    return trace
+
+
+@pytest.mark.parametrize("ci", range(5))
+def test_controller_traces_of_the_five_workloads_are_bit_exact(ci):
+    cfg = synth.config(ci)
+    want = run_trace(lambda t, b, G, g: oc.controller_step(t, b, G, **g), cfg, cfg["steps"])
+    got = run_trace(binding.controller_step, cfg, cfg["steps"])
+    assert got == want
+    assert all(sum(b) == cfg["global_batch"] for b in got)
+
+
+def test_controller_matches_oracle_on_random_inputs():
+    rng = np.random.default_rng(2305)
+    for it in range(3000):
+        K = int(rng.integers(1, 17))
+        G = int(rng.integers(K, 5000))
+        b = synth.ragged_split(G, K, 1000 + it)
+        t = list(rng.uniform(0.01, 100.0, K) * 10.0 ** rng.integers(-3, 4))
+        lo = int(rng.integers(0, G // K + 1))
+        hi = int(rng.integers(-(-G // K), G + 1))
+        gains = dict(kp=float(rng.choice([1.0, 0.5, 0.25, 1.7])),
+                     deadband=float(rng.choice([0.0, 0.05, 0.2])), b_min=lo, b_max=hi)
+        want = oc.controller_step(t, b, G, **gains)
+        got = binding.controller_step(t, b, G, gains)
+        assert got == want, (t, b, G, gains)
+
+
+def test_controller_matches_oracle_near_ties():
+    # speeds that make the rescaled sizes land on or next to .5 and integer boundaries
+    for G in (10, 12, 64, 100):
+        for s in ([1, 1], [1, 1, 1], [3, 1], [1, 1, 2], [0.5, 0.5, 0.25, 0.25], [1, 3, 5, 7]):
+            K = len(s)
+            b = [G // K] * K
+            b[0] += G - sum(b)
+            t = synth.iteration_times(b, s)
+            for db in (0.0, 0.05):
+                gains = dict(kp=1.0, deadband=db, b_min=0, b_max=G)
+                assert binding.controller_step(t, b, G, gains) == oc.controller_step(t, b, G, **gains)
+
+
+def test_controller_error_codes():
+    g = dict(kp=1.0, deadband=0.05, b_min=1, b_max=10)
+    for t, b, G in (([1.0, -1.0], [5, 5], 10), ([1.0, float("nan")], [5, 5], 10),
+                    ([1.0, 1.0], [5, 4], 10), ([1.0, 1.0], [11, -1], 10),
+                    ([1.0, float("inf")], [5, 5], 10)):
+        with pytest.raises(binding.DynbError) as e:
+            binding.controller_step(t, b, G, g)
+        assert e.value.code == -1
+    with pytest.raises(binding.DynbError):
+        binding.controller_step([1.0, 1.0], [5, 5], 10, dict(g, b_min=6))
+    with pytest.raises(binding.DynbError):
+        binding.controller_step([1.0, 1.0], [5, 5], 10, dict(g, b_max=4))
+    with pytest.raises(binding.DynbError):
+        binding.controller_step([1.0, 1.0], [5, 5], 10, dict(g, deadband=-0.1))
+    assert "controller" in binding.load().dynb_last_error().decode()
+
+
+def test_ewma_and_static_allocation_match_oracle():
+    rng = np.random.default_rng(5)
+    mu_c = mu_o = None
+    for i in range(20):
+        t = list(rng.uniform(0.5, 2.0, 5))
+        reset = i % 7 == 0
+        mu_c = binding.ewma_update(mu_c, t, 0.3, reset)
+        mu_o = oc.ewma_update(mu_o, t, 0.3, reset)
+        assert mu_c == mu_o
+    for _ in range(200):
+        K = int(rng.integers(1, 12))
+        X = list(rng.uniform(0.01, 10.0, K))
+        b0 = int(rng.integers(1, 600))
+        assert binding.static_allocate(X, b0) == oc.static_allocation(X, b0)
+    assert binding.static_allocate([0.813, 0.187], 500) == [813, 187]
+
+
+def test_model_description_is_validated_on_the_host():
+    m = binding.Model(synth.config(1)["spec"])
+    assert m.num_params() == 3072 * 512 + 512 + 512 * 512 + 512 + 512 * 10 + 10 == 1841162
+    assert m.padded_params() % 256 == 0 and 0 <= m.padded_params() - m.num_params() < 256
+    assert m.workspace_bytes(256, 4) > 0
+    assert m.workspace_bytes(0, 4) == 0
+    assert binding.Model(synth.config(4)["spec"]).num_params() == 54440936
+    bad = synth.mlp_spec([8, 4, 3], "f32")
+    bad["layers"][1]["in"] = 5
+    with pytest.raises(binding.DynbError):
+        binding.Model(bad)
+    bad = synth.mlp_spec([8, 4, 3], "f32")
+    bad["classes"] = 7
+    with pytest.raises(binding.DynbError):
+        binding.Model(bad)
+    # calls on an unbound model are refused before anything touches the GPU
+    with pytest.raises(binding.DynbError) as e:
+        binding.forward_backward(m, 256, 256, [1], 256)
+    assert e.value.code == -4
+
+
+def test_streaming_calls_validate_arguments_without_a_gpu():
+    for args in ((0, [1, 1], 8, 256), (256, [1, 1], 8, 0), (256, [0, 0], 8, 256),
+                 (256, [1, -1], 8, 256), (256, [1, 1], 6, 256), (257, [1, 1], 8, 256)):
+        with pytest.raises(binding.DynbError):
+            binding.weighted_aggregate(args[0], args[1], args[2], args[3])
+    with pytest.raises(binding.DynbError):
+        binding.sgd_update(0, 256, 8, 0.1)
+    with pytest.raises(binding.DynbError):
+        binding.sgd_momentum_update(256, 0, 256, 8, 0.1, 0.9)
