@@ -1,0 +1,183 @@
+#!/usr/bin/env python3
+"""Throughput of the dynamic-batching hot path on one MI355X.
+
+A step is one pass of the whole path over one global batch: per-worker forward/backward on
+the ragged split b[K], weighted aggregation, SGD update (with the 16-bit weight refresh), and
+the host controller that resizes b[K] from the synthetic iteration times.  Inputs are resident
+in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps 20] [--warmup 3] [--workload 4] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK = {"mfma_bf16": 2500.0, "fp32": 157.3, "hbm": 8000.0}   # TFLOP/s, TFLOP/s, GB/s
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", type=int, default=4)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build runs on one GPU only (K workers are simulated on it); "
+                 "--gpus must be 1")
+
+    import numpy as np
+    import torch
+    from paper_2305_12213_amd import binding, synth
+
+    binding.load()
+    torch.cuda.set_device(0)
+    cfg = synth.config(args.workload)
+    spec, seed = cfg["spec"], synth.BASE_SEED + cfg["index"]
+    G, K = cfg["global_batch"], cfg["K"]
+    n_batches = args.warmup + args.steps
+
+    model = binding.Model(spec)
+    P, Pp = model.num_params(), model.padded_params()
+    params = torch.from_numpy(synth.flatten_params(synth.init_params(spec, cfg["init"], seed), 256)).cuda()
+    nbytes = model.workspace_bytes(G, K)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    model.bind(params, ws, nbytes, G, K)
+    grads = torch.empty(K, Pp, device="cuda")
+    out = torch.empty(Pp, device="cuda")
+    velocity = torch.zeros(Pp, device="cuda") if cfg["momentum"] else None
+    xs, ys = [], []
+    for s in range(n_batches):          # a fresh global batch per step, resident in HBM
+        x, y = synth.make_batch(spec, cfg["x_dist"], G, seed, s)
+        xs.append(torch.from_numpy(x).cuda()); ys.append(torch.from_numpy(y).cuda())
+    torch.cuda.synchronize()
+
+    state = {"b": list(cfg["b0"]), "step": 0, "trace": []}
+
+    def one_step():
+        s = state["step"]
+        b = state["b"]
+        binding.forward_backward(model, xs[s % n_batches], ys[s % n_batches], b, grads)
+        binding.weighted_aggregate(grads, b, Pp, out)
+        binding.model_sgd_update(model, out, cfg["lr"], cfg["momentum"], velocity)
+        t = synth.iteration_times(b, cfg["speeds"])
+        state["b"] = binding.controller_step(t, b, G, cfg["gains"])
+        state["trace"].append(b)
+        state["step"] = s + 1
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+    timed_splits = state["trace"][args.warmup:]
+
+    # per-kernel-class durations: the same steps again with HIP events around every launch
+    binding.profile_reset()
+    binding.profile_enable(True)
+    state["step"] = args.warmup
+    state["b"] = timed_splits[0]
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    prof = binding.profile_read()
+    binding.profile_enable(False)
+    kernels = {}
+    for name, v in prof.items():
+        if v["launches"]:
+            kernels[name] = {"ms_per_step": v["ms"] / args.steps,
+                             "launches_per_step": v["launches"] / args.steps,
+                             "avg_launch_ms": v["ms"] / v["launches"],
+                             "tflops": v["flops"] / v["ms"] / 1e9 if v["ms"] else 0.0,
+                             "gbps": v["bytes"] / v["ms"] / 1e6 if v["ms"] else 0.0}
+    dominant = max(kernels, key=lambda n: kernels[n]["ms_per_step"])
+    bf = spec["dtype"] == "bf16"
+    if dominant.startswith("gemm") and dominant != "gemm_wgrad":
+        peak = PEAK["mfma_bf16"] if bf else PEAK["fp32"]
+        roofline = {"kernel": dominant, "bound": "mfma" if bf else "alu",
+                    "achieved": kernels[dominant]["tflops"], "peak": peak, "unit": "TFLOP/s",
+                    "frac": kernels[dominant]["tflops"] / peak, "traffic": None}
+    else:
+        # the per-worker weight gradient writes K*P floats, aggregation and update are pure streams
+        roofline = {"kernel": dominant, "bound": "hbm", "achieved": kernels[dominant]["gbps"],
+                    "peak": PEAK["hbm"], "unit": "GB/s",
+                    "frac": kernels[dominant]["gbps"] / PEAK["hbm"], "traffic": None}
+    roofline["avg_launch_ms"] = kernels[dominant]["avg_launch_ms"]
+
+    result = {
+        "metric": "samples/s fwd+bwd+weighted-agg+update at ragged K-way b_k",
+        "value": G * args.steps / elapsed, "unit": "samples/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if bf else "f32", "data": "synthetic",
+        "config": {"workload": "configs[%d]: %s" % (cfg["index"], cfg["name"]), "global_batch": G,
+                   "workers": K, "b_timed_first": timed_splits[0], "b_timed_last": timed_splits[-1],
+                   "params": P},
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, timed_splits[-1])
+    print(json.dumps(result))
+
+
+def cpu_baseline(cfg, b):
+    """The CPU checker, as it stands, on a bounded sample of the same workload."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+    from oracle import network as on
+    from paper_2305_12213_amd import synth
+
+    spec, seed = cfg["spec"], synth.BASE_SEED + cfg["index"]
+    G = cfg["global_batch"]
+    bf = spec["dtype"] == "bf16"
+    params = synth.init_params(spec, cfg["init"], seed)
+    x, y = synth.make_batch(spec, cfg["x_dist"], G, seed, 0)
+
+    def step(bs, xs, ys):
+        t0 = time.perf_counter()
+        _, gk = on.worker_gradients(spec, params, xs, ys, bs, emulate_bf16=bf)
+        agg = on.weighted_aggregate(gk, bs)
+        on.sgd_update(params, agg, cfg["lr"])
+        return time.perf_counter() - t0
+
+    # calibrate on the smallest workers, then take as many whole workers (largest last) as fit ~20 s
+    order = sorted(range(len(b)), key=lambda k: b[k])
+    small = [k for k in order if b[k] > 0][:max(1, len(b) // 2)]
+    off = np.concatenate([[0], np.cumsum(b)])
+    def rows(ks):
+        idx = np.concatenate([np.arange(off[k], off[k + 1]) for k in ks]) if ks else np.arange(0)
+        return x[idx], y[idx]
+    xs, ys = rows(small)
+    dt = step([b[k] for k in small], xs, ys)
+    per_sample = dt / max(1, sum(b[k] for k in small))
+    budget, chosen, used = 20.0, [], 0.0
+    for k in order:
+        if b[k] == 0:
+            continue
+        cost = per_sample * b[k]
+        if chosen and used + cost > budget:
+            break
+        chosen.append(k); used += cost
+    xs, ys = rows(chosen)
+    bs = [b[k] for k in chosen]
+    dt = step(bs, xs, ys)
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    return {"value": sum(bs) / dt, "unit": "samples/s", "cores": threads, "kind": "oracle",
+            "sample": "one step (per-worker fwd+bwd, aggregate, update) over workers %s of the "
+                      "timed split, %d of %d samples, %.1f s" % (sorted(chosen), sum(bs), G, dt)}
+
+
+if __name__ == "__main__":
+    main()

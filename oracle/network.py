@@ -136,11 +136,63 @@ def forward(spec, params, x, emulate_bf16=False):
     return a, stored
 
 
-def loss_and_gradient(spec, params, x, y, emulate_bf16=False):
+def ambiguous_relu_units(spec, params, x, emulate_bf16=False, band=8.0):
+    """ReLU units whose 0/1 derivative two correct implementations may decide differently.
+
+    relu'(z) is a decision on a computed number.  An fp32 accumulation of K products a_j w_j
+    is uncertain by about 2^-24 sqrt(K) sqrt(sum_j a_j^2 w_j^2) (one "noise unit"); `band`
+    noise units are taken as the uncertainty dz of a first-layer pre-activation.  A stored
+    activation can then differ between implementations by da = q(relu(z+dz)) - q(relu(z-dz)),
+    where q is the storage rounding (bfloat16 when emulated: one unit in the last place
+    whenever a rounding boundary lies inside the interval); the next layer's uncertainty is
+    dz' = band * noise' + da @ |W'|, and so on.  A unit is ambiguous when |z| <= dz.
+
+    Returns {layer index: boolean array shaped like that layer's output}.  Everything outside
+    these sets is decided identically by any implementation within the noise model.
+    """
+    P = _f64_params(params, emulate_bf16)
+    a = _q(np.asarray(x, np.float64), emulate_bf16)
+    da = np.zeros_like(a)
+    n = a.shape[0]
+    out, pi = {}, 0
+    n_layers = len(spec["layers"])
+    for li, L in enumerate(spec["layers"]):
+        if L["kind"] == "dense":
+            W, b = P[pi]; pi += 1
+            a2, da2 = a.reshape(n, -1), da.reshape(n, -1)
+            z = a2 @ W + b
+            noise = np.sqrt((a2 * a2) @ (W * W)) * np.sqrt(W.shape[0])
+            dz = band * 2.0 ** -24 * noise + da2 @ np.abs(W)
+        elif L["kind"] == "conv3x3":
+            W, b = P[pi]; pi += 1
+            z = conv3x3_forward(a, W, b, L["stride"])
+            noise = np.sqrt(conv3x3_forward(a * a, W * W, 0.0, L["stride"])) * np.sqrt(9 * W.shape[2])
+            dz = band * 2.0 ** -24 * noise + conv3x3_forward(da, np.abs(W), 0.0, L["stride"])
+        else:                                   # global average pool
+            z = a.mean(axis=(1, 2))
+            dz = da.mean(axis=(1, 2)) + 2.0 ** -22 * np.abs(z)
+        lo, hi = z - dz, z + dz
+        if L.get("relu"):
+            out[li] = np.abs(z) <= dz
+            z, lo, hi = np.maximum(z, 0.0), np.maximum(lo, 0.0), np.maximum(hi, 0.0)
+        if li == n_layers - 1:
+            break
+        a = _q(z, emulate_bf16)
+        da = _q(hi, emulate_bf16) - _q(lo, emulate_bf16)
+    return out
+
+
+def loss_and_gradient(spec, params, x, y, emulate_bf16=False, relu_masks=None, trace=None):
     """Mean loss over the given samples and its gradient as [(dW, dbias)].
 
     This is grad f(x_{b_k,t}) for one worker when (x, y) is that worker's
     mini-batch.  An empty mini-batch yields loss 0 and a zero gradient.
+
+    relu_masks ({layer index: boolean array}) replaces the derivative decision
+    "stored output > 0" of those layers (used to evaluate the gradient under another
+    admissible decision of ambiguous units).  If `trace` is a dict, trace[layer index] =
+    (layer input, gradient arriving at the layer output before the ReLU mask) is recorded
+    for every ReLU layer.
     """
     n = int(np.shape(x)[0])
     if n == 0:
@@ -157,7 +209,10 @@ def loss_and_gradient(spec, params, x, y, emulate_bf16=False):
         L = spec["layers"][li]
         a_in, a_out = stored[li], stored[li + 1]
         if L.get("relu"):
-            da = da * (a_out > 0.0)           # relu'(0) = 0; exact, needs no re-rounding
+            if trace is not None:
+                trace[li] = (a_in, da)
+            mask = (a_out > 0.0) if relu_masks is None or li not in relu_masks else relu_masks[li]
+            da = da * mask                    # relu'(0) = 0; exact, needs no re-rounding
         need_dx = li > first_param_layer
         if L["kind"] == "dense":
             pi -= 1
@@ -177,6 +232,12 @@ def loss_and_gradient(spec, params, x, y, emulate_bf16=False):
             _, H, Wd, _ = a_in.shape
             da = _q(np.broadcast_to(da[:, None, None, :] / (H * Wd), a_in.shape), emulate_bf16)
     return loss, grads
+
+
+def relu_masks_of(spec, params, x, emulate_bf16=False):
+    """{layer index: stored output > 0} for every ReLU layer (the checker's own decisions)."""
+    _, stored = forward(spec, params, x, emulate_bf16)
+    return {li: stored[li + 1] > 0.0 for li, L in enumerate(spec["layers"]) if L.get("relu")}
 
 
 def worker_gradients(spec, params, x, y, b, emulate_bf16=False):

@@ -26,6 +26,22 @@ def worst_relerr(flat_got, spec, ref_params):
     return worst
 
 
+def worker_grads_as_lists(spec, g_host, P):
+    """Rows of the device gradient matrix [K][P_pad] as per-worker [(dW, db)] lists."""
+    return [synth.unflatten_params(spec, g_host[k, :P]) for k in range(g_host.shape[0])]
+
+
+def worst_pair_relerr(got_list, ref_list):
+    worst = 0.0
+    for (gW, gb), (rW, rb) in zip(got_list, ref_list):
+        worst = max(worst, relerr(gW, rW))
+        if np.max(np.abs(rb)) > 0:
+            worst = max(worst, relerr(gb, rb))
+        else:
+            assert np.max(np.abs(gb)) < 1e-30
+    return worst
+
+
 class GpuRun:
     def __init__(self, spec, params_list, max_batch, max_workers):
         import torch
@@ -58,6 +74,13 @@ class GpuRun:
     def aggregate(self, b):
         binding.weighted_aggregate(self.grads, b, self.Pp, self.out)
         return self.out
+
+    def set_velocity(self, vel_list):
+        v = self.torch.from_numpy(synth.flatten_params(vel_list, 256)).cuda()
+        if self.velocity is None:
+            self.velocity = v
+        else:
+            self.velocity.copy_(v)
 
     def update(self, lr, mu=0.0):
         if mu:

@@ -1,9 +1,12 @@
 """GPU parity: the HIP path (through the C interface) against the CPU checker, element by
 element on the same seeded inputs.
 
-Tolerances (max-abs-normalised per tensor): fp32 1e-4; bf16 2e-2 against the exact float64
-computation.  Against the checker with bf16 rounding emulated at the same points the bf16 path
-only differs by fp32-vs-fp64 accumulation and an occasional flipped rounding: 4e-3.
+Tolerances (max-abs-normalised per tensor, max|got - ref| / max|ref|): fp32 1e-4; bf16 2e-2.
+The bf16 reference is the checker with bfloat16 rounding emulated at the points where the kernels
+store 16-bit values; against it the kernels differ only by fp32-vs-fp64 accumulation and a
+stored value that rounds the other way now and then, so the tests hold them to 4e-3.
+ReLU derivative decisions on units inside the rounding band are resolved as tests/relu_ties.py
+describes; all other decisions are the checker's.
 """
 import numpy as np
 import pytest
@@ -11,7 +14,8 @@ import pytest
 from oracle import controller as oc
 from oracle import network as on
 from paper_2305_12213_amd import binding, synth
-from gpu_harness import GpuRun, relerr, worst_relerr
+from gpu_harness import GpuRun, relerr, worker_grads_as_lists, worst_pair_relerr, worst_relerr
+from relu_ties import resolved_worker_references
 
 pytestmark = pytest.mark.gpu
 
@@ -23,21 +27,23 @@ def check_worker_gradients(spec, params, x, y, b, run=None, label=""):
     run = run or GpuRun(spec, params, max(1, sum(b)), len(b))
     g = run.forward_backward(x, y, b).cpu().numpy()
     bf = spec["dtype"] == "bf16"
-    losses, ref = on.worker_gradients(spec, params, x, y, b, emulate_bf16=False)
+    got = worker_grads_as_lists(spec, g, run.P)
+    refs, losses, n_amb, n_flip = resolved_worker_references(spec, params, x, y, b, got, bf)
     got_losses = run.losses(len(b))
+    tol = TOL_EMULATED if bf else TOL["f32"]
     for k in range(len(b)):
-        e = worst_relerr(g[k, :run.P], spec, ref[k])
-        assert e < TOL[spec["dtype"]], (label, "worker", k, b[k], e)
-        assert abs(got_losses[k] - losses[k]) <= (2e-2 if bf else 1e-4) * max(1.0, abs(losses[k]))
+        e = worst_pair_relerr(got[k], refs[k])
+        assert e < tol, (label, "worker", k, b[k], e, n_amb, n_flip)
+        assert abs(got_losses[k] - losses[k]) <= (4e-3 if bf else 1e-5) * max(1.0, abs(losses[k]))
         assert np.all(g[k, run.P:] == 0.0)
         if b[k] == 0:
             assert np.all(g[k] == 0.0)
-    if bf:
-        _, ref_e = on.worker_gradients(spec, params, x, y, b, emulate_bf16=True)
+    if bf and not any(L.get("relu") for L in spec["layers"]):
+        # no 0/1 decisions: the exact float64 computation is a fair reference at 2e-2
+        _, exact = on.worker_gradients(spec, params, x, y, b)
         for k in range(len(b)):
-            e = worst_relerr(g[k, :run.P], spec, ref_e[k])
-            assert e < TOL_EMULATED, (label, "emulated, worker", k, b[k], e)
-    return run, g, ref
+            assert worst_pair_relerr(got[k], exact[k]) < TOL["bf16"]
+    return run, g, refs
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -138,69 +144,105 @@ def test_split_invariance_on_the_gpu():
     for b in ([60, 60], [1, 119], [17, 0, 3, 100], [15] * 8):
         run.forward_backward(x, y, b)
         got = run.aggregate(b).cpu().numpy()
+        # rows keep their position relative to an 8-row boundary only by chance, so the fp32
+        # summation order of a row's products may differ between splits: 1e-5, not equality
         assert relerr(got, whole) < 1e-5, b
 
 
-def run_workload(ci, steps, teacher_forced_every=1):
-    """Runs `steps` training steps of workload ci on the GPU and on the checker.
+def run_workload(ci, steps):
+    """Runs `steps` training steps of workload ci, every step on both sides from the same state.
 
-    The two trajectories run independently (each from its own parameters); in addition, at every
-    `teacher_forced_every`-th step the checker recomputes that step's gradients from the GPU's
-    current parameters, so that per-step kernels are compared without accumulated drift.
+    The checker owns the trajectory (fp32 master parameters, like the GPU's): before each step
+    its parameters (and velocity) are copied to the GPU, both sides take the step on the same
+    seeded batch and the same b[K], and every worker's gradient, the aggregate and the updated
+    parameters are compared.  Nothing flows from the GPU into the checker's trajectory: ReLU
+    ties (tests/relu_ties.py) only select which admissible reference a gradient is compared
+    with, the trajectory always continues from the checker's own decisions.
+    Returns the worst errors seen and the final batch sizes.
     """
     cfg = synth.config(ci)
     spec, seed = cfg["spec"], synth.BASE_SEED + ci
     bf = spec["dtype"] == "bf16"
-    p0 = synth.init_params(spec, cfg["init"], seed)
-    run = GpuRun(spec, p0, cfg["global_batch"], cfg["K"])
-    ref_p = [(W.astype(np.float64), b.astype(np.float64)) for W, b in p0]
+    G, K = cfg["global_batch"], cfg["K"]
+    ref_p = synth.init_params(spec, cfg["init"], seed)
     ref_v = on.zeros_like_params(ref_p)
+    run = GpuRun(spec, ref_p, G, K)
     b_gpu = list(cfg["b0"]); b_ref = list(cfg["b0"])
-    worst_tf = 0.0
+    worst_g = worst_agg = worst_p = 0.0
+    amb = flips = 0
     for step in range(steps):
-        x, y = synth.make_batch(spec, cfg["x_dist"], cfg["global_batch"], seed, step)
         assert b_gpu == b_ref
-        g = run.forward_backward(x, y, b_gpu)
-        if step % teacher_forced_every == 0:
-            cur = synth.unflatten_params(spec, run.params.cpu().numpy())
-            _, gk = on.worker_gradients(spec, cur, x, y, b_gpu, emulate_bf16=bf)
-            gh = g.cpu().numpy()
-            for k in range(cfg["K"]):
-                worst_tf = max(worst_tf, worst_relerr(gh[k, :run.P], spec, gk[k]))
-            agg = on.weighted_aggregate(gk, b_gpu)
-            worst_tf = max(worst_tf, worst_relerr(run.aggregate(b_gpu).cpu().numpy()[:run.P], spec, agg))
-        run.aggregate(b_gpu)
+        x, y = synth.make_batch(spec, cfg["x_dist"], G, seed, step)
+        if step:
+            run.set_params(ref_p)
+            if cfg["momentum"]:
+                run.set_velocity(ref_v)
+        g = run.forward_backward(x, y, b_gpu).cpu().numpy()
+        out = run.aggregate(b_gpu).cpu().numpy()
         run.update(cfg["lr"], cfg["momentum"])
-        # the checker's own trajectory
+        got = worker_grads_as_lists(spec, g, run.P)
+        refs, _, a, f = resolved_worker_references(spec, ref_p, x, y, b_ref, got, bf)
+        amb += a; flips += f
+        for k in range(K):
+            worst_g = max(worst_g, worst_pair_relerr(got[k], refs[k]))
+        # the aggregate and the update are compared given the same decisions as the gradients
+        agg_given = on.weighted_aggregate(refs, b_ref)
+        worst_agg = max(worst_agg, worst_relerr(out[:run.P], spec, agg_given))
+        if cfg["momentum"]:
+            p_given, _ = on.momentum_update(ref_p, ref_v, agg_given, cfg["lr"], cfg["momentum"])
+        else:
+            p_given = on.sgd_update(ref_p, agg_given, cfg["lr"])
+        worst_p = max(worst_p, worst_relerr(run.params.cpu().numpy()[:run.P], spec, p_given))
+        # the checker's own step (its own decisions), fp32 master state
         _, gk = on.worker_gradients(spec, ref_p, x, y, b_ref, emulate_bf16=bf)
         agg = on.weighted_aggregate(gk, b_ref)
         if cfg["momentum"]:
-            ref_p, ref_v = on.momentum_update(ref_p, ref_v, agg, cfg["lr"], cfg["momentum"])
+            new_p, ref_v = on.momentum_update(ref_p, ref_v, agg, cfg["lr"], cfg["momentum"])
+            ref_v = [(W.astype(np.float32).astype(np.float64), b.astype(np.float32).astype(np.float64))
+                     for W, b in ref_v]
         else:
-            ref_p = on.sgd_update(ref_p, agg, cfg["lr"])
-        # controller on the synthetic plant, both sides
+            new_p = on.sgd_update(ref_p, agg, cfg["lr"])
+        ref_p = [(W.astype(np.float32), b.astype(np.float32)) for W, b in new_p]
         t = synth.iteration_times(b_gpu, cfg["speeds"])
-        b_gpu = binding.controller_step(t, b_gpu, cfg["global_batch"], cfg["gains"])
-        b_ref = oc.controller_step(t, b_ref, cfg["global_batch"], **cfg["gains"])
-    final = worst_relerr(run.params.cpu().numpy()[:run.P], spec, ref_p)
-    return worst_tf, final, b_gpu
+        b_gpu = binding.controller_step(t, b_gpu, G, cfg["gains"])
+        b_ref = oc.controller_step(t, b_ref, G, **cfg["gains"])
+    print("workload %d: worst grad %.2e agg %.2e params %.2e; ambiguous units %d, decided "
+          "differently %d" % (ci, worst_g, worst_agg, worst_p, amb, flips))
+    return worst_g, worst_agg, worst_p, b_gpu
 
 
 def test_workload0_softmax_regression_10_steps():
-    tf, final, b = run_workload(0, 10)
-    assert tf < 1e-4 and final < 1e-4, (tf, final)
+    g, agg, p, b = run_workload(0, 10)
+    assert max(g, agg, p) < 1e-4, (g, agg, p)
     assert b == [43, 21]
 
 
+def test_workload0_free_running_trajectories_agree():
+    # no ReLU, hence no 0/1 decisions: two independent 10-step runs stay within tolerance
+    cfg = synth.config(0)
+    spec, seed = cfg["spec"], synth.BASE_SEED
+    p = synth.init_params(spec, cfg["init"], seed)
+    run = GpuRun(spec, p, 64, 2)
+    ref = p
+    b = list(cfg["b0"])
+    for step in range(cfg["steps"]):
+        x, y = synth.make_batch(spec, cfg["x_dist"], 64, seed, step)
+        run.forward_backward(x, y, b); run.aggregate(b); run.update(cfg["lr"])
+        _, gk = on.worker_gradients(spec, ref, x, y, b)
+        ref = on.sgd_update(ref, on.weighted_aggregate(gk, b), cfg["lr"])
+        b = binding.controller_step(synth.iteration_times(b, cfg["speeds"]), b, 64, cfg["gains"])
+    assert worst_relerr(run.params.cpu().numpy()[:run.P], spec, ref) < 1e-4
+
+
 def test_workload1_mlp_fp32_50_steps():
-    tf, final, b = run_workload(1, 50, teacher_forced_every=5)
-    assert tf < 1e-4 and final < 1e-4, (tf, final)
+    g, agg, p, b = run_workload(1, 50)
+    assert max(g, agg, p) < 1e-4, (g, agg, p)
     assert sum(b) == 256
 
 
 def test_workload2_mlp_bf16_momentum_100_steps():
-    tf, final, b = run_workload(2, 100, teacher_forced_every=20)
-    assert tf < TOL_EMULATED and final < 2e-2, (tf, final)
+    g, agg, p, b = run_workload(2, 100)
+    assert max(g, agg) < TOL_EMULATED and p < 1e-4, (g, agg, p)
     assert sum(b) == 1024
 
 
@@ -211,25 +253,32 @@ def test_workload4_wide_mlp_full_size_step():
     spec, seed = cfg["spec"], synth.BASE_SEED + 4
     p0 = synth.init_params(spec, cfg["init"], seed)
     G, K = cfg["global_batch"], cfg["K"]
-    b = list(cfg["b0"])
-    b = binding.controller_step(synth.iteration_times(b, cfg["speeds"]), b, G, cfg["gains"])
-    assert b == oc.controller_step(synth.iteration_times(cfg["b0"], cfg["speeds"]), cfg["b0"], G,
-                                   **cfg["gains"])
+    b, b_ref = list(cfg["b0"]), list(cfg["b0"])
+    for _ in range(3):       # the bounds clip the first raw step; the second adjustment converges
+        b = binding.controller_step(synth.iteration_times(b, cfg["speeds"]), b, G, cfg["gains"])
+        b_ref = oc.controller_step(synth.iteration_times(b_ref, cfg["speeds"]), b_ref, G, **cfg["gains"])
+    assert b == b_ref
     assert min(b) <= 8 and max(b) > 1000                   # the ragged split, 5 ... 1265
     x, y = synth.make_batch(spec, cfg["x_dist"], G, seed, 0)
     run = GpuRun(spec, p0, G, K)
     g = run.forward_backward(x, y, b)
-    agg_ref = None
-    off = 0
+    out = run.aggregate(b).cpu().numpy()
+    run.update(cfg["lr"])
+    new_params = run.params.cpu().numpy()
+    agg_ref, off, amb, flips = None, 0, 0, 0
+    from relu_ties import resolved_reference
     for k in range(K):
-        _, gk = on.loss_and_gradient(spec, p0, x[off:off + b[k]], y[off:off + b[k]], emulate_bf16=True)
-        e = worst_relerr(g[k, :run.P].cpu().numpy(), spec, gk)
+        got = synth.unflatten_params(spec, g[k, :run.P].cpu().numpy())
+        ref, _, a, f = resolved_reference(spec, p0, x[off:off + b[k]], y[off:off + b[k]], got, True)
+        amb += a; flips += f
+        e = worst_pair_relerr(got, ref)
+        print("worker %2d b=%4d err %.2e (ambiguous %d, decided differently %d)" % (k, b[k], e, a, f),
+              flush=True)
         assert e < TOL_EMULATED, (k, b[k], e)
         lam = b[k] / G
-        agg_ref = [(lam * dW, lam * db) for dW, db in gk] if agg_ref is None else \
-            [(aW + lam * dW, ab + lam * db) for (aW, ab), (dW, db) in zip(agg_ref, gk)]
+        agg_ref = [(lam * dW, lam * db) for dW, db in ref] if agg_ref is None else \
+            [(aW + lam * dW, ab + lam * db) for (aW, ab), (dW, db) in zip(agg_ref, ref)]
         off += b[k]
-    assert worst_relerr(run.aggregate(b).cpu().numpy()[:run.P], spec, agg_ref) < TOL_EMULATED
-    run.update(cfg["lr"])
+    assert worst_relerr(out[:run.P], spec, agg_ref) < TOL_EMULATED
     ref_p = on.sgd_update(p0, agg_ref, cfg["lr"])
-    assert worst_relerr(run.params.cpu().numpy()[:run.P], spec, ref_p) < 1e-4
+    assert worst_relerr(new_params[:run.P], spec, ref_p) < 1e-4

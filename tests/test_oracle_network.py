@@ -235,3 +235,61 @@ def test_bf16_emulation_stays_close_to_the_exact_gradient():
     _, ge = on.loss_and_gradient(spec, params, x, y, emulate_bf16=True)
     for (a, _), (e, _) in zip(g, ge):
         assert np.max(np.abs(a - e)) / np.max(np.abs(a)) < 2e-2
+
+
+def test_ambiguous_units_are_exactly_the_near_ties():
+    spec = synth.mlp_spec([4, 3, 2], "f32")
+    W1 = np.array([[1.0, 1.0, 1.0], [1.0, -1.0, 0.5], [0.0, 0.0, 0.0], [0.0, 0.0, 0.0]])
+    params = [(W1, np.zeros(3)), (np.ones((3, 2)), np.zeros(2))]
+    x = np.array([[1.0, 1.0, 0, 0],            # unit 1: z = 0 exactly
+                  [1.0, 1.0 - 1e-7, 0, 0],      # unit 1: z = 1e-7, inside the noise band
+                  [1.0, 1.0 - 1e-3, 0, 0],      # unit 1: z = 1e-3, far outside
+                  [1.0, 0.5, 0, 0]])
+    amb = on.ambiguous_relu_units(spec, params, x)
+    assert list(amb) == [0]
+    np.testing.assert_array_equal(amb[0], [[0, 1, 0], [0, 1, 0], [0, 0, 0], [0, 0, 0]])
+
+
+def test_bf16_rounding_boundaries_widen_the_next_layers_band():
+    # layer-1 output 1 + 2^-8 sits exactly on a bfloat16 rounding boundary: the stored value
+    # may be 1 or 1 + 2^-7, so a layer-2 unit with |z| below 2^-7 |w| is ambiguous -- but only
+    # when rounding is emulated
+    spec = synth.mlp_spec([1, 1, 1, 1], "bf16")
+    w2 = 0.5
+    params = [(np.array([[1.0]]), np.zeros(1)), (np.array([[w2]]), np.array([-w2 * (1 + 2.0 ** -8)])),
+              (np.ones((1, 1)), np.zeros(1))]
+    x = np.array([[1.0 + 2.0 ** -8]])
+    params_e = [(W, b) for W, b in params]
+    amb = on.ambiguous_relu_units(spec, params_e, x, emulate_bf16=False)
+    assert not amb[0][0, 0] and amb[1][0, 0]          # exact: z2 = 0 -> tie
+    params_e[1] = (params[1][0], np.array([-w2 * (1 + 2.0 ** -8) + 2.0 ** -10]))
+    assert not on.ambiguous_relu_units(spec, params_e, x, emulate_bf16=False)[1][0, 0]
+    # emulated: x rounds to 1.0 (ties to even) exactly, layer 1 stores 1.0: no ambiguity there;
+    # make layer 1 produce the boundary value through its bias instead
+    params_b = [(np.array([[1.0]]), np.array([2.0 ** -8])), (np.array([[w2]]), np.array([-w2 + 2.0 ** -10])),
+                (np.ones((1, 1)), np.zeros(1))]
+    amb = on.ambiguous_relu_units(spec, params_b, np.array([[1.0]]), emulate_bf16=True)
+    assert amb[1][0, 0]                                 # |z2| ~ 2^-10 < 2^-7 * 0.5
+
+
+def test_forced_relu_masks_change_exactly_the_flipped_units_contribution():
+    spec = tiny_mlp()
+    rng = np.random.default_rng(12)
+    params = rand_params(spec, 4)
+    x = rng.standard_normal((3, 5)); y = rng.integers(0, 3, 3)
+    masks = on.relu_masks_of(spec, params, x)
+    trace = {}
+    _, g0 = on.loss_and_gradient(spec, params, x, y, relu_masks=masks, trace=trace)
+    _, g_plain = on.loss_and_gradient(spec, params, x, y)
+    for (a, b), (c, d) in zip(g0, g_plain):
+        np.testing.assert_array_equal(a, c); np.testing.assert_array_equal(b, d)
+    # flip unit (sample 1, unit 2) of the second hidden layer (layer index 1)
+    m2 = {k: v.copy() for k, v in masks.items()}
+    was_on = m2[1][1, 2]
+    m2[1][1, 2] = not was_on
+    _, g1 = on.loss_and_gradient(spec, params, x, y, relu_masks=m2)
+    a_in, incoming = trace[1]
+    sign = -1.0 if was_on else 1.0
+    want = np.zeros_like(g0[1][0]); want[:, 2] = sign * a_in[1] * incoming[1, 2]
+    np.testing.assert_allclose(g1[1][0] - g0[1][0], want, atol=1e-14)
+    np.testing.assert_allclose(g1[2][0], g0[2][0], atol=0)          # layers above: untouched
