@@ -78,17 +78,19 @@ struct GemmArgs {
   float* Cf; int64_t ldcf;
   const void* mask; int64_t ldmask;
   int64_t group_stride;
+  int groups_per_block;                // WGRAD, bf16 kernel: workers streamed by one workgroup
 };
 
 int launch_gemm(int dtype, const GemmArgs& a, const Segs& s, void* stream);
 
-// x fp32 [rows][D] (dense rows) -> out T [padded rows][ld]; pad rows are written as zero.
-int launch_pack_rows(int dtype, const float* x, int D, void* out, int64_t ld, const Segs& s,
+// x fp32 [rows][D] -> out T [rows][ld]
+int launch_pack_rows(int dtype, const float* x, int rows, int D, void* out, int64_t ld,
                      void* stream);
-// in T [R][ldi] -> out T [C][ldo] (out[c][r] = in[r][c])
-int launch_transpose(int dtype, const void* in, int64_t ldi, int R, int C, void* out, int64_t ldo,
-                     void* stream);
-// logits fp32 [Mp][ldz] -> dz T [Mp][ldd] (pad rows and pad columns zero), rowloss[Mp]
+// in T [rows][ldi] -> out T [C][ldo] over the padded row space: out[c][poff_k + r] =
+// in[off_k + r][c] for r < b_k, zero for the padding positions of each worker's segment
+int launch_transpose(int dtype, const void* in, int64_t ldi, int C, void* out, int64_t ldo,
+                     const Segs& s, void* stream);
+// logits fp32 [rows][ldz] -> dz T [rows][ldd] (pad columns zero), rowloss[rows]
 int launch_softmax_xent(int dtype, const float* logits, int64_t ldz, const int32_t* y, int C,
                         void* dz, int64_t ldd, int ld_cols, float* rowloss, const Segs& s,
                         void* stream);

@@ -13,7 +13,9 @@ namespace {
 
 typedef __bf16 bf16;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 struct GroupView {
   int64_t col0;  // first reduction column of this group
@@ -57,117 +59,344 @@ __device__ inline void store_one(const GemmArgs& p, const GroupView& gv, int i, 
 constexpr int BK = 64;          // reduction elements per stage
 constexpr int GPR = BK / 8;     // 16-byte granules per tile row
 
+// Workgroup -> tile.  Consecutive workgroup ids are spread round-robin over the 8 XCDs, each
+// with its own L2: give every XCD a contiguous chunk of the tile sequence, and walk the tiles
+// in bands of 8 tile-rows so that a chunk covers a compact rectangle (few distinct operand
+// panels per L2).
+__device__ inline void tile_of_block(int pid, int tiles_i, int tiles_j, int& ti, int& tj) {
+  const int total = tiles_i * tiles_j;
+  const int per = total / 8, extra = total % 8, xcd = pid % 8, local = pid / 8;
+  int t = pid;
+  if (total >= 16) t = xcd * per + (xcd < extra ? xcd : extra) + local;
+  const int band = 8;
+  const int bsz = band * tiles_j;
+  const int b0 = t / bsz, r = t % bsz;
+  const int rows = (tiles_i - b0 * band) < band ? (tiles_i - b0 * band) : band;
+  ti = b0 * band + r % rows;
+  tj = r / rows;
+}
+
+// 16 bytes of zeros: lanes whose reduction column lies past a worker's depth fetch this
+// instead of a neighbour's data (an LDS-direct load cannot be predicated to zero).
+__device__ uint4 g_zero_granule[1];
+
+// Asynchronous global -> LDS copy of 64 x 16 bytes: lane l's 16 bytes at `src` land at LDS
+// byte address lds_base + 16*l (lds_base is wave-uniform).  Completion is tracked by vmcnt
+// only; the kernel waits for it explicitly before the barrier that publishes a stage.  It is
+// written as assembly so that the compiler does not order later LDS reads of the *other*
+// stage behind it.
+__device__ inline void async_copy_1k(const void* src, uint32_t lds_base) {
+  const uint32_t base = __builtin_amdgcn_readfirstlane(lds_base);
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(base), "v"(src)
+               : "memory", "m0");
+}
+
+// Position in the stream of 64-deep stages that one workgroup walks: stage `kt` of group `g`.
+// FWD/DGRAD have one group; WGRAD has one group per worker, and a workgroup runs through its
+// workers back to back so that the load pipeline never drains between them.
+struct StageCursor {
+  int g, kt;
+};
+
 template <int BM, int BN, int WM, int WN, int MODE>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Segs segs) {
-  constexpr int NT = WM * WN * 64;
+  constexpr int NW = WM * WN;
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
-  constexpr int LA = BM * GPR / NT, LB = BN * GPR / NT;
-  static_assert(BM * GPR % NT == 0 && BN * GPR % NT == 0, "tile/threads mismatch");
+  constexpr int LA = BM / 8 / NW, LB = BN / 8 / NW;   // 8-row blocks per wave and stage
+  constexpr int SPITCH = 36;                          // floats per row of a staged 32x32 tile
+  static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0 && GPR == 8, "tile/waves mismatch");
 
   __shared__ uint4 sA[2][BM * GPR];
   __shared__ uint4 sB[2][BN * GPR];
+  __shared__ float sStage[MODE == MODE_WGRAD ? NW * 32 * SPITCH : 4];
 
-  const GroupView gv = group_view(p, segs, blockIdx.z);
-  const int i0 = blockIdx.x * BM, j0 = blockIdx.y * BN;
+  // groups (workers) of this workgroup: [g_lo, g_hi)
+  const int g_lo = MODE == MODE_WGRAD ? blockIdx.y * p.groups_per_block : 0;
+  const int g_hi = MODE == MODE_WGRAD
+                       ? (g_lo + p.groups_per_block < segs.K ? g_lo + p.groups_per_block : segs.K)
+                       : 1;
+  int ti, tj;
+  tile_of_block(blockIdx.x, (p.M + BM - 1) / BM, (p.N + BN - 1) / BN, ti, tj);
+  const int i0 = ti * BM, j0 = tj * BN;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave % WM, wn = wave / WM;
 
-  const bf16* A = (const bf16*)p.A + gv.col0;
-  const bf16* B = (const bf16*)p.B + gv.col0;
-
-  uint4 ra[LA], rb[LB];
-  auto gload = [&](int k0) {
-#pragma unroll
-    for (int u = 0; u < LA; ++u) {
-      const int idx = tid + u * NT, row = idx / GPR, gr = idx % GPR;
-      const int i = i0 + row, k = k0 + gr * 8;
-      ra[u] = (i < p.M && k < gv.depth) ? *(const uint4*)(A + (int64_t)i * p.lda + k)
-                                        : make_uint4(0, 0, 0, 0);
-    }
-#pragma unroll
-    for (int u = 0; u < LB; ++u) {
-      const int idx = tid + u * NT, row = idx / GPR, gr = idx % GPR;
-      const int j = j0 + row, k = k0 + gr * 8;
-      rb[u] = (j < p.N && k < gv.depth) ? *(const uint4*)(B + (int64_t)j * p.ldb + k)
-                                        : make_uint4(0, 0, 0, 0);
+  auto depth_of = [&](int g) { return MODE == MODE_WGRAD ? segs.poff[g + 1] - segs.poff[g] : p.K; };
+  auto stages_of = [&](int g) { return (depth_of(g) + BK - 1) / BK; };
+  auto settle = [&](StageCursor& c) {   // first stage at or after c; skips groups without rows
+    while (c.g < g_hi && c.kt >= stages_of(c.g)) {
+      ++c.g;
+      c.kt = 0;
     }
   };
-  auto lstore = [&](int buf) {
+
+  // global -> LDS, asynchronously and without registers: one instruction moves 8 rows x 128
+  // bytes; lane l lands at LDS slot l of the block, i.e. row l/8, physical granule l%8, which
+  // holds logical granule (l%8) ^ (row & 7).  Rows past the matrix edge are clamped (their
+  // products are never stored).  Reduction columns past a worker's depth fetch zeros.
+  const int lrow = lane >> 3, lgran = (lane & 7) ^ (lane >> 3);
+  const char* Ab = (const char*)p.A;
+  const char* Bb = (const char*)p.B;
+  uint32_t offA[LA], offB[LB];
+#pragma unroll
+  for (int u = 0; u < LA; ++u) {
+    int i = i0 + (wave + NW * u) * 8 + lrow;
+    i = i < p.M ? i : p.M - 1;
+    offA[u] = (uint32_t)(((int64_t)i * p.lda + lgran * 8) * 2);
+  }
+#pragma unroll
+  for (int u = 0; u < LB; ++u) {
+    int j = j0 + (wave + NW * u) * 8 + lrow;
+    j = j < p.N ? j : p.N - 1;
+    offB[u] = (uint32_t)(((int64_t)j * p.ldb + lgran * 8) * 2);
+  }
+  const uint32_t ldsA = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)&sA[0][0];
+  const uint32_t ldsB = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)&sB[0][0];
+  auto issue = [&](int buf, const StageCursor& c) {
+    const int k0 = c.kt * BK;
+    bool live = true;
+    uint32_t kbyte = (uint32_t)k0 * 2;
+    if (MODE == MODE_WGRAD) {
+      live = k0 + lgran * 8 < depth_of(c.g);
+      kbyte += (uint32_t)segs.poff[c.g] * 2;
+    }
 #pragma unroll
     for (int u = 0; u < LA; ++u) {
-      const int idx = tid + u * NT, row = idx / GPR, gr = idx % GPR;
-      sA[buf][row * GPR + (gr ^ (row & 7))] = ra[u];
+      const void* src = live ? (const void*)(Ab + offA[u] + kbyte) : (const void*)g_zero_granule;
+      async_copy_1k(src, ldsA + (uint32_t)((buf * BM * GPR + (wave + NW * u) * 64) * 16));
     }
 #pragma unroll
     for (int u = 0; u < LB; ++u) {
-      const int idx = tid + u * NT, row = idx / GPR, gr = idx % GPR;
-      sB[buf][row * GPR + (gr ^ (row & 7))] = rb[u];
+      const void* src = live ? (const void*)(Bb + offB[u] + kbyte) : (const void*)g_zero_granule;
+      async_copy_1k(src, ldsB + (uint32_t)((buf * BN * GPR + (wave + NW * u) * 64) * 16));
     }
+  };
+
+  // LDS -> MFMA fragments: lane reads row (lane & 31) of a 32-row block, granule 2*kk + lane/32
+  const int frow_a = (wm * (BM / WM) + (lane & 31)) * GPR;
+  const int frow_b = (wn * (BN / WN) + (lane & 31)) * GPR;
+  const int fsw = lane & 7, fhi = lane >> 5;
+  bf16x8 fa[2][TM], fb[2][TN];   // two register sets, alternating per k-step
+  auto lfrag = [&](const uint4* sa, const uint4* sb, int kk, int set) {
+    const int g = (kk * 2 + fhi) ^ fsw;
+#pragma unroll
+    for (int a = 0; a < TM; ++a) fa[set][a] = *(const bf16x8*)&sa[frow_a + a * 32 * GPR + g];
+#pragma unroll
+    for (int b = 0; b < TN; ++b) fb[set][b] = *(const bf16x8*)&sb[frow_b + b * 32 * GPR + g];
   };
 
   f32x16 acc[TM][TN];
+  auto clear_acc = [&]() {
 #pragma unroll
-  for (int a = 0; a < TM; ++a)
+    for (int a = 0; a < TM; ++a)
 #pragma unroll
-    for (int b = 0; b < TN; ++b)
+      for (int b = 0; b < TN; ++b)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+        for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+  };
+  clear_acc();
+  auto mma = [&](int set) {
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+      for (int b = 0; b < TN; ++b)
+        // The MFMA's first operand indexes the 4-consecutive-per-lane dimension of the result.
+        // Weight gradients are stored [j][i] with i contiguous; forward / activation-gradient
+        // results are stored [i][j] with j contiguous: feed the operands accordingly.
+        if (MODE == MODE_WGRAD)
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][a], fb[set][b], acc[a][b], 0, 0, 0);
+        else
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][b], fa[set][a], acc[a][b], 0, 0, 0);
+  };
 
-  const int nk = (gv.depth + BK - 1) / BK;
-  if (nk > 0) {
-    gload(0);
-    lstore(0);
-  }
-  __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < nk) gload((kt + 1) * BK);
+  // Accumulator element v of lane l sits at (8*(v/4) + 4*(l/32) + v%4, l%32) of its 32x32 tile,
+  // first coordinate = the first MFMA operand's row: each lane owns runs of 4 consecutive
+  // elements along the output's contiguous dimension.
+  const int hi4 = 4 * (lane >> 5), l31 = lane & 31;
+
+  // Weight-gradient tile of worker g -> grads[g].  Each wave passes its 32x32 sub-tiles through
+  // a private LDS patch so that one store instruction writes 8 rows x 128 contiguous bytes
+  // (whole lines) instead of 32 rows x 32 bytes: these stores are the largest HBM stream of a
+  // step.  LDS operations of one wave execute in order, so the patch needs no barrier.
+  auto store_wgrad = [&](int g) {
+    float* Cg = p.Cf + (int64_t)g * p.group_stride;
+    float* patch = &sStage[wave * 32 * SPITCH];
+    const bool vec_ok = (p.ldcf & 3) == 0 && (((uintptr_t)Cg) & 15) == 0;
+    const int rr = lane >> 3, rc = (lane & 7) * 4;
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 fa[TM], fb[TN];
-      const int gr = kk * 2 + (lane >> 5);
-#pragma unroll
-      for (int a = 0; a < TM; ++a) {
-        const int row = wm * (BM / WM) + a * 32 + (lane & 31);
-        fa[a] = *(const bf16x8*)&sA[buf][row * GPR + (gr ^ (row & 7))];
-      }
+    for (int a = 0; a < TM; ++a)
 #pragma unroll
       for (int b = 0; b < TN; ++b) {
-        const int row = wn * (BN / WN) + b * 32 + (lane & 31);
-        fb[b] = *(const bf16x8*)&sB[buf][row * GPR + (gr ^ (row & 7))];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const f32x4 o = {acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2],
+                           acc[a][b][4 * q + 3]};
+          *(f32x4*)&patch[l31 * SPITCH + 8 * q + hi4] = o;
+        }
+        __builtin_amdgcn_wave_barrier();
+        const int ib = i0 + wm * (BM / WM) + a * 32 + rc;
+        const int jb = j0 + wn * (BN / WN) + b * 32 + rr;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const f32x4 o = *(const f32x4*)&patch[(rr + 8 * t) * SPITCH + rc];
+          const int j = jb + 8 * t;
+          if (j < p.N) {
+            float* dst = Cg + (int64_t)j * p.ldcf + ib;
+            if (vec_ok && ib + 3 < p.M) {
+              __builtin_nontemporal_store(o, (f32x4*)dst);
+            } else {
+#pragma unroll
+              for (int r = 0; r < 4; ++r)
+                if (ib + r < p.M) dst[r] = o[r];
+            }
+          }
+        }
+        __builtin_amdgcn_wave_barrier();
       }
-#pragma unroll
-      for (int a = 0; a < TM; ++a)
-#pragma unroll
-        for (int b = 0; b < TN; ++b)
-          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+  };
+
+  // A worker without rows contributes a zero tile (not unrolled: it is rare and tiny).
+  auto store_zero = [&](int g) {
+    float* Cg = p.Cf + (int64_t)g * p.group_stride;
+    const bool vec_ok = (p.ldcf & 3) == 0 && (((uintptr_t)Cg) & 15) == 0;
+    const int rr = lane >> 3, rc = (lane & 7) * 4;
+#pragma unroll 1
+    for (int t = 0; t < TM * TN * 4; ++t) {
+      const int a = t / (TN * 4), b = (t / 4) % TN;
+      const int ib = i0 + wm * (BM / WM) + a * 32 + rc;
+      const int j = j0 + wn * (BN / WN) + b * 32 + rr + 8 * (t % 4);
+      if (j >= p.N) continue;
+      float* dst = Cg + (int64_t)j * p.ldcf + ib;
+      if (vec_ok && ib + 3 < p.M) {
+        const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+        __builtin_nontemporal_store(z, (f32x4*)dst);
+      } else {
+        for (int r = 0; r < 4; ++r)
+          if (ib + r < p.M) dst[r] = 0.f;
+      }
     }
-    if (kt + 1 < nk) lstore(buf ^ 1);
+  };
+
+  // ---- the stage pipeline ----
+  // One 64-deep stage = 4 MFMA k-steps; fragments are fetched one k-step ahead into the
+  // register set the previous group of MFMAs has just released.  After the last fragment fetch
+  // of a stage every wave waits for its own outstanding LDS-direct loads (the other buffer)
+  // and meets the barrier: from there on the other buffer is complete and this one is free,
+  // so the stage after next is issued into it, with a whole stage of MFMAs to land.
+  // sched_barrier(0) keeps the compiler's scheduler from gathering the MFMAs behind the waits.
+  StageCursor ic = {g_lo, 0};   // next stage to issue
+  settle(ic);
+  StageCursor cc = ic;          // stage being computed
+  int stored = g_lo;            // workers whose tile has been written
+  if (MODE == MODE_WGRAD)       // workers without rows in front of the first stage: zero gradient
+    for (; stored < (cc.g < g_hi ? cc.g : g_hi); ++stored) store_zero(stored);
+
+  const bool have0 = ic.g < g_hi;
+  if (have0) {
+    issue(0, ic);
+    ++ic.kt;
+    settle(ic);
+  }
+  const bool have1 = ic.g < g_hi;
+  if (have1) {
+    issue(1, ic);
+    ++ic.kt;
+    settle(ic);
+  }
+  if (have0) {
+    if (have1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LA + LB) : "memory");   // stage 0 landed
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
+    lfrag(sA[0], sB[0], 0, 0);
+  }
+  int buf = 0;
+  while (cc.g < g_hi) {
+    const int g = cc.g, nst = stages_of(g);
+    StageCursor ng = {g + 1, 0};   // first stage of the next worker that has rows
+    settle(ng);
+    const bool later = ng.g < g_hi;
+    for (int kt = 0; kt < nst; ++kt) {   // the hot loop: all stages of worker g
+      const bool more1 = kt + 1 < nst || later;   // a next stage exists (already on its way)
+      const bool more2 = ic.g < g_hi;             // and one after it, to be issued now
+      lfrag(sA[buf], sB[buf], 1, 1);
+      mma(0);
+      __builtin_amdgcn_sched_barrier(0);
+      lfrag(sA[buf], sB[buf], 2, 0);
+      mma(1);
+      __builtin_amdgcn_sched_barrier(0);
+      lfrag(sA[buf], sB[buf], 3, 1);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // my part of the other buffer has landed
+      __syncthreads();
+      __builtin_amdgcn_sched_barrier(0);
+      if (more2) {
+        issue(buf, ic);
+        ++ic.kt;
+        settle(ic);
+      }
+      mma(0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (more1) lfrag(sA[buf ^ 1], sB[buf ^ 1], 0, 0);
+      mma(1);
+      __builtin_amdgcn_sched_barrier(0);
+      buf ^= 1;
+    }
+    if (MODE == MODE_WGRAD) {
+      store_wgrad(g);
+      clear_acc();
+      for (stored = g + 1; stored < (later ? ng.g : g_hi); ++stored) store_zero(stored);
+    }
+    cc = ng;
   }
 
-  // accumulator element v of lane l:  i = 8*(v/4) + 4*(l/32) + v%4,  j = l%32
-  const bool vec_ok = MODE == MODE_WGRAD && (p.ldcf & 3) == 0 && (((uintptr_t)gv.Cf) & 15) == 0;
+  if (MODE != MODE_WGRAD) {
+    const GroupView gv = group_view(p, segs, 0);
+    const bool bias_vec = (((uintptr_t)p.bias) & 15) == 0;   // a layer's bias may start anywhere
 #pragma unroll
-  for (int a = 0; a < TM; ++a)
+    for (int a = 0; a < TM; ++a) {
+      const int i = i0 + wm * (BM / WM) + a * 32 + l31;
+      if (i >= p.M) continue;
 #pragma unroll
-    for (int b = 0; b < TN; ++b) {
-      const int j = j0 + wn * (BN / WN) + b * 32 + (lane & 31);
-      if (j >= p.N) continue;
+      for (int b = 0; b < TN; ++b)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int ib = i0 + wm * (BM / WM) + a * 32 + 8 * q + 4 * (lane >> 5);
-        if (MODE == MODE_WGRAD && vec_ok && ib + 3 < p.M) {
-          float4 o = make_float4(acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2],
-                                 acc[a][b][4 * q + 3]);
-          *(float4*)&gv.Cf[(int64_t)j * p.ldcf + ib] = o;
-        } else {
+        for (int q = 0; q < 4; ++q) {
+          const int jb = j0 + wn * (BN / WN) + b * 32 + 8 * q + hi4;
+          if (jb >= p.N) continue;
+          float v[4] = {acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2],
+                        acc[a][b][4 * q + 3]};
+          if (jb + 3 < p.N) {
+            if (MODE == MODE_FWD) {
+              if (p.bias) {
+                if (bias_vec) {
+                  const float4 bv = *(const float4*)&p.bias[jb];
+                  v[0] += bv.x; v[1] += bv.y; v[2] += bv.z; v[3] += bv.w;
+                } else {
 #pragma unroll
-          for (int r = 0; r < 4; ++r)
-            if (ib + r < p.M) store_one<bf16, MODE>(p, gv, ib + r, j, acc[a][b][4 * q + r]);
+                  for (int r = 0; r < 4; ++r) v[r] += p.bias[jb + r];
+                }
+              }
+              if (p.relu) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) v[r] = fmaxf(v[r], 0.f);
+              }
+              if (p.Cf) *(float4*)&p.Cf[(int64_t)i * p.ldcf + jb] = make_float4(v[0], v[1], v[2], v[3]);
+            } else if (p.mask) {
+              const bf16x4 mk = *(const bf16x4*)((const bf16*)p.mask + (int64_t)i * p.ldmask + jb);
+#pragma unroll
+              for (int r = 0; r < 4; ++r)
+                if (!((float)mk[r] > 0.f)) v[r] = 0.f;
+            }
+            if (p.C) {
+              bf16x4 o = {(bf16)v[0], (bf16)v[1], (bf16)v[2], (bf16)v[3]};
+              *(bf16x4*)((bf16*)p.C + (int64_t)i * p.ldc + jb) = o;
+            }
+          } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+              if (jb + r < p.N) store_one<bf16, MODE>(p, gv, i, jb + r, v[r]);
+          }
         }
-      }
     }
+  }
 }
 
 // ------------------------------------------------------------------------------------
@@ -223,8 +452,19 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs p, Segs segs) {
 }
 
 template <int BM, int BN, int WM, int WN>
-void launch_bf16(const GemmArgs& a, const Segs& s, int groups, hipStream_t st) {
-  dim3 grid((a.M + BM - 1) / BM, (a.N + BN - 1) / BN, groups), block(WM * WN * 64);
+void launch_bf16(GemmArgs a, const Segs& s, hipStream_t st) {
+  const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
+  int gy = 1;
+  a.groups_per_block = 1;
+  if (a.mode == MODE_WGRAD) {
+    // a workgroup streams through several workers; split the workers over more workgroups only
+    // when the tiles alone cannot occupy the 256 compute units
+    int chunks = (256 + tiles - 1) / tiles;
+    if (chunks > s.K) chunks = s.K;
+    a.groups_per_block = (s.K + chunks - 1) / chunks;
+    gy = (s.K + a.groups_per_block - 1) / a.groups_per_block;
+  }
+  dim3 grid(tiles, gy, 1), block(WM * WN * 64);
   switch (a.mode) {
     case MODE_FWD:
       hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, MODE_FWD>), grid, block, 0, st, a, s);
@@ -273,9 +513,15 @@ int launch_gemm(int dtype, const GemmArgs& a, const Segs& s, void* stream) {
   const KClass cls = a.mode == MODE_FWD ? KC_GEMM_FWD : a.mode == MODE_DGRAD ? KC_GEMM_DGRAD
                                                                               : KC_GEMM_WGRAD;
   Timed t(cls, stream, flops, bytes);
-  if (dtype == DYNB_BF16)
-    launch_bf16<128, 128, 2, 2>(a, s, groups, (hipStream_t)stream);
-  else
+  if (dtype == DYNB_BF16) {
+    // large tiles have the best LDS-traffic-to-MFMA ratio; small problems need more, smaller
+    // tiles to occupy 256 compute units
+    const int64_t big = (int64_t)((a.M + 255) / 256) * ((a.N + 255) / 256);
+    if (big >= 192)
+      launch_bf16<256, 256, 2, 2>(a, s, (hipStream_t)stream);
+    else
+      launch_bf16<128, 128, 2, 2>(a, s, (hipStream_t)stream);
+  } else
     launch_f32(a, s, groups, (hipStream_t)stream);
   return hipGetLastError() == hipSuccess ? DYNB_OK : fail(DYNB_ERR_HIP, "gemm launch failed");
 }

@@ -13,11 +13,17 @@ typedef __bf16 bf16;
 template <typename T> __device__ inline T from_float(float v) { return (T)v; }
 template <typename T> __device__ inline float to_float(T v) { return (float)v; }
 
-// Padded row -> (worker, row inside the worker's segment).
-__device__ inline void locate(const Segs& s, int prow, int& k, int& r) {
+// Padded row -> (worker, row inside the worker's padded segment).
+__device__ inline void locate_padded(const Segs& s, int prow, int& k, int& r) {
   k = 0;
   while (k + 1 < s.K && prow >= s.poff[k + 1]) ++k;
   r = prow - s.poff[k];
+}
+// Dense row -> worker.
+__device__ inline int worker_of(const Segs& s, int row) {
+  int k = 0;
+  while (k + 1 < s.K && row >= s.off[k + 1]) ++k;
+  return k;
 }
 
 __device__ inline float wave_sum(float v) {
@@ -31,41 +37,46 @@ __device__ inline float wave_max(float v) {
   return v;
 }
 
-// ---- pack: dense fp32 rows -> padded rows of T --------------------------------------
+// ---- pack: fp32 rows -> rows of T ---------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void pack_rows_kernel(const float* __restrict__ x, int D,
-                                                        T* __restrict__ out, int64_t ld, Segs s) {
-  const int prow = blockIdx.y;
-  int k, r;
-  locate(s, prow, k, r);
-  const bool live = r < s.off[k + 1] - s.off[k];
-  const float* src = x + (int64_t)(s.off[k] + r) * D;
-  T* dst = out + (int64_t)prow * ld;
+                                                        T* __restrict__ out, int64_t ld) {
+  const int row = blockIdx.y;
+  const float* src = x + (int64_t)row * D;
+  T* dst = out + (int64_t)row * ld;
   for (int c = blockIdx.x * 256 + threadIdx.x; c < D; c += gridDim.x * 256)
-    dst[c] = from_float<T>(live ? src[c] : 0.f);
+    dst[c] = from_float<T>(src[c]);
 }
 
-// ---- transpose: out[c][r] = in[r][c] ----------------------------------------------------
+// ---- transpose into the padded row space: out[c][p] = in[m(p)][c], 0 where p is padding ----
+// p runs over the padded positions; worker k's b_k rows sit at [poff_k, poff_k + b_k).
 template <typename T>
 __global__ __launch_bounds__(256) void transpose_kernel(const T* __restrict__ in, int64_t ldi,
-                                                        int R, int C, T* __restrict__ out,
-                                                        int64_t ldo) {
+                                                        int C, T* __restrict__ out, int64_t ldo,
+                                                        Segs s) {
   __shared__ T tile[64][66];
-  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  const int p0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
   const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const int P = s.poff[s.K];
   for (int i = ty; i < 64; i += 4) {
-    const int r = r0 + i, c = c0 + tx;
-    tile[i][tx] = (r < R && c < C) ? in[(int64_t)r * ldi + c] : from_float<T>(0.f);
+    const int pr = p0 + i, c = c0 + tx;
+    T v = from_float<T>(0.f);
+    if (pr < P && c < C) {
+      int k, r;
+      locate_padded(s, pr, k, r);
+      if (r < s.off[k + 1] - s.off[k]) v = in[(int64_t)(s.off[k] + r) * ldi + c];
+    }
+    tile[i][tx] = v;
   }
   __syncthreads();
   for (int i = ty; i < 64; i += 4) {
-    const int c = c0 + i, r = r0 + tx;
-    if (c < C && r < R) out[(int64_t)c * ldo + r] = tile[tx][i];
+    const int c = c0 + i, pr = p0 + tx;
+    if (c < C && pr < P) out[(int64_t)c * ldo + pr] = tile[tx][i];
   }
 }
 
-// ---- softmax cross-entropy, one wavefront per padded row --------------------------------
-// dz = (softmax(z) - onehot(y)) / b_k for live rows; zero for pad rows and pad columns.
+// ---- softmax cross-entropy, one wavefront per row -----------------------------------------
+// dz = (softmax(z) - onehot(y)) / b_k for the rows of worker k; zero in the pad columns.
 template <typename T>
 __global__ __launch_bounds__(256) void softmax_xent_kernel(const float* __restrict__ z, int64_t ldz,
                                                            const int32_t* __restrict__ y, int C,
@@ -73,19 +84,13 @@ __global__ __launch_bounds__(256) void softmax_xent_kernel(const float* __restri
                                                            int ld_cols, float* __restrict__ rowloss,
                                                            Segs s) {
   const int lane = threadIdx.x & 63;
-  const int prow = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (prow >= s.poff[s.K]) return;
-  int k, r;
-  locate(s, prow, k, r);
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= s.off[s.K]) return;
+  const int k = worker_of(s, row);
   const int bk = s.off[k + 1] - s.off[k];
-  T* drow = dz + (int64_t)prow * ldd;
-  if (r >= bk) {
-    for (int c = lane; c < ld_cols; c += 64) drow[c] = from_float<T>(0.f);
-    if (lane == 0) rowloss[prow] = 0.f;
-    return;
-  }
-  const float* zr = z + (int64_t)prow * ldz;
-  int label = y[s.off[k] + r];
+  T* drow = dz + (int64_t)row * ldd;
+  const float* zr = z + (int64_t)row * ldz;
+  int label = y[row];
   label = label < 0 ? 0 : (label >= C ? C - 1 : label);   // keeps the read in bounds
   float m = -INFINITY;
   for (int c = lane; c < C; c += 64) m = fmaxf(m, zr[c]);
@@ -100,7 +105,7 @@ __global__ __launch_bounds__(256) void softmax_xent_kernel(const float* __restri
     if (c < C) v = (expf(zr[c] - m) * inv - (c == label ? 1.f : 0.f)) * scale;
     drow[c] = from_float<T>(v);
   }
-  if (lane == 0) rowloss[prow] = logf(sum) - (zr[label] - m);
+  if (lane == 0) rowloss[row] = logf(sum) - (zr[label] - m);
 }
 
 // ---- bias gradient: one wavefront per (output feature, worker) --------------------------
@@ -128,7 +133,7 @@ __global__ __launch_bounds__(64) void finalize_kernel(const float* __restrict__ 
   const int g = blockIdx.x, lane = threadIdx.x;
   const int bk = s.off[g + 1] - s.off[g];
   float acc = 0.f;
-  for (int i = lane; i < bk; i += 64) acc += rowloss[s.poff[g] + i];
+  for (int i = lane; i < bk; i += 64) acc += rowloss[s.off[g] + i];
   acc = wave_sum(acc);
   if (lane == 0) loss[g] = bk > 0 ? acc / (float)bk : 0.f;
   if (grads)
@@ -171,33 +176,33 @@ inline int ok(const char* what) {
     else { typedef float T; CALL; }                          \
   } while (0)
 
-int launch_pack_rows(int dtype, const float* x, int D, void* out, int64_t ld, const Segs& s,
+int launch_pack_rows(int dtype, const float* x, int rows, int D, void* out, int64_t ld,
                      void* stream) {
-  const int rows = s.poff[s.K];
   if (rows == 0) return DYNB_OK;
   const int es = dtype == DYNB_BF16 ? 2 : 4;
-  Timed t(KC_PACK, stream, 0, (double)s.off[s.K] * D * (4 + es));
+  Timed t(KC_PACK, stream, 0, (double)rows * D * (4 + es));
   dim3 grid((D + 255) / 256 > 8 ? 8 : (D + 255) / 256, rows);
   DISPATCH_T(dtype, hipLaunchKernelGGL(pack_rows_kernel<T>, grid, dim3(256), 0,
-                                       (hipStream_t)stream, x, D, (T*)out, ld, s));
+                                       (hipStream_t)stream, x, D, (T*)out, ld));
   return ok("pack_rows");
 }
 
-int launch_transpose(int dtype, const void* in, int64_t ldi, int R, int C, void* out, int64_t ldo,
-                     void* stream) {
-  if (R == 0 || C == 0) return DYNB_OK;
+int launch_transpose(int dtype, const void* in, int64_t ldi, int C, void* out, int64_t ldo,
+                     const Segs& s, void* stream) {
+  const int P = s.poff[s.K];
+  if (P == 0 || C == 0) return DYNB_OK;
   const int es = dtype == DYNB_BF16 ? 2 : 4;
-  Timed t(KC_TRANSPOSE, stream, 0, 2.0 * R * C * es);
-  dim3 grid((C + 63) / 64, (R + 63) / 64);
+  Timed t(KC_TRANSPOSE, stream, 0, 2.0 * s.off[s.K] * C * es);
+  dim3 grid((C + 63) / 64, (P + 63) / 64);
   DISPATCH_T(dtype, hipLaunchKernelGGL(transpose_kernel<T>, grid, dim3(256), 0,
-                                       (hipStream_t)stream, (const T*)in, ldi, R, C, (T*)out, ldo));
+                                       (hipStream_t)stream, (const T*)in, ldi, C, (T*)out, ldo, s));
   return ok("transpose");
 }
 
 int launch_softmax_xent(int dtype, const float* logits, int64_t ldz, const int32_t* y, int C,
                         void* dz, int64_t ldd, int ld_cols, float* rowloss, const Segs& s,
                         void* stream) {
-  const int rows = s.poff[s.K];
+  const int rows = s.off[s.K];
   if (rows == 0) return DYNB_OK;
   Timed t(KC_SOFTMAX, stream, 0, (double)rows * C * 6);
   DISPATCH_T(dtype, hipLaunchKernelGGL(softmax_xent_kernel<T>, dim3((rows + 3) / 4), dim3(256), 0,

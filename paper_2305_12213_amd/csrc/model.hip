@@ -1,16 +1,16 @@
 // Model handle: layer plan, workspace carving, and the per-step orchestration of
 // dynb_forward_backward (forward, loss, backward per worker) on one stream.
 //
-// Row space.  Worker k's b_k rows are placed at padded rows [poff_k, poff_k + b_k) with
-// poff_k = sum_{j<k} round_up(b_j, 8).  Forward and the activation-gradient pass treat the
-// padded batch as one matrix (rows are independent and all workers share the weights);
-// only the loss scaling 1/b_k and the weight/bias gradients are per worker.  Pad rows carry
-// exact zeros in every activation-gradient, so they add nothing to any weight gradient.
+// Forward and the activation-gradient pass treat the global batch as one matrix of sum(b)
+// rows (rows are independent and all workers share the weights); only the loss scaling 1/b_k
+// and the weight/bias gradients are per worker.
 //
 // Every activation and activation-gradient is kept twice: row-major [rows][features] (the
 // k-contiguous operand of forward / activation-gradient GEMMs) and transposed
-// [features][rows] (the k-contiguous operands of the per-worker weight-gradient GEMMs,
-// whose reduction runs over the worker's rows).
+// [features][padded rows] (the k-contiguous operands of the per-worker weight-gradient GEMMs,
+// whose reduction runs over the worker's rows).  In the transposed copies worker k's b_k rows
+// sit at columns [poff_k, poff_k + b_k), poff_k = sum_{j<k} round_up(b_j, 8), so that every
+// worker's segment starts on a 16-byte boundary; the padding columns are written as zero.
 #include <hip/hip_runtime.h>
 
 #include <new>
@@ -222,16 +222,16 @@ extern "C" int dynb_forward_backward(dynb_model* m, const float* x, const int32_
   if (s.off[K] > m->max_batch)
     return fail(DYNB_ERR_BADARG, "forward_backward: sum(b)=%d exceeds max_global_batch=%d",
                 s.off[K], m->max_batch);
-  const int Mp = s.poff[K];   // padded rows in use (<= rows_cap by construction)
+  const int Mp = s.off[K];    // rows of the global batch
   const int dt = m->dtype;
   const size_t L = m->layers.size();
   const int64_t ldT = m->rows_cap;
 
   if (Mp > 0) {
     // ---- forward ----
-    rc = launch_pack_rows(dt, x, m->in_features, m->act[0], m->layers[0].ld_in, s, stream);
+    rc = launch_pack_rows(dt, x, Mp, m->in_features, m->act[0], m->layers[0].ld_in, stream);
     if (rc) return rc;
-    rc = launch_transpose(dt, m->act[0], m->layers[0].ld_in, Mp, m->layers[0].n_in, m->actT[0], ldT,
+    rc = launch_transpose(dt, m->act[0], m->layers[0].ld_in, m->layers[0].n_in, m->actT[0], ldT, s,
                           stream);
     if (rc) return rc;
     for (size_t l = 0; l < L; ++l) {
@@ -249,7 +249,7 @@ extern "C" int dynb_forward_backward(dynb_model* m, const float* x, const int32_
       rc = launch_gemm(dt, g, s, stream);
       if (rc) return rc;
       if (!last) {
-        rc = launch_transpose(dt, m->act[l + 1], D.ld_out, Mp, D.n_out, m->actT[l + 1], ldT, stream);
+        rc = launch_transpose(dt, m->act[l + 1], D.ld_out, D.n_out, m->actT[l + 1], ldT, s, stream);
         if (rc) return rc;
       }
     }
@@ -261,7 +261,7 @@ extern "C" int dynb_forward_backward(dynb_model* m, const float* x, const int32_
     // ---- backward ----
     for (size_t l = L; l-- > 0;) {
       const DenseLayer& D = m->layers[l];
-      rc = launch_transpose(dt, m->dy[l], D.ld_out, Mp, D.n_out, m->dyT[l], ldT, stream);
+      rc = launch_transpose(dt, m->dy[l], D.ld_out, D.n_out, m->dyT[l], ldT, s, stream);
       if (rc) return rc;
       if (l > 0) {  // gradient wrt this layer's input, masked by the ReLU of the layer below
         const DenseLayer& Dp = m->layers[l - 1];

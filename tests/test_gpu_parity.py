@@ -3,8 +3,11 @@ element on the same seeded inputs.
 
 Tolerances (max-abs-normalised per tensor, max|got - ref| / max|ref|): fp32 1e-4; bf16 2e-2.
 The bf16 reference is the checker with bfloat16 rounding emulated at the points where the kernels
-store 16-bit values; against it the kernels differ only by fp32-vs-fp64 accumulation and a
-stored value that rounds the other way now and then, so the tests hold them to 4e-3.
+store 16-bit values; against it the kernels differ only by fp32-vs-fp64 accumulation and by a
+stored value that rounds the other way now and then (one bfloat16 unit in the last place, 2^-8
+relative).  In a worker with a handful of samples one stored value can dominate an output entry,
+and two such roundings can chain (an activation and the gradient arriving at it), so the tests
+hold the kernels to 2 * 2^-8 = 8e-3, inside the 2e-2 the method is allowed.
 ReLU derivative decisions on units inside the rounding band are resolved as tests/relu_ties.py
 describes; all other decisions are the checker's.
 """
@@ -20,7 +23,7 @@ from relu_ties import resolved_worker_references
 pytestmark = pytest.mark.gpu
 
 TOL = {"f32": 1e-4, "bf16": 2e-2}
-TOL_EMULATED = 4e-3
+TOL_EMULATED = 8e-3
 
 
 def check_worker_gradients(spec, params, x, y, b, run=None, label=""):
