@@ -50,28 +50,39 @@ __global__ __launch_bounds__(256) void pack_rows_kernel(const float* __restrict_
 
 // ---- transpose into the padded row space: out[c][p] = in[m(p)][c], 0 where p is padding ----
 // p runs over the padded positions; worker k's b_k rows sit at [poff_k, poff_k + b_k).
+// A 64 x 64 tile moves through LDS; global loads and stores are 16 bytes per lane, and eight
+// neighbouring lanes write one contiguous 128-byte line of an output row.
 template <typename T>
 __global__ __launch_bounds__(256) void transpose_kernel(const T* __restrict__ in, int64_t ldi,
                                                         int C, T* __restrict__ out, int64_t ldo,
                                                         Segs s) {
-  __shared__ T tile[64][66];
+  constexpr int G = 16 / sizeof(T);          // elements per 16-byte granule
+  constexpr int GC = 64 / G;                 // granules per tile row
+  __shared__ T tile[64][64 + 2 * G];
   const int p0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
-  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
   const int P = s.poff[s.K];
-  for (int i = ty; i < 64; i += 4) {
-    const int pr = p0 + i, c = c0 + tx;
-    T v = from_float<T>(0.f);
-    if (pr < P && c < C) {
-      int k, r;
-      locate_padded(s, pr, k, r);
-      if (r < s.off[k + 1] - s.off[k]) v = in[(int64_t)(s.off[k] + r) * ldi + c];
+  typedef T vecT __attribute__((ext_vector_type(G)));
+  for (int idx = threadIdx.x; idx < 64 * GC; idx += 256) {
+    const int r = idx / GC, gc = idx % GC;
+    const int pr = p0 + r;
+    vecT v = {};
+    if (pr < P) {
+      int k, rl;
+      locate_padded(s, pr, k, rl);
+      if (rl < s.off[k + 1] - s.off[k])
+        v = *(const vecT*)(in + (int64_t)(s.off[k] + rl) * ldi + c0 + gc * G);
     }
-    tile[i][tx] = v;
+#pragma unroll
+    for (int e = 0; e < G; ++e) tile[r][gc * G + e] = v[e];
   }
   __syncthreads();
-  for (int i = ty; i < 64; i += 4) {
-    const int c = c0 + i, pr = p0 + tx;
-    if (c < C && pr < P) out[(int64_t)c * ldo + pr] = tile[tx][i];
+  for (int idx = threadIdx.x; idx < 64 * GC; idx += 256) {
+    const int rg = idx % GC, c = idx / GC;    // rg: granule of padded positions, c: output row
+    if (c0 + c >= C) continue;
+    vecT v;
+#pragma unroll
+    for (int e = 0; e < G; ++e) v[e] = tile[rg * G + e][c];
+    *(vecT*)(out + (int64_t)(c0 + c) * ldo + p0 + rg * G) = v;
   }
 }
 
