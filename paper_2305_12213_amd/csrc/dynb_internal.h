@@ -79,6 +79,22 @@ struct GemmArgs {
   const void* mask; int64_t ldmask;
   int64_t group_stride;
   int groups_per_block;                // WGRAD, bf16 kernel: workers streamed by one workgroup
+  // Implicit-GEMM gather of operand A for a 3x3 convolution with zero padding 1 (bf16 only).
+  // conv == 0: A is a plain matrix.  conv == 1 (forward): row i is output pixel (n, y, x) of a
+  // row_h x row_w grid and reduction index k = (kh*3 + kw)*cp + c reads channel c of source
+  // pixel (y*stride + kh - 1, x*stride + kw - 1).  conv == 2 (input gradient): row i is input
+  // pixel (n, y, x) and k reads channel c of output pixel ((y + 1 - kh)/stride,
+  // (x + 1 - kw)/stride) when both divisions are exact.  Out-of-range taps read zero.
+  // A points at the source tensor [n * src_h * src_w][lda]; cp is a multiple of 8.
+  int conv, src_h, src_w, row_h, row_w, stride, cp;
+  double alg_flops, alg_bytes;         // algorithmic work of the launch (timing aid only)
+  // WGRAD, bf16 kernel: split every worker's reduction into `split` chunks of `chunk` columns
+  // (a multiple of 64).  Chunk c of worker g writes its tile to partial + (g*split + c) *
+  // partial_stride (row pitch ldcf); launch_wgrad_reduce sums the chunks in a fixed order.
+  // split <= 1: no split, tiles go straight to Cf.
+  int split, chunk;
+  float* partial;
+  int64_t partial_stride;
 };
 
 int launch_gemm(int dtype, const GemmArgs& a, const Segs& s, void* stream);
@@ -107,6 +123,21 @@ int launch_momentum(float* params, float* v, const float* g, int64_t n, float lr
 // W fp32 [R][C] (dense) -> Wn T [R][ldn] and Wt T [C][ldt]
 int launch_weight_cast(int dtype, const float* W, int R, int C, void* Wn, int64_t ldn, void* Wt,
                        int64_t ldt, void* stream);
+
+// out[g*group_stride + e] = sum_{c < split} partial[(g*split + c)*partial_stride + e], e < n
+int launch_wgrad_reduce(const float* partial, int split, int64_t partial_stride, int64_t n,
+                        float* out, int64_t group_stride, int K, void* stream);
+
+// ---- convolution helpers (bf16 storage) ----
+// out bf16 [9*C][ldo]: transposed patch matrix over the padded pixel positions of segments s
+int launch_im2col_t(const void* in, int64_t ldi, int C, int H, int W, int Ho, int Wo, int stride,
+                    void* out, int64_t ldo, const Segs& s, void* stream);
+int launch_gap_forward(const void* act, int64_t lda, int HW, int C, int samples, void* pooled,
+                       int64_t ldp, void* stream);
+int launch_gap_backward(const void* dpooled, int64_t ldp, const void* act, int64_t lda, int HW,
+                        int C, int samples, int relu, void* dact, int64_t ldd, void* stream);
+int launch_conv_weight_cast(const float* W, int Cin, int Cout, int cin_p, int cout_p, void* Wf,
+                            int kf, void* Wd, int kd, void* stream);
 
 }  // namespace dynb
 

@@ -98,7 +98,7 @@ struct StageCursor {
   int g, kt;
 };
 
-template <int BM, int BN, int WM, int WN, int MODE>
+template <int BM, int BN, int WM, int WN, int MODE, bool GATHER>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Segs segs) {
   constexpr int NW = WM * WN;
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
@@ -110,10 +110,13 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
   __shared__ uint4 sB[2][BN * GPR];
   __shared__ float sStage[MODE == MODE_WGRAD ? NW * 32 * SPITCH : 4];
 
-  // groups (workers) of this workgroup: [g_lo, g_hi)
+  // groups of this workgroup: [g_lo, g_hi).  A group is a worker, or, when the reduction is
+  // split, one chunk of a worker's rows (group id = worker * split + chunk).
+  const int split = MODE == MODE_WGRAD && p.split > 1 ? p.split : 1;
+  const int n_groups = MODE == MODE_WGRAD ? segs.K * split : 1;
   const int g_lo = MODE == MODE_WGRAD ? blockIdx.y * p.groups_per_block : 0;
   const int g_hi = MODE == MODE_WGRAD
-                       ? (g_lo + p.groups_per_block < segs.K ? g_lo + p.groups_per_block : segs.K)
+                       ? (g_lo + p.groups_per_block < n_groups ? g_lo + p.groups_per_block : n_groups)
                        : 1;
   int ti, tj;
   tile_of_block(blockIdx.x, (p.M + BM - 1) / BM, (p.N + BN - 1) / BN, ti, tj);
@@ -121,7 +124,20 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave % WM, wn = wave / WM;
 
-  auto depth_of = [&](int g) { return MODE == MODE_WGRAD ? segs.poff[g + 1] - segs.poff[g] : p.K; };
+  auto col0_of = [&](int g) {   // first reduction column of a group
+    if (MODE != MODE_WGRAD) return 0;
+    return split > 1 ? segs.poff[g / split] + (g % split) * p.chunk : segs.poff[g];
+  };
+  auto depth_of = [&](int g) {
+    if (MODE != MODE_WGRAD) return p.K;
+    if (split == 1) return segs.poff[g + 1] - segs.poff[g];
+    const int w = g / split, left = segs.poff[w + 1] - segs.poff[w] - (g % split) * p.chunk;
+    return left < 0 ? 0 : (left < p.chunk ? left : p.chunk);
+  };
+  auto tile_base = [&](int g) -> float* {   // where a group's tile goes
+    if (split > 1) return p.partial + (int64_t)g * p.partial_stride;
+    return p.Cf + (int64_t)g * p.group_stride;
+  };
   auto stages_of = [&](int g) { return (depth_of(g) + BK - 1) / BK; };
   auto settle = [&](StageCursor& c) {   // first stage at or after c; skips groups without rows
     while (c.g < g_hi && c.kt >= stages_of(c.g)) {
@@ -138,11 +154,20 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
   const char* Ab = (const char*)p.A;
   const char* Bb = (const char*)p.B;
   uint32_t offA[LA], offB[LB];
+  int gy[GATHER ? LA : 1], gx[GATHER ? LA : 1];   // gather: the row's pixel coordinates
 #pragma unroll
   for (int u = 0; u < LA; ++u) {
     int i = i0 + (wave + NW * u) * 8 + lrow;
     i = i < p.M ? i : p.M - 1;
-    offA[u] = (uint32_t)(((int64_t)i * p.lda + lgran * 8) * 2);
+    if (GATHER) {
+      const int hw = p.row_h * p.row_w;
+      const int n = i / hw, rem = i - n * hw;
+      gy[u] = rem / p.row_w;
+      gx[u] = rem - gy[u] * p.row_w;
+      offA[u] = (uint32_t)(n * p.src_h * p.src_w);   // first source pixel of the sample
+    } else {
+      offA[u] = (uint32_t)(((int64_t)i * p.lda + lgran * 8) * 2);
+    }
   }
 #pragma unroll
   for (int u = 0; u < LB; ++u) {
@@ -158,11 +183,39 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
     uint32_t kbyte = (uint32_t)k0 * 2;
     if (MODE == MODE_WGRAD) {
       live = k0 + lgran * 8 < depth_of(c.g);
-      kbyte += (uint32_t)segs.poff[c.g] * 2;
+      kbyte += (uint32_t)col0_of(c.g) * 2;
+    }
+    int kh = 0, kw = 0, ch = 0;
+    bool tap_ok = false;
+    if (GATHER) {
+      const int k = k0 + lgran * 8;
+      const int tap = k / p.cp;
+      ch = k - tap * p.cp;
+      kh = tap / 3;
+      kw = tap - kh * 3;
+      tap_ok = tap < 9;
     }
 #pragma unroll
     for (int u = 0; u < LA; ++u) {
-      const void* src = live ? (const void*)(Ab + offA[u] + kbyte) : (const void*)g_zero_granule;
+      const void* src;
+      if (GATHER) {
+        int sy, sx;
+        bool ok = tap_ok;
+        if (p.conv == 1) {
+          sy = gy[u] * p.stride + kh - 1;
+          sx = gx[u] * p.stride + kw - 1;
+        } else {
+          const int ty = gy[u] + 1 - kh, tx = gx[u] + 1 - kw;
+          sy = ty / p.stride;
+          sx = tx / p.stride;
+          ok = ok && ty >= 0 && tx >= 0 && sy * p.stride == ty && sx * p.stride == tx;
+        }
+        ok = ok && sy >= 0 && sy < p.src_h && sx >= 0 && sx < p.src_w;
+        const int64_t pix = (int64_t)offA[u] + sy * p.src_w + sx;
+        src = ok ? (const void*)(Ab + (pix * p.lda + ch) * 2) : (const void*)g_zero_granule;
+      } else {
+        src = live ? (const void*)(Ab + offA[u] + kbyte) : (const void*)g_zero_granule;
+      }
       async_copy_1k(src, ldsA + (uint32_t)((buf * BM * GPR + (wave + NW * u) * 64) * 16));
     }
 #pragma unroll
@@ -219,7 +272,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
   // (whole lines) instead of 32 rows x 32 bytes: these stores are the largest HBM stream of a
   // step.  LDS operations of one wave execute in order, so the patch needs no barrier.
   auto store_wgrad = [&](int g) {
-    float* Cg = p.Cf + (int64_t)g * p.group_stride;
+    float* Cg = tile_base(g);
     float* patch = &sStage[wave * 32 * SPITCH];
     const bool vec_ok = (p.ldcf & 3) == 0 && (((uintptr_t)Cg) & 15) == 0;
     const int rr = lane >> 3, rc = (lane & 7) * 4;
@@ -257,7 +310,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
 
   // A worker without rows contributes a zero tile (not unrolled: it is rare and tiny).
   auto store_zero = [&](int g) {
-    float* Cg = p.Cf + (int64_t)g * p.group_stride;
+    float* Cg = tile_base(g);
     const bool vec_ok = (p.ldcf & 3) == 0 && (((uintptr_t)Cg) & 15) == 0;
     const int rr = lane >> 3, rc = (lane & 7) * 4;
 #pragma unroll 1
@@ -459,22 +512,34 @@ void launch_bf16(GemmArgs a, const Segs& s, hipStream_t st) {
   if (a.mode == MODE_WGRAD) {
     // a workgroup streams through several workers; split the workers over more workgroups only
     // when the tiles alone cannot occupy the 256 compute units
+    const int n_groups = s.K * (a.split > 1 ? a.split : 1);
     int chunks = (256 + tiles - 1) / tiles;
-    if (chunks > s.K) chunks = s.K;
-    a.groups_per_block = (s.K + chunks - 1) / chunks;
-    gy = (s.K + a.groups_per_block - 1) / a.groups_per_block;
+    if (chunks > n_groups) chunks = n_groups;
+    a.groups_per_block = (n_groups + chunks - 1) / chunks;
+    gy = (n_groups + a.groups_per_block - 1) / a.groups_per_block;
   }
   dim3 grid(tiles, gy, 1), block(WM * WN * 64);
   switch (a.mode) {
     case MODE_FWD:
-      hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, MODE_FWD>), grid, block, 0, st, a, s);
+      hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, MODE_FWD, false>), grid, block, 0, st, a, s);
       break;
     case MODE_DGRAD:
-      hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, MODE_DGRAD>), grid, block, 0, st, a, s);
+      hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, MODE_DGRAD, false>), grid, block, 0, st, a, s);
       break;
     default:
-      hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, MODE_WGRAD>), grid, block, 0, st, a, s);
+      hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, MODE_WGRAD, false>), grid, block, 0, st, a, s);
   }
+}
+
+// implicit-GEMM convolution (operand A gathered): 128 x 128 tiles
+void launch_bf16_gather(GemmArgs a, const Segs& s, hipStream_t st) {
+  const int tiles = ((a.M + 127) / 128) * ((a.N + 127) / 128);
+  a.groups_per_block = 1;
+  dim3 grid(tiles, 1, 1), block(256);
+  if (a.mode == MODE_FWD)
+    hipLaunchKernelGGL((gemm_bf16_kernel<128, 128, 2, 2, MODE_FWD, true>), grid, block, 0, st, a, s);
+  else
+    hipLaunchKernelGGL((gemm_bf16_kernel<128, 128, 2, 2, MODE_DGRAD, true>), grid, block, 0, st, a, s);
 }
 
 void launch_f32(const GemmArgs& a, const Segs& s, int groups, hipStream_t st) {
@@ -500,20 +565,14 @@ int launch_gemm(int dtype, const GemmArgs& a, const Segs& s, void* stream) {
   if ((a.lda % gran) || (a.ldb % gran) || ((uintptr_t)a.A & 15) || ((uintptr_t)a.B & 15))
     return fail(DYNB_ERR_BADARG, "gemm: operands must have 16-byte aligned rows");
   const int groups = a.mode == MODE_WGRAD ? s.K : 1;
-  // algorithmic work: true (unpadded) rows only
-  double flops, bytes;
-  const double rows = s.off[s.K];
-  if (a.mode == MODE_WGRAD) {
-    flops = 2.0 * rows * a.M * a.N;
-    bytes = (double)groups * a.M * a.N * 4 + rows * (a.M + a.N) * es;
-  } else {
-    flops = 2.0 * rows * a.N * a.K;
-    bytes = rows * (a.K + a.N) * es + (double)a.N * a.K * es;
-  }
   const KClass cls = a.mode == MODE_FWD ? KC_GEMM_FWD : a.mode == MODE_DGRAD ? KC_GEMM_DGRAD
                                                                               : KC_GEMM_WGRAD;
-  Timed t(cls, stream, flops, bytes);
-  if (dtype == DYNB_BF16) {
+  Timed t(cls, stream, a.alg_flops, a.alg_bytes);
+  if (a.conv) {
+    if (dtype != DYNB_BF16 || a.mode == MODE_WGRAD || (a.cp & 7) || a.stride < 1)
+      return fail(DYNB_ERR_UNSUPPORTED, "gemm: gathered operand needs bf16, forward/input-gradient mode");
+    launch_bf16_gather(a, s, (hipStream_t)stream);
+  } else if (dtype == DYNB_BF16) {
     // large tiles have the best LDS-traffic-to-MFMA ratio; small problems need more, smaller
     // tiles to occupy 256 compute units
     const int64_t big = (int64_t)((a.M + 255) / 256) * ((a.N + 255) / 256);

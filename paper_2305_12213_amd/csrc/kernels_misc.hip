@@ -175,6 +175,19 @@ __global__ __launch_bounds__(256) void weight_cast_kernel(const float* __restric
   }
 }
 
+// ---- sum of the split weight-gradient chunks, fixed order -------------------------------
+__global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restrict__ partial,
+                                                           int split, int64_t pstride, int64_t n,
+                                                           float* __restrict__ out,
+                                                           int64_t group_stride) {
+  const int g = blockIdx.y;
+  for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < n; e += (int64_t)gridDim.x * 256) {
+    float acc = 0.f;
+    for (int c = 0; c < split; ++c) acc += partial[((int64_t)g * split + c) * pstride + e];
+    out[(int64_t)g * group_stride + e] = acc;
+  }
+}
+
 inline int ok(const char* what) {
   return hipGetLastError() == hipSuccess ? DYNB_OK : fail(DYNB_ERR_HIP, "%s: launch failed", what);
 }
@@ -238,6 +251,16 @@ int launch_finalize(const float* rowloss, float* loss, float* grads, int64_t P, 
   hipLaunchKernelGGL(finalize_kernel, dim3(s.K), dim3(64), 0, (hipStream_t)stream, rowloss, loss,
                      grads, P, P_pad, s);
   return ok("finalize");
+}
+
+int launch_wgrad_reduce(const float* partial, int split, int64_t partial_stride, int64_t n,
+                        float* out, int64_t group_stride, int K, void* stream) {
+  Timed t(KC_GEMM_WGRAD, stream, 0, 0);
+  int64_t bx = (n + 255) / 256;
+  if (bx > 1024) bx = 1024;
+  hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)bx, K), dim3(256), 0, (hipStream_t)stream,
+                     partial, split, partial_stride, n, out, group_stride);
+  return ok("wgrad_reduce");
 }
 
 int launch_weight_cast(int dtype, const float* W, int R, int C, void* Wn, int64_t ldn, void* Wt,

@@ -1,16 +1,16 @@
 // Model handle: layer plan, workspace carving, and the per-step orchestration of
 // dynb_forward_backward (forward, loss, backward per worker) on one stream.
 //
-// Forward and the activation-gradient pass treat the global batch as one matrix of sum(b)
-// rows (rows are independent and all workers share the weights); only the loss scaling 1/b_k
-// and the weight/bias gradients are per worker.
+// Forward and the activation-gradient pass treat the global batch as one matrix (rows are
+// independent and all workers share the weights); only the loss scaling 1/b_k and the
+// weight/bias gradients are per worker.  A "row" is a sample for dense layers and a pixel
+// (sample, y, x) for convolutions (NHWC with the channel pitch padded to 64).
 //
-// Every activation and activation-gradient is kept twice: row-major [rows][features] (the
-// k-contiguous operand of forward / activation-gradient GEMMs) and transposed
-// [features][padded rows] (the k-contiguous operands of the per-worker weight-gradient GEMMs,
-// whose reduction runs over the worker's rows).  In the transposed copies worker k's b_k rows
-// sit at columns [poff_k, poff_k + b_k), poff_k = sum_{j<k} round_up(b_j, 8), so that every
-// worker's segment starts on a 16-byte boundary; the padding columns are written as zero.
+// Every operand of a per-worker weight-gradient GEMM is kept transposed,
+// [features][padded rows], because its reduction runs over the worker's rows.  In these
+// copies worker k's rows sit at columns [poff_k, poff_k + rows_k), poff_k = sum_{j<k}
+// round_up(rows_j, 8), so that every worker's segment starts on a 16-byte boundary; the
+// padding columns are written as zero.
 #include <hip/hip_runtime.h>
 
 #include <new>
@@ -20,30 +20,44 @@
 
 using namespace dynb;
 
-struct DenseLayer {
-  int n_in, n_out;
-  int64_t ld_in, ld_out;   // padded leading dimensions of the activations
-  int64_t w_off, b_off;    // offsets into the flat parameter vector
-  bool relu;
-  void* Wn = nullptr;      // T [n_in][ld_out]   (B operand of the activation-gradient GEMM)
-  void* Wt = nullptr;      // T [n_out][ld_in]   (B operand of the forward GEMM)
+struct Layer {
+  int kind = DYNB_LAYER_DENSE;
+  int n_in = 0, n_out = 0;           // features (dense) or channels (conv, pool)
+  int h_in = 1, w_in = 1, h_out = 1, w_out = 1, stride = 1;
+  int hw_in = 1, hw_out = 1;         // rows per sample of the input / output
+  int64_t ld_in = 0, ld_out = 0;     // channel pitch of input / output rows
+  int cin_p = 0, cout_p = 0;         // conv: channels per tap, padded to 8
+  int kf = 0, kd = 0;                // conv: reduction length forward / input gradient (x64)
+  int wg_rows = 0;                   // rows of the transposed weight-gradient operand
+  int64_t w_off = 0, b_off = 0;      // offsets into the flat parameter vector
+  bool relu = false, has_params = false;
+  void* Wn = nullptr;                // B operand of the input-gradient GEMM
+  void* Wt = nullptr;                // B operand of the forward GEMM
+  void* out = nullptr;               // T [rows_out][ld_out]: stored output (not for the last layer)
+  void* inT = nullptr;               // T [wg_rows][cap]: transposed input (dense) / patches (conv)
+  void* dy = nullptr;                // T [rows_out][ld_out]: gradient wrt the output, masked
+  void* dyT = nullptr;               // T [n_out][cap]
+  int64_t capT = 0;                  // padded row capacity of inT / dyT
+  int max_split = 1;                 // most chunks a worker's weight-gradient reduction is cut into
 };
 
 struct dynb_model {
   int dtype = DYNB_F32;
-  int in_features = 0, n_classes = 0;
-  std::vector<DenseLayer> layers;
+  int in_h = 1, in_w = 1, in_c = 1, n_classes = 0;
+  std::vector<Layer> layers;
   int64_t P = 0, P_pad = 0;
+  int first_param_layer = 0;
 
   bool bound = false;
   float* params = nullptr;
   int max_batch = 0, max_workers = 0;
-  int64_t rows_cap = 0;    // padded row capacity (multiple of 64)
-  std::vector<void*> act, actT;   // act[l]: input of layer l   (l = 0..L-1)
-  std::vector<void*> dy, dyT;     // dy[l]: gradient wrt the output of layer l (after the mask)
+  void* act0 = nullptr;              // packed input, T [B * in_h * in_w][ld]
+  int64_t ld0 = 0;
   float* logits = nullptr;
   float* rowloss = nullptr;
   float* loss = nullptr;
+  float* partial = nullptr;          // scratch of the split weight-gradient reductions
+  int64_t partial_floats = 0;
 };
 
 namespace {
@@ -61,45 +75,75 @@ struct Carver {
   }
 };
 
+int64_t padded_cap(int64_t max_batch, int64_t hw, int max_workers) {
+  return round_up(max_batch * hw + (int64_t)(ROW_PAD - 1) * max_workers, 64);
+}
+
 // Lays out the workspace; with base == nullptr only the size is computed.
 size_t carve(dynb_model* m, void* base, int max_batch, int max_workers) {
   Carver c(base);
   const int es = elem_size(m->dtype);
-  const int64_t rows = round_up((int64_t)max_batch + (int64_t)(ROW_PAD - 1) * max_workers, 64);
-  const size_t L = m->layers.size();
-  m->act.assign(L, nullptr); m->actT.assign(L, nullptr);
-  m->dy.assign(L, nullptr);  m->dyT.assign(L, nullptr);
-  for (size_t l = 0; l < L; ++l) {
-    DenseLayer& D = m->layers[l];
-    m->act[l] = c.take((size_t)rows * D.ld_in * es);
-    m->actT[l] = c.take((size_t)D.n_in * rows * es);
-    m->dy[l] = c.take((size_t)rows * D.ld_out * es);
-    m->dyT[l] = c.take((size_t)D.n_out * rows * es);
-    D.Wn = c.take((size_t)D.n_in * D.ld_out * es);
-    D.Wt = c.take((size_t)D.n_out * D.ld_in * es);
+  m->act0 = c.take((size_t)max_batch * m->in_h * m->in_w * m->ld0 * es);
+  for (size_t l = 0; l < m->layers.size(); ++l) {
+    Layer& L = m->layers[l];
+    const bool last = l + 1 == m->layers.size();
+    const int64_t rows_out = (int64_t)max_batch * L.hw_out;
+    if (!last) L.out = c.take((size_t)rows_out * L.ld_out * es);
+    L.dy = c.take((size_t)rows_out * L.ld_out * es);
+    if (L.has_params) {
+      L.capT = padded_cap(max_batch, L.hw_out, max_workers);
+      L.inT = c.take((size_t)L.wg_rows * L.capT * es);
+      L.dyT = c.take((size_t)L.n_out * L.capT * es);
+      if (L.kind == DYNB_LAYER_DENSE) {
+        L.Wn = c.take((size_t)L.n_in * L.ld_out * es);
+        L.Wt = c.take((size_t)L.n_out * L.ld_in * es);
+      } else {
+        L.Wt = c.take((size_t)L.n_out * L.kf * es);
+        L.Wn = c.take((size_t)L.n_in * L.kd * es);
+      }
+    }
   }
   const int64_t ldc = m->layers.back().ld_out;
-  m->logits = (float*)c.take((size_t)rows * ldc * 4);
-  m->rowloss = (float*)c.take((size_t)rows * 4);
+  m->logits = (float*)c.take((size_t)max_batch * ldc * 4);
+  m->rowloss = (float*)c.take((size_t)max_batch * 4);
   m->loss = (float*)c.take((size_t)DYNB_MAX_WORKERS * 4);
-  if (base) m->rows_cap = rows;
+  // A layer with few weight-gradient tiles has a deep reduction per tile (a convolution sums
+  // over every pixel of every sample): its reduction is cut into chunks that run on separate
+  // workgroups and are summed afterwards in a fixed order.  One scratch area serves all layers.
+  m->partial_floats = 0;
+  for (Layer& L : m->layers) {
+    if (!L.has_params || m->dtype != DYNB_BF16) continue;
+    const int64_t tiles = ((L.n_out + 127) / 128) * (int64_t)((L.wg_rows + 127) / 128);
+    L.max_split = tiles >= 32 ? 1 : (int)(256 / tiles > 64 ? 64 : 256 / tiles);
+    if (L.max_split > 1) {
+      const int64_t need = round_up((int64_t)L.wg_rows * L.n_out, 64) * L.max_split * max_workers;
+      if (need > m->partial_floats) m->partial_floats = need;
+    }
+  }
+  m->partial = (float*)c.take((size_t)m->partial_floats * 4);
   return c.used;
 }
 
-int build_segs(const int32_t* b, int K, Segs& s) {
+// Segments in a row space with `hw` rows per sample.
+int build_segs(const int32_t* b, int K, int hw, Segs& s) {
   s.K = K;
   s.off[0] = 0;
   s.poff[0] = 0;
   for (int k = 0; k < K; ++k) {
     if (b[k] < 0) return fail(DYNB_ERR_BADARG, "negative batch size for worker %d", k);
-    s.off[k + 1] = s.off[k] + b[k];
-    s.poff[k + 1] = s.poff[k] + (int)round_up(b[k], ROW_PAD);
+    s.off[k + 1] = s.off[k] + b[k] * hw;
+    s.poff[k + 1] = s.poff[k] + (int)round_up((int64_t)b[k] * hw, ROW_PAD);
   }
   for (int k = K + 1; k <= DYNB_MAX_WORKERS; ++k) {
     s.off[k] = s.off[K];
     s.poff[k] = s.poff[K];
   }
   return DYNB_OK;
+}
+
+int bad_model(dynb_model* m, int code, const char* msg, int layer) {
+  delete m;
+  return fail(code, "model_create: layer %d: %s", layer, msg);
 }
 
 }  // namespace
@@ -116,33 +160,65 @@ extern "C" int dynb_model_create(const dynb_model_desc* d, dynb_model** out) {
   if (!m) return fail(DYNB_ERR_BADARG, "model_create: out of host memory");
   m->dtype = d->dtype;
   m->n_classes = d->n_classes;
-  m->in_features = d->in_h * d->in_w * d->in_c;
-  int64_t feat = m->in_features, off = 0;
+  m->in_h = d->in_h; m->in_w = d->in_w; m->in_c = d->in_c;
+  bool has_conv = false;
+  for (int l = 0; l < d->n_layers; ++l) has_conv |= d->layers[l].kind != DYNB_LAYER_DENSE;
+  // current activation geometry: h x w pixels of c channels per sample; a dense-only model
+  // treats the whole input as one row of h*w*c features
+  int h = has_conv ? d->in_h : 1, w = has_conv ? d->in_w : 1;
+  int c = has_conv ? d->in_c : d->in_h * d->in_w * d->in_c;
+  if (!has_conv) { m->in_c = c; m->in_h = 1; m->in_w = 1; }
+  m->ld0 = round_up(c, COL_PAD);
+  int64_t off = 0;
+  bool seen_param = false;
   for (int l = 0; l < d->n_layers; ++l) {
-    const dynb_layer_desc& L = d->layers[l];
-    if (L.kind != DYNB_LAYER_DENSE) {
-      delete m;
-      return fail(DYNB_ERR_UNSUPPORTED, "model_create: layer %d: only dense layers are built", l);
+    const dynb_layer_desc& S = d->layers[l];
+    Layer L;
+    L.kind = S.kind;
+    L.relu = S.relu != 0;
+    L.h_in = h; L.w_in = w; L.hw_in = h * w;
+    L.n_in = c;
+    L.ld_in = round_up(c, COL_PAD);
+    if (S.kind == DYNB_LAYER_DENSE) {
+      if (h * w != 1) return bad_model(m, DYNB_ERR_UNSUPPORTED, "dense layer on a spatial input (pool first)", l);
+      if (S.n_in != c || S.n_out < 1) return bad_model(m, DYNB_ERR_BADARG, "n_in does not match the incoming features", l);
+      L.n_out = S.n_out;
+      L.has_params = true;
+      L.wg_rows = L.n_in;
+      L.w_off = off; L.b_off = off + (int64_t)L.n_in * L.n_out;
+      off = L.b_off + L.n_out;
+    } else if (S.kind == DYNB_LAYER_CONV3X3) {
+      if (d->dtype != DYNB_BF16) return bad_model(m, DYNB_ERR_UNSUPPORTED, "convolutions are built for bf16 models only", l);
+      if (S.n_in != c || S.n_out < 1) return bad_model(m, DYNB_ERR_BADARG, "c_in does not match the incoming channels", l);
+      if (S.stride != 1 && S.stride != 2) return bad_model(m, DYNB_ERR_BADARG, "stride must be 1 or 2", l);
+      L.n_out = S.n_out;
+      L.stride = S.stride;
+      h = (h + 2 - 3) / S.stride + 1;
+      w = (w + 2 - 3) / S.stride + 1;
+      L.cin_p = (int)round_up(L.n_in, 8); L.cout_p = (int)round_up(L.n_out, 8);
+      L.kf = (int)round_up(9 * L.cin_p, 64); L.kd = (int)round_up(9 * L.cout_p, 64);
+      L.has_params = true;
+      L.wg_rows = 9 * L.n_in;
+      L.w_off = off; L.b_off = off + (int64_t)9 * L.n_in * L.n_out;
+      off = L.b_off + L.n_out;
+    } else if (S.kind == DYNB_LAYER_GAP) {
+      if (d->dtype != DYNB_BF16) return bad_model(m, DYNB_ERR_UNSUPPORTED, "pooling is built for bf16 models only", l);
+      if (S.relu) return bad_model(m, DYNB_ERR_UNSUPPORTED, "ReLU on a pooling layer", l);
+      L.n_out = c;
+      h = 1; w = 1;
+    } else {
+      return bad_model(m, DYNB_ERR_BADARG, "unknown layer kind", l);
     }
-    if (L.n_in != feat || L.n_out < 1) {
-      delete m;
-      return fail(DYNB_ERR_BADARG, "model_create: layer %d: n_in %d does not match %lld", l,
-                  L.n_in, (long long)feat);
-    }
-    DenseLayer D;
-    D.n_in = L.n_in; D.n_out = L.n_out;
-    D.ld_in = round_up(L.n_in, COL_PAD); D.ld_out = round_up(L.n_out, COL_PAD);
-    D.w_off = off; D.b_off = off + (int64_t)L.n_in * L.n_out;
-    D.relu = L.relu != 0;
-    off = D.b_off + L.n_out;
-    feat = L.n_out;
-    m->layers.push_back(D);
+    L.h_out = h; L.w_out = w; L.hw_out = h * w;
+    L.ld_out = round_up(L.n_out, COL_PAD);
+    c = L.n_out;
+    if (L.has_params && !seen_param) { m->first_param_layer = l; seen_param = true; }
+    m->layers.push_back(L);
   }
-  if (feat != d->n_classes) {
-    delete m;
-    return fail(DYNB_ERR_BADARG, "model_create: last layer has %lld outputs, n_classes is %d",
-                (long long)feat, d->n_classes);
-  }
+  if (!seen_param) return bad_model(m, DYNB_ERR_BADARG, "model has no parameters", 0);
+  const Layer& Z = m->layers.back();
+  if (Z.kind != DYNB_LAYER_DENSE || Z.n_out != d->n_classes || Z.hw_out != 1)
+    return bad_model(m, DYNB_ERR_BADARG, "the last layer must be dense with n_classes outputs", d->n_layers - 1);
   m->P = off;
   m->P_pad = round_up(off, 256);
   *out = m;
@@ -178,9 +254,15 @@ extern "C" size_t dynb_model_workspace_bytes(const dynb_model* m, int32_t max_ba
 extern "C" int dynb_model_sync_weights(dynb_model* m, void* stream) {
   if (!m) return fail(DYNB_ERR_BADARG, "sync_weights: null model");
   if (!m->bound) return fail(DYNB_ERR_STATE, "sync_weights: model not bound");
-  for (DenseLayer& D : m->layers) {
-    int rc = launch_weight_cast(m->dtype, m->params + D.w_off, D.n_in, D.n_out, D.Wn, D.ld_out,
-                                D.Wt, D.ld_in, stream);
+  for (Layer& L : m->layers) {
+    if (!L.has_params) continue;
+    int rc;
+    if (L.kind == DYNB_LAYER_DENSE)
+      rc = launch_weight_cast(m->dtype, m->params + L.w_off, L.n_in, L.n_out, L.Wn, L.ld_out, L.Wt,
+                              L.ld_in, stream);
+    else
+      rc = launch_conv_weight_cast(m->params + L.w_off, L.n_in, L.n_out, L.cin_p, L.cout_p, L.Wt,
+                                   L.kf, L.Wn, L.kd, stream);
     if (rc) return rc;
   }
   return DYNB_OK;
@@ -193,6 +275,10 @@ extern "C" int dynb_model_bind(dynb_model* m, float* params, void* ws, size_t ws
     return fail(DYNB_ERR_BADARG, "bind: bad max_global_batch / max_workers");
   if (((uintptr_t)ws & 255) || ((uintptr_t)params & 15))
     return fail(DYNB_ERR_BADARG, "bind: workspace must be 256-byte and params 16-byte aligned");
+  int64_t max_hw = (int64_t)m->in_h * m->in_w;
+  for (const Layer& L : m->layers) max_hw = L.hw_out > max_hw ? L.hw_out : max_hw;
+  if ((int64_t)max_batch * max_hw > (int64_t)1 << 30)
+    return fail(DYNB_ERR_UNSUPPORTED, "bind: max_global_batch * pixels exceeds 2^30 rows");
   const size_t need = dynb_model_workspace_bytes(m, max_batch, max_workers);
   if (ws_bytes < need)
     return fail(DYNB_ERR_BADARG, "bind: workspace has %zu bytes, %zu needed", ws_bytes, need);
@@ -200,9 +286,8 @@ extern "C" int dynb_model_bind(dynb_model* m, float* params, void* ws, size_t ws
   m->params = params;
   m->max_batch = max_batch;
   m->max_workers = max_workers;
-  // Padding (columns beyond a layer's width, rows beyond a worker's segment) must hold
-  // finite values: it is multiplied by exact zeros.  Clearing once is enough, kernels
-  // never write non-finite padding.
+  // Padding columns (beyond a layer's width) are operands of the GEMMs and are multiplied by
+  // zero weights: they must hold finite values.  Clearing once is enough, no kernel writes them.
   if (hipMemsetAsync(ws, 0, need, (hipStream_t)stream) != hipSuccess)
     return fail(DYNB_ERR_HIP, "bind: hipMemsetAsync failed");
   m->bound = true;
@@ -216,82 +301,150 @@ extern "C" int dynb_forward_backward(dynb_model* m, const float* x, const int32_
   if (K < 1 || K > m->max_workers)
     return fail(DYNB_ERR_BADARG, "forward_backward: K=%d outside [1, %d]", K, m->max_workers);
   if ((uintptr_t)grads & 15) return fail(DYNB_ERR_BADARG, "forward_backward: grads must be 16-byte aligned");
-  Segs s;
-  int rc = build_segs(b, K, s);
+  Segs s1;   // sample-level segments
+  int rc = build_segs(b, K, 1, s1);
   if (rc) return rc;
-  if (s.off[K] > m->max_batch)
-    return fail(DYNB_ERR_BADARG, "forward_backward: sum(b)=%d exceeds max_global_batch=%d",
-                s.off[K], m->max_batch);
-  const int Mp = s.off[K];    // rows of the global batch
-  const int dt = m->dtype;
-  const size_t L = m->layers.size();
-  const int64_t ldT = m->rows_cap;
+  const int B = s1.off[K];
+  if (B > m->max_batch)
+    return fail(DYNB_ERR_BADARG, "forward_backward: sum(b)=%d exceeds max_global_batch=%d", B,
+                m->max_batch);
+  const int dt = m->dtype, es = elem_size(dt);
+  const size_t nL = m->layers.size();
+  std::vector<Segs> segs(nL);   // row-level segments of every layer's output
+  for (size_t l = 0; l < nL; ++l) {
+    rc = build_segs(b, K, m->layers[l].hw_out, segs[l]);
+    if (rc) return rc;
+  }
+  auto in_act = [&](size_t l) -> const void* { return l == 0 ? m->act0 : m->layers[l - 1].out; };
 
-  if (Mp > 0) {
+  if (B > 0) {
     // ---- forward ----
-    rc = launch_pack_rows(dt, x, Mp, m->in_features, m->act[0], m->layers[0].ld_in, stream);
+    rc = launch_pack_rows(dt, x, B * m->in_h * m->in_w, m->in_c, m->act0, m->ld0, stream);
     if (rc) return rc;
-    rc = launch_transpose(dt, m->act[0], m->layers[0].ld_in, m->layers[0].n_in, m->actT[0], ldT, s,
-                          stream);
-    if (rc) return rc;
-    for (size_t l = 0; l < L; ++l) {
-      const DenseLayer& D = m->layers[l];
-      const bool last = l + 1 == L;
-      GemmArgs g = {};
-      g.A = m->act[l]; g.lda = D.ld_in; g.M = Mp;
-      g.B = D.Wt; g.ldb = D.ld_in; g.N = D.n_out;
-      g.K = (int)D.ld_in;
-      g.mode = MODE_FWD;
-      g.bias = m->params + D.b_off;
-      g.relu = D.relu;
-      if (last) { g.Cf = m->logits; g.ldcf = D.ld_out; }
-      else { g.C = m->act[l + 1]; g.ldc = D.ld_out; }
-      rc = launch_gemm(dt, g, s, stream);
-      if (rc) return rc;
-      if (!last) {
-        rc = launch_transpose(dt, m->act[l + 1], D.ld_out, D.n_out, m->actT[l + 1], ldT, s, stream);
+    for (size_t l = 0; l < nL; ++l) {
+      Layer& L = m->layers[l];
+      const bool last = l + 1 == nL;
+      const int rows_out = B * L.hw_out;
+      if (L.kind == DYNB_LAYER_GAP) {
+        rc = launch_gap_forward(in_act(l), L.ld_in, L.hw_in, L.n_in, B, L.out, L.ld_out, stream);
         if (rc) return rc;
+        continue;
       }
+      GemmArgs g = {};
+      g.mode = MODE_FWD;
+      g.M = rows_out;
+      g.N = L.n_out;
+      g.bias = m->params + L.b_off;
+      g.relu = L.relu;
+      if (last) { g.Cf = m->logits; g.ldcf = L.ld_out; }
+      else { g.C = L.out; g.ldc = L.ld_out; }
+      if (L.kind == DYNB_LAYER_DENSE) {
+        rc = launch_transpose(dt, in_act(l), L.ld_in, L.n_in, L.inT, L.capT, segs[l], stream);
+        if (rc) return rc;
+        g.A = in_act(l); g.lda = L.ld_in;
+        g.B = L.Wt; g.ldb = L.ld_in;
+        g.K = (int)L.ld_in;
+        g.alg_flops = 2.0 * rows_out * L.n_in * L.n_out;
+        g.alg_bytes = ((double)rows_out * (L.n_in + L.n_out) + (double)L.n_in * L.n_out) * es;
+      } else {
+        rc = launch_im2col_t(in_act(l), L.ld_in, L.n_in, L.h_in, L.w_in, L.h_out, L.w_out, L.stride,
+                             L.inT, L.capT, segs[l], stream);
+        if (rc) return rc;
+        g.A = in_act(l); g.lda = L.ld_in;
+        g.B = L.Wt; g.ldb = L.kf;
+        g.K = L.kf;
+        g.conv = 1; g.src_h = L.h_in; g.src_w = L.w_in; g.row_h = L.h_out; g.row_w = L.w_out;
+        g.stride = L.stride; g.cp = L.cin_p;
+        g.alg_flops = 2.0 * rows_out * 9 * L.n_in * L.n_out;
+        g.alg_bytes = ((double)B * L.hw_in * L.n_in + (double)rows_out * L.n_out +
+                       9.0 * L.n_in * L.n_out) * es;
+      }
+      rc = launch_gemm(dt, g, s1, stream);
+      if (rc) return rc;
     }
     // ---- loss and dlogits (mean over each worker's own b_k samples) ----
-    const DenseLayer& Z = m->layers[L - 1];
-    rc = launch_softmax_xent(dt, m->logits, Z.ld_out, y, m->n_classes, m->dy[L - 1], Z.ld_out,
-                             (int)Z.ld_out, m->rowloss, s, stream);
+    const Layer& Z = m->layers[nL - 1];
+    rc = launch_softmax_xent(dt, m->logits, Z.ld_out, y, m->n_classes, Z.dy, Z.ld_out,
+                             (int)Z.ld_out, m->rowloss, s1, stream);
     if (rc) return rc;
-    // ---- backward ----
-    for (size_t l = L; l-- > 0;) {
-      const DenseLayer& D = m->layers[l];
-      rc = launch_transpose(dt, m->dy[l], D.ld_out, D.n_out, m->dyT[l], ldT, s, stream);
-      if (rc) return rc;
-      if (l > 0) {  // gradient wrt this layer's input, masked by the ReLU of the layer below
-        const DenseLayer& Dp = m->layers[l - 1];
-        GemmArgs g = {};
-        g.A = m->dy[l]; g.lda = D.ld_out; g.M = Mp;
-        g.B = D.Wn; g.ldb = D.ld_out; g.N = D.n_in;
-        g.K = (int)D.ld_out;
-        g.mode = MODE_DGRAD;
-        g.C = m->dy[l - 1]; g.ldc = Dp.ld_out;
-        if (Dp.relu) { g.mask = m->act[l]; g.ldmask = D.ld_in; }
-        rc = launch_gemm(dt, g, s, stream);
+    // ---- backward: gradient wrt every layer's output, masked by that layer's ReLU ----
+    for (size_t l = nL; l-- > 0;) {
+      Layer& L = m->layers[l];
+      if (L.has_params) {
+        rc = launch_transpose(dt, L.dy, L.ld_out, L.n_out, L.dyT, L.capT, segs[l], stream);
         if (rc) return rc;
       }
+      if ((int)l <= m->first_param_layer) continue;   // nothing below needs a gradient
+      Layer& Lp = m->layers[l - 1];                   // producer of this layer's input
+      const int rows_in = B * L.hw_in;
+      if (L.kind == DYNB_LAYER_GAP) {
+        rc = launch_gap_backward(L.dy, L.ld_out, Lp.out, Lp.ld_out, L.hw_in, L.n_in, B, Lp.relu,
+                                 Lp.dy, Lp.ld_out, stream);
+        if (rc) return rc;
+        continue;
+      }
+      GemmArgs g = {};
+      g.mode = MODE_DGRAD;
+      g.M = rows_in;
+      g.N = L.n_in;
+      g.C = Lp.dy; g.ldc = Lp.ld_out;
+      if (Lp.relu) { g.mask = Lp.out; g.ldmask = Lp.ld_out; }
+      if (L.kind == DYNB_LAYER_DENSE) {
+        g.A = L.dy; g.lda = L.ld_out;
+        g.B = L.Wn; g.ldb = L.ld_out;
+        g.K = (int)L.ld_out;
+        g.alg_flops = 2.0 * rows_in * L.n_in * L.n_out;
+        g.alg_bytes = ((double)rows_in * (L.n_in + L.n_out) + (double)L.n_in * L.n_out) * es;
+      } else {
+        g.A = L.dy; g.lda = L.ld_out;
+        g.B = L.Wn; g.ldb = L.kd;
+        g.K = L.kd;
+        g.conv = 2; g.src_h = L.h_out; g.src_w = L.w_out; g.row_h = L.h_in; g.row_w = L.w_in;
+        g.stride = L.stride; g.cp = L.cout_p;
+        g.alg_flops = 2.0 * B * L.hw_out * 9 * L.n_in * L.n_out;
+        g.alg_bytes = ((double)rows_in * L.n_in + (double)B * L.hw_out * L.n_out +
+                       9.0 * L.n_in * L.n_out) * es;
+      }
+      rc = launch_gemm(dt, g, s1, stream);
+      if (rc) return rc;
     }
   }
   // ---- per-worker weight and bias gradients ----
-  for (size_t l = 0; l < L; ++l) {
-    const DenseLayer& D = m->layers[l];
+  for (size_t l = 0; l < nL; ++l) {
+    Layer& L = m->layers[l];
+    if (!L.has_params) continue;
     GemmArgs g = {};
-    g.A = m->dyT[l]; g.lda = ldT; g.M = D.n_out;
-    g.B = m->actT[l]; g.ldb = ldT; g.N = D.n_in;
     g.mode = MODE_WGRAD;
-    g.Cf = grads + D.w_off; g.ldcf = D.n_out;
+    g.A = L.dyT; g.lda = L.capT; g.M = L.n_out;
+    g.B = L.inT; g.ldb = L.capT; g.N = L.wg_rows;
+    g.Cf = grads + L.w_off; g.ldcf = L.n_out;
     g.group_stride = m->P_pad;
-    rc = launch_gemm(dt, g, s, stream);
+    g.alg_flops = 2.0 * B * L.hw_out * L.wg_rows * L.n_out;
+    g.alg_bytes = (double)K * L.wg_rows * L.n_out * 4 + (double)B * L.hw_out * (L.wg_rows + L.n_out) * es;
+    int deepest = 0;
+    for (int k = 0; k < K; ++k) {
+      const int d = segs[l].poff[k + 1] - segs[l].poff[k];
+      deepest = d > deepest ? d : deepest;
+    }
+    int split = (deepest + 255) / 256;               // chunks of at least four 64-deep stages
+    split = split > L.max_split ? L.max_split : split;
+    if (split > 1) {
+      g.split = split;
+      g.chunk = (int)round_up((deepest + split - 1) / split, 64);
+      g.partial = m->partial;
+      g.partial_stride = round_up((int64_t)L.wg_rows * L.n_out, 64);
+    }
+    rc = launch_gemm(dt, g, segs[l], stream);
     if (rc) return rc;
-    rc = launch_bias_grad(dt, m->dyT[l], ldT, D.n_out, grads + D.b_off, m->P_pad, s, stream);
+    if (split > 1) {
+      rc = launch_wgrad_reduce(m->partial, split, g.partial_stride, (int64_t)L.wg_rows * L.n_out,
+                               grads + L.w_off, m->P_pad, K, stream);
+      if (rc) return rc;
+    }
+    rc = launch_bias_grad(dt, L.dyT, L.capT, L.n_out, grads + L.b_off, m->P_pad, segs[l], stream);
     if (rc) return rc;
   }
-  return launch_finalize(m->rowloss, m->loss, grads, m->P, m->P_pad, s, stream);
+  return launch_finalize(m->rowloss, m->loss, grads, m->P, m->P_pad, s1, stream);
 }
 
 extern "C" int dynb_model_sgd_update(dynb_model* m, const float* g, float lr, float mu,
