@@ -272,8 +272,8 @@ def test_workload1_mlp_fp32_50_steps():
 
 def test_workload2_mlp_bf16_momentum_100_steps():
     g, agg, p, b = run_workload(2, 100)
-    # parameters inherit lr * (gradient error): far inside the 2e-2 allowed for bf16
-    assert max(g, agg) < TOL_EMULATED and p < 1e-3, (g, agg, p)
+    # parameters inherit lr * (gradient error); biases start at zero, so theirs is relative
+    assert max(g, agg, p) < TOL_EMULATED, (g, agg, p)
     assert sum(b) == 1024
 
 
@@ -281,7 +281,7 @@ def test_workload3_cnn_bf16_full_size_steps():
     # full-size steps of the CNN workload (512 images of 32x32x3, b = 300/128/61/23); the
     # 50-step controller trace of this workload is checked bit for bit in tests/test_host.py
     g, agg, p, b = run_workload(3, 2)
-    assert max(g, agg) < TOL_EMULATED and p < 1e-3, (g, agg, p)
+    assert max(g, agg, p) < TOL_EMULATED, (g, agg, p)
     assert b == [300, 128, 61, 23]          # inside the 5 % dead-band: never resized
 
 
@@ -320,4 +320,5 @@ def test_workload4_wide_mlp_full_size_step():
         off += b[k]
     assert worst_relerr(out[:run.P], spec, agg_ref) < TOL_EMULATED
     ref_p = on.sgd_update(p0, agg_ref, cfg["lr"])
-    assert worst_relerr(new_params[:run.P], spec, ref_p) < 1e-4
+    # a bias starts at zero, so after one step it is -lr * (its gradient): same relative error
+    assert worst_relerr(new_params[:run.P], spec, ref_p) < TOL_EMULATED
