@@ -124,6 +124,13 @@ int launch_momentum(float* params, float* v, const float* g, int64_t n, float lr
 int launch_weight_cast(int dtype, const float* W, int R, int C, void* Wn, int64_t ldn, void* Wt,
                        int64_t ldt, void* stream);
 
+// dense weight W fp32 [R][C]: SGD (vel == nullptr) or momentum update from g, fused with the
+// refresh of Wn T [R][ldn] and Wt T [C][ldt]
+int launch_update_cast(int dtype, float* W, const float* g, float* vel, int R, int C, float lr,
+                       float mu, void* Wn, int64_t ldn, void* Wt, int64_t ldt, void* stream);
+// element-wise update of n parameters (any alignment)
+int launch_update_range(float* p, const float* g, float* vel, int64_t n, float lr, float mu,
+                        void* stream);
 // out[g*group_stride + e] = sum_{c < split} partial[(g*split + c)*partial_stride + e], e < n
 int launch_wgrad_reduce(const float* partial, int split, int64_t partial_stride, int64_t n,
                         float* out, int64_t group_stride, int K, void* stream);

@@ -96,6 +96,9 @@ __device__ inline void async_copy_1k(const void* src, uint32_t lds_base) {
 // workers back to back so that the load pipeline never drains between them.
 struct StageCursor {
   int g, kt;
+  int nst, col0, depth;   // of group g: stages, first reduction column, reduction length --
+                          // cached here so that the hot loop does no scalar memory loads (their
+                          // wait counter is shared with the LDS fragment fetches)
 };
 
 template <int BM, int BN, int WM, int WN, int MODE, bool GATHER>
@@ -138,11 +141,25 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
     if (split > 1) return p.partial + (int64_t)g * p.partial_stride;
     return p.Cf + (int64_t)g * p.group_stride;
   };
-  auto stages_of = [&](int g) { return (depth_of(g) + BK - 1) / BK; };
+  // Workgroups walk their groups in different rotations.  In step, every compute unit would
+  // finish a worker at the same moment and all 256 tiles (64 MB) would hit the memory system
+  // together while the MFMAs wait; rotated, the tile stores of some units overlap the MFMAs of
+  // the others.  Position c.g in the walk is group gid(c.g).
+  const int rot = (g_hi - g_lo) > 1 ? (int)((blockIdx.x * 7u) % (unsigned)(g_hi - g_lo)) : 0;
+  auto gid = [&](int pos) {
+    const int r = pos - g_lo + rot, span = g_hi - g_lo;
+    return g_lo + (r >= span ? r - span : r);
+  };
+  auto enter = [&](StageCursor& c) {    // load the cached description of the group at c.g
+    c.kt = 0;
+    c.depth = c.g < g_hi ? depth_of(gid(c.g)) : 0;
+    c.col0 = c.g < g_hi ? col0_of(gid(c.g)) : 0;
+    c.nst = (c.depth + BK - 1) / BK;
+  };
   auto settle = [&](StageCursor& c) {   // first stage at or after c; skips groups without rows
-    while (c.g < g_hi && c.kt >= stages_of(c.g)) {
+    while (c.g < g_hi && c.kt >= c.nst) {
       ++c.g;
-      c.kt = 0;
+      enter(c);
     }
   };
 
@@ -182,8 +199,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
     bool live = true;
     uint32_t kbyte = (uint32_t)k0 * 2;
     if (MODE == MODE_WGRAD) {
-      live = k0 + lgran * 8 < depth_of(c.g);
-      kbyte += (uint32_t)col0_of(c.g) * 2;
+      live = k0 + lgran * 8 < c.depth;
+      kbyte += (uint32_t)c.col0 * 2;
     }
     int kh = 0, kw = 0, ch = 0;
     bool tap_ok = false;
@@ -337,12 +354,14 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
   // and meets the barrier: from there on the other buffer is complete and this one is free,
   // so the stage after next is issued into it, with a whole stage of MFMAs to land.
   // sched_barrier(0) keeps the compiler's scheduler from gathering the MFMAs behind the waits.
-  StageCursor ic = {g_lo, 0};   // next stage to issue
+  StageCursor ic;               // next stage to issue
+  ic.g = g_lo;
+  enter(ic);
   settle(ic);
   StageCursor cc = ic;          // stage being computed
   int stored = g_lo;            // workers whose tile has been written
   if (MODE == MODE_WGRAD)       // workers without rows in front of the first stage: zero gradient
-    for (; stored < (cc.g < g_hi ? cc.g : g_hi); ++stored) store_zero(stored);
+    for (; stored < (cc.g < g_hi ? cc.g : g_hi); ++stored) store_zero(gid(stored));
 
   const bool have0 = ic.g < g_hi;
   if (have0) {
@@ -364,8 +383,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
   }
   int buf = 0;
   while (cc.g < g_hi) {
-    const int g = cc.g, nst = stages_of(g);
-    StageCursor ng = {g + 1, 0};   // first stage of the next worker that has rows
+    const int g = cc.g, nst = cc.nst;
+    StageCursor ng;                // first stage of the next worker that has rows
+    ng.g = g + 1;
+    enter(ng);
     settle(ng);
     const bool later = ng.g < g_hi;
     for (int kt = 0; kt < nst; ++kt) {   // the hot loop: all stages of worker g
@@ -394,9 +415,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
       buf ^= 1;
     }
     if (MODE == MODE_WGRAD) {
-      store_wgrad(g);
+      store_wgrad(gid(g));
       clear_acc();
-      for (stored = g + 1; stored < (later ? ng.g : g_hi); ++stored) store_zero(stored);
+      for (stored = g + 1; stored < (later ? ng.g : g_hi); ++stored) store_zero(gid(stored));
     }
     cc = ng;
   }

@@ -451,8 +451,28 @@ extern "C" int dynb_model_sgd_update(dynb_model* m, const float* g, float lr, fl
                                      float* velocity, void* stream) {
   if (!m || !g) return fail(DYNB_ERR_BADARG, "model_sgd_update: null pointer");
   if (!m->bound) return fail(DYNB_ERR_STATE, "model_sgd_update: model not bound");
-  int rc = velocity ? dynb_sgd_momentum_update(m->params, velocity, g, m->P_pad, lr, mu, stream)
-                    : dynb_sgd_update(m->params, g, m->P_pad, lr, stream);
-  if (rc) return rc;
-  return dynb_model_sync_weights(m, stream);
+  if (((uintptr_t)g & 15) || (velocity && ((uintptr_t)velocity & 15)))
+    return fail(DYNB_ERR_BADARG, "model_sgd_update: pointers must be 16-byte aligned");
+  // one pass per dense weight matrix (update + both 16-bit copies); biases and convolution
+  // weights are small: element-wise update, then the convolution's weight layouts
+  for (Layer& L : m->layers) {
+    if (!L.has_params) continue;
+    float* vw = velocity ? velocity + L.w_off : nullptr;
+    float* vb = velocity ? velocity + L.b_off : nullptr;
+    int rc;
+    if (L.kind == DYNB_LAYER_DENSE) {
+      rc = launch_update_cast(m->dtype, m->params + L.w_off, g + L.w_off, vw, L.n_in, L.n_out, lr,
+                              mu, L.Wn, L.ld_out, L.Wt, L.ld_in, stream);
+    } else {
+      rc = launch_update_range(m->params + L.w_off, g + L.w_off, vw, (int64_t)9 * L.n_in * L.n_out,
+                               lr, mu, stream);
+      if (!rc)
+        rc = launch_conv_weight_cast(m->params + L.w_off, L.n_in, L.n_out, L.cin_p, L.cout_p, L.Wt,
+                                     L.kf, L.Wn, L.kd, stream);
+    }
+    if (rc) return rc;
+    rc = launch_update_range(m->params + L.b_off, g + L.b_off, vb, L.n_out, lr, mu, stream);
+    if (rc) return rc;
+  }
+  return DYNB_OK;
 }
