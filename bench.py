@@ -20,6 +20,28 @@ if ROOT not in sys.path:
 
 PEAK = {"mfma_bf16": 2500.0, "fp32": 157.3, "hbm": 8000.0}   # TFLOP/s, TFLOP/s, GB/s
 
+# HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (scaled by a plain copy of known
+# size; profiles/bench_workload4_rocprofv3.md), valid for workload 4 and only as long as the
+# kernel source they were taken from is unchanged (sha1 of the file, first 12 hex digits).
+MEASURED_TRAFFIC = {
+    "gemm_wgrad": {"bytes_per_launch": 1.1068e9, "source": "paper_2305_12213_amd/csrc/gemm.hip",
+                   "sha1": "a291f01105e2"},
+    "weighted_aggregate": {"bytes_per_launch": 3.7018e9,
+                           "source": "paper_2305_12213_amd/csrc/kernels_stream.hip", "sha1": "966a046ba1f7"},
+}
+
+
+def measured_traffic(kernel, workload):
+    import hashlib
+    m = MEASURED_TRAFFIC.get(kernel)
+    if not m or workload != 4:
+        return None
+    try:
+        sha = hashlib.sha1(open(os.path.join(ROOT, m["source"]), "rb").read()).hexdigest()[:12]
+    except OSError:
+        return None
+    return m["bytes_per_launch"] if sha == m["sha1"] else None
+
 
 def main():
     ap = argparse.ArgumentParser()
@@ -28,6 +50,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
+                    help="also run one plain device copy of MIB mebibytes (a dispatch of known "
+                         "traffic to scale FETCH_SIZE / WRITE_SIZE counter readings by)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on one GPU only (K workers are simulated on it); "
@@ -83,6 +108,13 @@ def main():
     ms_per_step = 1e3 * elapsed / args.steps
     timed_splits = state["trace"][args.warmup:]
 
+    if args.copy_calibration:
+        n = args.copy_calibration * (1 << 20) // 4
+        src = torch.ones(n, device="cuda"); dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+
     # per-kernel-class durations: the same steps again with HIP events around every launch
     binding.profile_reset()
     binding.profile_enable(True)
@@ -114,6 +146,7 @@ def main():
                     "peak": PEAK["hbm"], "unit": "GB/s",
                     "frac": kernels[dominant]["gbps"] / PEAK["hbm"], "traffic": None}
     roofline["avg_launch_ms"] = kernels[dominant]["avg_launch_ms"]
+    roofline["traffic"] = measured_traffic(dominant, cfg["index"])
 
     result = {
         "metric": "samples/s fwd+bwd+weighted-agg+update at ragged K-way b_k",
