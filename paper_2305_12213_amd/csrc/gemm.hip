@@ -292,7 +292,11 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
     float* Cg = tile_base(g);
     float* patch = &sStage[wave * 32 * SPITCH];
     const bool vec_ok = (p.ldcf & 3) == 0 && (((uintptr_t)Cg) & 15) == 0;
+    const bool interior = vec_ok && i0 + BM <= p.M && j0 + BN <= p.N;   // no edge checks needed
     const int rr = lane >> 3, rc = (lane & 7) * 4;
+    const int ib0 = i0 + wm * (BM / WM) + rc, jb0 = j0 + wn * (BN / WN) + rr;
+    float* base = Cg + (int64_t)jb0 * p.ldcf + ib0;
+    const int64_t row8 = (int64_t)8 * p.ldcf;
 #pragma unroll
     for (int a = 0; a < TM; ++a)
 #pragma unroll
@@ -304,20 +308,27 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
           *(f32x4*)&patch[l31 * SPITCH + 8 * q + hi4] = o;
         }
         __builtin_amdgcn_wave_barrier();
-        const int ib = i0 + wm * (BM / WM) + a * 32 + rc;
-        const int jb = j0 + wn * (BN / WN) + b * 32 + rr;
+        float* d = base + (int64_t)(4 * b) * row8 + a * 32;
+        if (interior) {
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          const f32x4 o = *(const f32x4*)&patch[(rr + 8 * t) * SPITCH + rc];
-          const int j = jb + 8 * t;
-          if (j < p.N) {
-            float* dst = Cg + (int64_t)j * p.ldcf + ib;
-            if (vec_ok && ib + 3 < p.M) {
-              __builtin_nontemporal_store(o, (f32x4*)dst);
-            } else {
+          for (int t = 0; t < 4; ++t) {
+            const f32x4 o = *(const f32x4*)&patch[(rr + 8 * t) * SPITCH + rc];
+            __builtin_nontemporal_store(o, (f32x4*)(d + t * row8));
+          }
+        } else {
+          const int ib = ib0 + a * 32;
 #pragma unroll
-              for (int r = 0; r < 4; ++r)
-                if (ib + r < p.M) dst[r] = o[r];
+          for (int t = 0; t < 4; ++t) {
+            const f32x4 o = *(const f32x4*)&patch[(rr + 8 * t) * SPITCH + rc];
+            if (jb0 + b * 32 + 8 * t < p.N) {
+              float* dst = d + t * row8;
+              if (vec_ok && ib + 3 < p.M) {
+                __builtin_nontemporal_store(o, (f32x4*)dst);
+              } else {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                  if (ib + r < p.M) dst[r] = o[r];
+              }
             }
           }
         }
@@ -425,19 +436,24 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
   if (MODE != MODE_WGRAD) {
     const GroupView gv = group_view(p, segs, 0);
     const bool bias_vec = (((uintptr_t)p.bias) & 15) == 0;   // a layer's bias may start anywhere
+    const bool interior = i0 + BM <= p.M && j0 + BN <= p.N && (p.N & 3) == 0;   // no edge checks
+    // a lane walks along its row: consecutive instructions touch neighbouring bytes of a line
 #pragma unroll
     for (int a = 0; a < TM; ++a) {
       const int i = i0 + wm * (BM / WM) + a * 32 + l31;
-      if (i >= p.M) continue;
+      if (!interior && i >= p.M) continue;
+      bf16* crow = p.C ? (bf16*)p.C + (int64_t)i * p.ldc : nullptr;
+      float* frow = p.Cf ? p.Cf + (int64_t)i * p.ldcf : nullptr;
+      const bf16* mrow = p.mask ? (const bf16*)p.mask + (int64_t)i * p.ldmask : nullptr;
 #pragma unroll
       for (int b = 0; b < TN; ++b)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const int jb = j0 + wn * (BN / WN) + b * 32 + 8 * q + hi4;
-          if (jb >= p.N) continue;
+          if (!interior && jb >= p.N) continue;
           float v[4] = {acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2],
                         acc[a][b][4 * q + 3]};
-          if (jb + 3 < p.N) {
+          if (interior || jb + 3 < p.N) {
             if (MODE == MODE_FWD) {
               if (p.bias) {
                 if (bias_vec) {
@@ -452,16 +468,16 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
 #pragma unroll
                 for (int r = 0; r < 4; ++r) v[r] = fmaxf(v[r], 0.f);
               }
-              if (p.Cf) *(float4*)&p.Cf[(int64_t)i * p.ldcf + jb] = make_float4(v[0], v[1], v[2], v[3]);
-            } else if (p.mask) {
-              const bf16x4 mk = *(const bf16x4*)((const bf16*)p.mask + (int64_t)i * p.ldmask + jb);
+              if (frow) *(float4*)&frow[jb] = make_float4(v[0], v[1], v[2], v[3]);
+            } else if (mrow) {
+              const bf16x4 mk = *(const bf16x4*)(mrow + jb);
 #pragma unroll
               for (int r = 0; r < 4; ++r)
                 if (!((float)mk[r] > 0.f)) v[r] = 0.f;
             }
-            if (p.C) {
+            if (crow) {
               bf16x4 o = {(bf16)v[0], (bf16)v[1], (bf16)v[2], (bf16)v[3]};
-              *(bf16x4*)((bf16*)p.C + (int64_t)i * p.ldc + jb) = o;
+              *(bf16x4*)(crow + jb) = o;
             }
           } else {
 #pragma unroll
