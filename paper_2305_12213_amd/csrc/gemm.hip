@@ -56,7 +56,7 @@ __device__ inline void store_one(const GemmArgs& p, const GroupView& gv, int i, 
 // ------------------------------------------------------------------------------------
 // bf16 MFMA kernel
 // ------------------------------------------------------------------------------------
-constexpr int BK = 64;          // reduction elements per stage
+constexpr int BK = 32;          // reduction elements per stage (two MFMA k-steps)
 constexpr int GPR = BK / 8;     // 16-byte granules per tile row
 
 // Workgroup -> tile.  Consecutive workgroup ids are spread round-robin over the 8 XCDs, each
@@ -101,17 +101,50 @@ struct StageCursor {
                           // wait counter is shared with the LDS fragment fetches)
 };
 
-template <int BM, int BN, int WM, int WN, int MODE, bool GATHER>
+// Wait until at most `stages` stages' worth of this wave's LDS-direct copies are pending
+// (copies complete in issue order; PER = copies per wave and stage).
+template <int PER>
+__device__ inline void wait_copies(int stages) {
+  static_assert(7 * PER <= 63, "vmcnt range");
+  switch (stages) {
+    case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+    case 1: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PER) : "memory"); break;
+    case 2: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * PER) : "memory"); break;
+    case 3: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(3 * PER) : "memory"); break;
+    case 4: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(4 * PER) : "memory"); break;
+    case 5: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(5 * PER) : "memory"); break;
+    case 6: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(6 * PER) : "memory"); break;
+    default: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(7 * PER) : "memory"); break;
+  }
+}
+
+// LDS patch area of the weight-gradient epilogue; other modes declare nothing (the 256 x 256
+// forward kernel uses all 160 KB for its stage ring).
+template <int N>
+struct PatchArea {
+  static __device__ float* get() {
+    __shared__ float area[N];
+    return area;
+  }
+};
+template <>
+struct PatchArea<0> {
+  static __device__ float* get() { return nullptr; }
+};
+
+// S = number of LDS stage buffers (ring).
+template <int BM, int BN, int WM, int WN, int MODE, bool GATHER, int S>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Segs segs) {
   constexpr int NW = WM * WN;
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
-  constexpr int LA = BM / 8 / NW, LB = BN / 8 / NW;   // 8-row blocks per wave and stage
-  constexpr int SPITCH = 36;                          // floats per row of a staged 32x32 tile
-  static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0 && GPR == 8, "tile/waves mismatch");
+  constexpr int LA = BM / 16 / NW, LB = BN / 16 / NW;   // 16-row blocks per wave and stage
+  constexpr int SPITCH = 36;                            // floats per row of a staged 32x32 tile
+  static_assert(BM % (16 * NW) == 0 && BN % (16 * NW) == 0 && GPR == 4 && S >= 2 && S <= 8,
+                "tile/waves mismatch");
 
-  __shared__ uint4 sA[2][BM * GPR];
-  __shared__ uint4 sB[2][BN * GPR];
-  __shared__ float sStage[MODE == MODE_WGRAD ? NW * 32 * SPITCH : 4];
+  __shared__ uint4 sA[S][BM * GPR];
+  __shared__ uint4 sB[S][BN * GPR];
+  float* const sStage = PatchArea<MODE == MODE_WGRAD ? NW * 32 * SPITCH : 0>::get();
 
   // groups of this workgroup: [g_lo, g_hi).  A group is a worker, or, when the reduction is
   // split, one chunk of a worker's rows (group id = worker * split + chunk).
@@ -163,18 +196,19 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
     }
   };
 
-  // global -> LDS, asynchronously and without registers: one instruction moves 8 rows x 128
-  // bytes; lane l lands at LDS slot l of the block, i.e. row l/8, physical granule l%8, which
-  // holds logical granule (l%8) ^ (row & 7).  Rows past the matrix edge are clamped (their
-  // products are never stored).  Reduction columns past a worker's depth fetch zeros.
-  const int lrow = lane >> 3, lgran = (lane & 7) ^ (lane >> 3);
+  // global -> LDS, asynchronously and without registers: one instruction moves 16 rows x 64
+  // bytes; lane l lands at LDS slot l of the block, i.e. row l/4, physical granule l%4, which
+  // holds logical granule (l%4) ^ ((row/2) & 3) (conflict-free 16-byte fragment reads).  Rows
+  // past the matrix edge are clamped (their products are never stored).  Reduction columns
+  // past a worker's depth fetch zeros.
+  const int lrow = lane >> 2, lgran = (lane & 3) ^ ((lane >> 3) & 3);
   const char* Ab = (const char*)p.A;
   const char* Bb = (const char*)p.B;
   uint32_t offA[LA], offB[LB];
   int gy[GATHER ? LA : 1], gx[GATHER ? LA : 1];   // gather: the row's pixel coordinates
 #pragma unroll
   for (int u = 0; u < LA; ++u) {
-    int i = i0 + (wave + NW * u) * 8 + lrow;
+    int i = i0 + (wave + NW * u) * 16 + lrow;
     i = i < p.M ? i : p.M - 1;
     if (GATHER) {
       const int hw = p.row_h * p.row_w;
@@ -188,7 +222,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
   }
 #pragma unroll
   for (int u = 0; u < LB; ++u) {
-    int j = j0 + (wave + NW * u) * 8 + lrow;
+    int j = j0 + (wave + NW * u) * 16 + lrow;
     j = j < p.N ? j : p.N - 1;
     offB[u] = (uint32_t)(((int64_t)j * p.ldb + lgran * 8) * 2);
   }
@@ -245,7 +279,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
   // LDS -> MFMA fragments: lane reads row (lane & 31) of a 32-row block, granule 2*kk + lane/32
   const int frow_a = (wm * (BM / WM) + (lane & 31)) * GPR;
   const int frow_b = (wn * (BN / WN) + (lane & 31)) * GPR;
-  const int fsw = lane & 7, fhi = lane >> 5;
+  const int fsw = ((lane & 31) >> 1) & 3, fhi = lane >> 5;
   bf16x8 fa[2][TM], fb[2][TN];   // two register sets, alternating per k-step
   auto lfrag = [&](const uint4* sa, const uint4* sb, int kk, int set) {
     const int g = (kk * 2 + fhi) ^ fsw;
@@ -359,11 +393,13 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
   };
 
   // ---- the stage pipeline ----
-  // One 64-deep stage = 4 MFMA k-steps; fragments are fetched one k-step ahead into the
-  // register set the previous group of MFMAs has just released.  After the last fragment fetch
-  // of a stage every wave waits for its own outstanding LDS-direct loads (the other buffer)
-  // and meets the barrier: from there on the other buffer is complete and this one is free,
-  // so the stage after next is issued into it, with a whole stage of MFMAs to land.
+  // A ring of S stage buffers, each one 32-deep stage (two MFMA k-steps).  Up to S stages are in
+  // flight: the barrier of a stage sits right behind the last fragment fetch from its buffer,
+  // so the buffer is free from there on and the stage S ahead is issued into it -- it has S-1
+  // stages of MFMAs to land, which covers the ~1 us a load takes when every compute unit pulls
+  // its operands through L2 at the same time.  Each wave waits only for its own copies of the
+  // *next* stage before the barrier (copies complete in order).  Fragments are fetched one
+  // k-step ahead into the register set the previous group of MFMAs has released.
   // sched_barrier(0) keeps the compiler's scheduler from gathering the MFMAs behind the waits.
   StageCursor ic;               // next stage to issue
   ic.g = g_lo;
@@ -374,21 +410,17 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
   if (MODE == MODE_WGRAD)       // workers without rows in front of the first stage: zero gradient
     for (; stored < (cc.g < g_hi ? cc.g : g_hi); ++stored) store_zero(gid(stored));
 
-  const bool have0 = ic.g < g_hi;
-  if (have0) {
-    issue(0, ic);
-    ++ic.kt;
-    settle(ic);
-  }
-  const bool have1 = ic.g < g_hi;
-  if (have1) {
-    issue(1, ic);
-    ++ic.kt;
-    settle(ic);
-  }
-  if (have0) {
-    if (have1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LA + LB) : "memory");   // stage 0 landed
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  int ahead = -1;               // stages issued beyond the one being computed
+#pragma unroll
+  for (int f = 0; f < S; ++f)
+    if (ic.g < g_hi) {
+      issue(f, ic);
+      ++ic.kt;
+      settle(ic);
+      ++ahead;
+    }
+  if (ahead >= 0) {
+    wait_copies<LA + LB>(ahead);   // stage 0 has landed
     __syncthreads();
     lfrag(sA[0], sB[0], 0, 0);
   }
@@ -401,29 +433,24 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
     settle(ng);
     const bool later = ng.g < g_hi;
     for (int kt = 0; kt < nst; ++kt) {   // the hot loop: all stages of worker g
-      const bool more1 = kt + 1 < nst || later;   // a next stage exists (already on its way)
-      const bool more2 = ic.g < g_hi;             // and one after it, to be issued now
+      const int nbuf = buf + 1 == S ? 0 : buf + 1;
       lfrag(sA[buf], sB[buf], 1, 1);
       mma(0);
       __builtin_amdgcn_sched_barrier(0);
-      lfrag(sA[buf], sB[buf], 2, 0);
-      mma(1);
-      __builtin_amdgcn_sched_barrier(0);
-      lfrag(sA[buf], sB[buf], 3, 1);
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // my part of the other buffer has landed
+      wait_copies<LA + LB>(ahead > 0 ? ahead - 1 : 0);   // my copies of the next stage landed
       __syncthreads();
       __builtin_amdgcn_sched_barrier(0);
-      if (more2) {
+      if (ic.g < g_hi) {           // refill the buffer this stage has just released
         issue(buf, ic);
         ++ic.kt;
         settle(ic);
+        ++ahead;
       }
-      mma(0);
-      __builtin_amdgcn_sched_barrier(0);
-      if (more1) lfrag(sA[buf ^ 1], sB[buf ^ 1], 0, 0);
+      if (ahead > 0) lfrag(sA[nbuf], sB[nbuf], 0, 0);
       mma(1);
       __builtin_amdgcn_sched_barrier(0);
-      buf ^= 1;
+      buf = nbuf;
+      --ahead;
     }
     if (MODE == MODE_WGRAD) {
       store_wgrad(gid(g));
@@ -433,58 +460,95 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
     cc = ng;
   }
 
-  if (MODE != MODE_WGRAD) {
-    const GroupView gv = group_view(p, segs, 0);
+  if constexpr (MODE != MODE_WGRAD) {
+    // Epilogue.  The stage ring is free now (every wave is past the last barrier and its last
+    // fragment fetch), so each wave passes its 128-column strip, 32 rows at a time, through a
+    // private fp32 patch in LDS: the accumulator layout (4 consecutive columns per lane, 32
+    // rows per instruction) becomes 8 consecutive columns per lane, 4 rows per instruction,
+    // and bias/ReLU/mask, the bf16 conversion and the global accesses run on whole 128-byte
+    // lines.
+    constexpr int CW = BN / WN;              // columns of a wave's strip
+    constexpr int EP = CW + 4;               // patch row pitch in floats
+    static_assert(CW == 128 || CW == 64, "strip width");
+    static_assert((size_t)NW * 32 * EP * 4 <= sizeof(sA), "patch must fit in the A ring");
+    float* patch = (float*)&sA[0][0] + wave * 32 * EP;
+    constexpr int LPR = CW / 8;              // lanes per row in the read-back phase
+    constexpr int RPI = 64 / LPR;            // rows per read-back instruction
+    const int rrow = lane / LPR, rcol = (lane % LPR) * 8;
+    const int jcol = j0 + wn * CW + rcol;    // first of the lane's 8 columns
+    const bool col_ok = jcol + 7 < p.N;
     const bool bias_vec = (((uintptr_t)p.bias) & 15) == 0;   // a layer's bias may start anywhere
-    const bool interior = i0 + BM <= p.M && j0 + BN <= p.N && (p.N & 3) == 0;   // no edge checks
-    // a lane walks along its row: consecutive instructions touch neighbouring bytes of a line
+    float bv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (MODE == MODE_FWD && p.bias) {
+      if (col_ok && bias_vec) {
+        const float4 t0 = *(const float4*)&p.bias[jcol], t1 = *(const float4*)&p.bias[jcol + 4];
+        bv[0] = t0.x; bv[1] = t0.y; bv[2] = t0.z; bv[3] = t0.w;
+        bv[4] = t1.x; bv[5] = t1.y; bv[6] = t1.z; bv[7] = t1.w;
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          if (jcol + e < p.N) bv[e] = p.bias[jcol + e];
+      }
+    }
 #pragma unroll
     for (int a = 0; a < TM; ++a) {
-      const int i = i0 + wm * (BM / WM) + a * 32 + l31;
-      if (!interior && i >= p.M) continue;
-      bf16* crow = p.C ? (bf16*)p.C + (int64_t)i * p.ldc : nullptr;
-      float* frow = p.Cf ? p.Cf + (int64_t)i * p.ldcf : nullptr;
-      const bf16* mrow = p.mask ? (const bf16*)p.mask + (int64_t)i * p.ldmask : nullptr;
 #pragma unroll
       for (int b = 0; b < TN; ++b)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-          const int jb = j0 + wn * (BN / WN) + b * 32 + 8 * q + hi4;
-          if (!interior && jb >= p.N) continue;
-          float v[4] = {acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2],
-                        acc[a][b][4 * q + 3]};
-          if (interior || jb + 3 < p.N) {
-            if (MODE == MODE_FWD) {
-              if (p.bias) {
-                if (bias_vec) {
-                  const float4 bv = *(const float4*)&p.bias[jb];
-                  v[0] += bv.x; v[1] += bv.y; v[2] += bv.z; v[3] += bv.w;
-                } else {
+          const f32x4 o = {acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2],
+                           acc[a][b][4 * q + 3]};
+          *(f32x4*)&patch[l31 * EP + b * 32 + 8 * q + hi4] = o;
+        }
+      __builtin_amdgcn_wave_barrier();
 #pragma unroll
-                  for (int r = 0; r < 4; ++r) v[r] += p.bias[jb + r];
-                }
-              }
-              if (p.relu) {
+      for (int t = 0; t < 32 / RPI; ++t) {
+        const int r = rrow + RPI * t;
+        const int i = i0 + wm * (BM / WM) + a * 32 + r;
+        const f32x4 lo = *(const f32x4*)&patch[r * EP + rcol];
+        const f32x4 hi = *(const f32x4*)&patch[r * EP + rcol + 4];
+        if (i >= p.M || jcol >= p.N) continue;
+        float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        if (MODE == MODE_FWD) {
 #pragma unroll
-                for (int r = 0; r < 4; ++r) v[r] = fmaxf(v[r], 0.f);
-              }
-              if (frow) *(float4*)&frow[jb] = make_float4(v[0], v[1], v[2], v[3]);
-            } else if (mrow) {
-              const bf16x4 mk = *(const bf16x4*)(mrow + jb);
+          for (int e = 0; e < 8; ++e) v[e] += bv[e];
+          if (p.relu) {
 #pragma unroll
-              for (int r = 0; r < 4; ++r)
-                if (!((float)mk[r] > 0.f)) v[r] = 0.f;
-            }
-            if (crow) {
-              bf16x4 o = {(bf16)v[0], (bf16)v[1], (bf16)v[2], (bf16)v[3]};
-              *(bf16x4*)(crow + jb) = o;
-            }
-          } else {
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-              if (jb + r < p.N) store_one<bf16, MODE>(p, gv, i, jb + r, v[r]);
+            for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
           }
         }
+        if (col_ok) {
+          if (MODE == MODE_DGRAD && p.mask) {
+            const bf16x8 mk = *(const bf16x8*)((const bf16*)p.mask + (int64_t)i * p.ldmask + jcol);
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+              if (!((float)mk[e] > 0.f)) v[e] = 0.f;
+          }
+          if (MODE == MODE_FWD && p.Cf) {
+            float* dst = p.Cf + (int64_t)i * p.ldcf + jcol;
+            *(float4*)dst = make_float4(v[0], v[1], v[2], v[3]);
+            *(float4*)(dst + 4) = make_float4(v[4], v[5], v[6], v[7]);
+          }
+          if (p.C) {
+            const bf16x8 o = {(bf16)v[0], (bf16)v[1], (bf16)v[2], (bf16)v[3],
+                              (bf16)v[4], (bf16)v[5], (bf16)v[6], (bf16)v[7]};
+            *(bf16x8*)((bf16*)p.C + (int64_t)i * p.ldc + jcol) = o;
+          }
+        } else {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const int j = jcol + e;
+            if (j >= p.N) continue;
+            float w = v[e];
+            if (MODE == MODE_DGRAD && p.mask &&
+                !((float)((const bf16*)p.mask)[(int64_t)i * p.ldmask + j] > 0.f))
+              w = 0.f;
+            if (MODE == MODE_FWD && p.Cf) p.Cf[(int64_t)i * p.ldcf + j] = w;
+            if (p.C) ((bf16*)p.C)[(int64_t)i * p.ldc + j] = (bf16)w;
+          }
+        }
+      }
+      __builtin_amdgcn_wave_barrier();
     }
   }
 }
@@ -541,7 +605,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs p, Segs segs) {
     }
 }
 
-template <int BM, int BN, int WM, int WN>
+template <int BM, int BN, int WM, int WN, int S_PLAIN, int S_WGRAD>
 void launch_bf16(GemmArgs a, const Segs& s, hipStream_t st) {
   const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
   int gy = 1;
@@ -558,13 +622,13 @@ void launch_bf16(GemmArgs a, const Segs& s, hipStream_t st) {
   dim3 grid(tiles, gy, 1), block(WM * WN * 64);
   switch (a.mode) {
     case MODE_FWD:
-      hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, MODE_FWD, false>), grid, block, 0, st, a, s);
+      hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, MODE_FWD, false, S_PLAIN>), grid, block, 0, st, a, s);
       break;
     case MODE_DGRAD:
-      hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, MODE_DGRAD, false>), grid, block, 0, st, a, s);
+      hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, MODE_DGRAD, false, S_PLAIN>), grid, block, 0, st, a, s);
       break;
     default:
-      hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, MODE_WGRAD, false>), grid, block, 0, st, a, s);
+      hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, MODE_WGRAD, false, S_WGRAD>), grid, block, 0, st, a, s);
   }
 }
 
@@ -574,9 +638,9 @@ void launch_bf16_gather(GemmArgs a, const Segs& s, hipStream_t st) {
   a.groups_per_block = 1;
   dim3 grid(tiles, 1, 1), block(256);
   if (a.mode == MODE_FWD)
-    hipLaunchKernelGGL((gemm_bf16_kernel<128, 128, 2, 2, MODE_FWD, true>), grid, block, 0, st, a, s);
+    hipLaunchKernelGGL((gemm_bf16_kernel<128, 128, 2, 2, MODE_FWD, true, 8>), grid, block, 0, st, a, s);
   else
-    hipLaunchKernelGGL((gemm_bf16_kernel<128, 128, 2, 2, MODE_DGRAD, true>), grid, block, 0, st, a, s);
+    hipLaunchKernelGGL((gemm_bf16_kernel<128, 128, 2, 2, MODE_DGRAD, true, 8>), grid, block, 0, st, a, s);
 }
 
 void launch_f32(const GemmArgs& a, const Segs& s, int groups, hipStream_t st) {
@@ -614,9 +678,9 @@ int launch_gemm(int dtype, const GemmArgs& a, const Segs& s, void* stream) {
     // tiles to occupy 256 compute units
     const int64_t big = (int64_t)((a.M + 255) / 256) * ((a.N + 255) / 256);
     if (big >= 192)
-      launch_bf16<256, 256, 2, 2>(a, s, (hipStream_t)stream);
+      launch_bf16<256, 256, 2, 2, 5, 4>(a, s, (hipStream_t)stream);   // 160 KB / 128 + 18 KB of LDS
     else
-      launch_bf16<128, 128, 2, 2>(a, s, (hipStream_t)stream);
+      launch_bf16<128, 128, 2, 2, 8, 8>(a, s, (hipStream_t)stream);
   } else
     launch_f32(a, s, groups, (hipStream_t)stream);
   return hipGetLastError() == hipSuccess ? DYNB_OK : fail(DYNB_ERR_HIP, "gemm launch failed");
