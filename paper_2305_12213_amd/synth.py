@@ -172,6 +172,33 @@ def iteration_times(b, speeds):
     return [v if v is not None else fill for v in t]
 
 
+def plant_times(b, speeds, overhead=None, knee=None, knee_penalty=1.0, noise=0.0, seed=0,
+                step=0):
+    """Synthetic plant with the effects the linear model leaves out:
+
+        t_k = (c_k + b_k / s_k * (knee_penalty if b_k > knee_k else 1)) * (1 + noise * u_k)
+
+    c_k is a fixed per-iteration overhead, knee_k the batch size past which worker k's
+    throughput falls (memory exhaustion), u_k uniform in [-1, 1) drawn from (seed, step).
+    An idle worker reports the mean time of the busy ones.
+    """
+    K = len(b)
+    c = [0.0] * K if overhead is None else [float(v) for v in overhead]
+    u = np.random.Generator(np.random.PCG64([int(seed), 5, int(step)])).uniform(-1.0, 1.0, size=K)
+    t = []
+    for k in range(K):
+        if b[k] <= 0:
+            t.append(None)
+            continue
+        work = float(b[k]) / float(speeds[k])
+        if knee is not None and knee[k] is not None and b[k] > knee[k]:
+            work = work * float(knee_penalty)
+        t.append((c[k] + work) * (1.0 + float(noise) * float(u[k])))
+    busy = [v for v in t if v is not None]
+    fill = (sum(busy) / len(busy)) if busy else 1.0
+    return [v if v is not None else fill for v in t]
+
+
 def ragged_split(total, K, seed):
     """A random K-way split of `total` (entries may be 0), for parity tests."""
     rng = np.random.Generator(np.random.PCG64([int(seed), 3]))

@@ -212,3 +212,141 @@ def test_ewma_closed_form():
     for n in range(1, 6):
         mu = oc.ewma_update(mu, [1.0], 0.3, reset=False)
         assert abs(mu[0] - (1 - 0.7 ** n)) < 1e-12
+
+
+# ---------------------------------------------------------------------------------------------
+# DynamicBatcher: the controller with its state (subsection "Control stability")
+# ---------------------------------------------------------------------------------------------
+def test_ewma_since_last_readjustment_matches_unrolled_sum():
+    # mu after n iterations without readjustment = alpha * sum_i (1-alpha)^i t_{n-i} + (1-alpha)^(n-1) t_1
+    rng = np.random.default_rng(5)
+    alpha = 0.3
+    d = oc.DynamicBatcher([40, 40, 40], 120, ewma_alpha=alpha, deadband=10.0)   # never resizes
+    ts = rng.uniform(1.0, 2.0, size=(7, 3))
+    for n in range(1, 8):
+        d.observe(list(ts[n - 1]))
+        want = (1 - alpha) ** (n - 1) * ts[0]
+        for i in range(1, n):
+            want = want + alpha * (1 - alpha) ** (n - 1 - i) * ts[i]
+        np.testing.assert_allclose(d.mu, want, rtol=1e-13)
+    assert d.readjustments == 0 and d.observations == 7
+
+
+def test_ewma_restarts_after_a_readjustment():
+    d = oc.DynamicBatcher([50, 50], 100, ewma_alpha=0.25)
+    d.observe([10.0, 30.0])                      # large error: resizes
+    assert d.readjustments == 1 and d.observations == 0
+    d.observe([7.0, 9.0])
+    assert d.mu == [7.0, 9.0]                    # first iteration after the readjustment: no memory
+    d2 = oc.DynamicBatcher([50, 50], 100, ewma_alpha=0.25, deadband=10.0)
+    d2.observe([10.0, 30.0]); d2.observe([7.0, 9.0])
+    assert d2.mu == [0.25 * 7.0 + 0.75 * 10.0, 0.25 * 9.0 + 0.75 * 30.0]
+
+
+def test_goal_state_equal_iteration_times_under_affine_time_model():
+    # with t_k = c_k + b_k/s_k the goal t_i = t_j has the solution b_k = s_k (T - c_k) with
+    # sum_k b_k = G; the controller must settle there (dead-band 0: within rounding)
+    s = [1.0, 2.0, 5.0, 8.0]; c = [3.0, 1.0, 2.0, 0.5]; G = 4000
+    T = (G + sum(sk * ck for sk, ck in zip(s, c))) / sum(s)
+    want = [sk * (T - ck) for sk, ck in zip(s, c)]
+    d = oc.DynamicBatcher([G // 4] * 4, G, ewma_alpha=1.0, deadband=0.0)
+    b = list(d.b)
+    for it in range(40):
+        b = d.observe(synth.plant_times(b, s, overhead=c))
+    assert sum(b) == G
+    assert max(abs(bk - wk) for bk, wk in zip(b, want)) <= 2.0, (b, want)
+    t = synth.plant_times(b, s, overhead=c)
+    assert (max(t) - min(t)) / min(t) < 5e-3
+
+
+def test_timeline_converges_within_two_readjustments_with_deadband():
+    # Fig. "Batch sizes quickly converge within two adjustments": three workers, equal start,
+    # a fixed overhead makes the proportional rule inexact, so the first step lands near the
+    # goal and the second finishes; the dead-band then holds the sizes.
+    s = [3.0, 9.0, 18.0]; c = [0.4, 0.4, 0.4]; G = 300
+    d = oc.DynamicBatcher([100, 100, 100], G, ewma_alpha=0.5, deadband=0.05)
+    b = list(d.b); history = []
+    for it in range(30):
+        b = d.observe(synth.plant_times(b, s, overhead=c))
+        history.append(list(b))
+    assert 1 <= d.readjustments <= 2
+    assert history[2:] == [history[2]] * 28                 # flat after the second iteration
+    t = synth.plant_times(b, s, overhead=c)
+    assert (max(t) - min(t)) / (sum(t) / 3) < 0.10          # inside the dead-band's resolution
+
+
+def test_timeline_oscillates_without_deadband_under_noise():
+    # Fig. "Oscillations in mini-batch sizes without dead-banding": the same loop chases the
+    # noise forever with a zero dead-band and stops after the start-up with the paper's 0.05.
+    s = [3.0, 5.0, 12.0]; G = 600
+    def run(deadband, alpha):
+        # (the learnt upper bounds are off: with zero tolerance they would read the noise as
+        # throughput drops and freeze the sizes, which is not what the figure shows)
+        d = oc.DynamicBatcher([200, 200, 200], G, ewma_alpha=alpha, deadband=deadband,
+                              adaptive_b_max=False)
+        b = list(d.b)
+        for it in range(200):
+            b = d.observe(synth.plant_times(b, s, noise=0.02, seed=77, step=it))
+        return d.readjustments
+    assert run(0.0, 1.0) > 100
+    assert run(0.05, 1.0) <= 3
+    assert run(0.05, 0.5) <= 2
+
+
+def test_dynamic_heterogeneity_is_tracked_and_ewma_spans_only_the_quiet_interval():
+    G = 1200
+    d = oc.DynamicBatcher([300] * 4, G, ewma_alpha=0.5, deadband=0.05)
+    s = [1.0, 1.0, 2.0, 4.0]
+    b = list(d.b)
+    for it in range(10):
+        b = d.observe(synth.plant_times(b, s))
+    assert b == [150, 150, 300, 600] and d.readjustments == 1
+    s = [1.0, 0.25, 2.0, 4.0]                               # worker 1 loses 3/4 of its speed
+    n0 = d.readjustments
+    for it in range(20):
+        b = d.observe(synth.plant_times(b, s))
+    want = [G * v / sum(s) for v in s]
+    assert max(abs(bk - wk) / wk for bk, wk in zip(b, want)) < 0.06
+    assert 1 <= d.readjustments - n0 <= 6                   # smoothed: a few steps, then quiet
+    for it in range(20):
+        assert d.observe(synth.plant_times(b, s)) == b
+
+
+def test_throughput_knee_hand_worked_trace():
+    rows = read_rows("throughput_knee_example.txt")
+    d = oc.DynamicBatcher([50, 50], 100, ewma_alpha=1.0, deadband=0.05, b_min=1, b_max=100)
+    b = list(d.b)
+    for it, want_b, want_hi in rows:
+        b = d.observe(synth.plant_times(b, [1.0, 3.0], knee=[None, 60], knee_penalty=2.0))
+        assert b == [int(v) for v in want_b], (it, b)
+        assert d.b_hi == [int(v) for v in want_hi], (it, d.b_hi)
+
+
+def test_learnt_bound_never_breaks_the_global_batch_and_only_shrinks():
+    rng = np.random.default_rng(11)
+    for trial in range(30):
+        K = int(rng.integers(2, 7)); G = int(rng.integers(K * 20, K * 200))
+        s = list(rng.uniform(0.5, 8.0, K))
+        knee = [int(v) for v in rng.integers(G // K // 2, G, K)]
+        d = oc.DynamicBatcher(synth.ragged_split(G, K, trial), G, ewma_alpha=0.5, b_min=1)
+        b = list(d.b); hi_prev = list(d.b_hi)
+        for it in range(25):
+            b = d.observe(synth.plant_times(b, s, knee=knee, knee_penalty=3.0, noise=0.01,
+                                            seed=trial, step=it))
+            assert sum(b) == G and all(1 <= b[k] <= d.b_hi[k] for k in range(K))
+            assert all(d.b_hi[k] <= hi_prev[k] for k in range(K)) and sum(d.b_hi) >= G
+            hi_prev = list(d.b_hi)
+
+
+def test_min_observations_delays_the_first_readjustment():
+    d = oc.DynamicBatcher([50, 50], 100, ewma_alpha=0.5, min_observations=3)
+    assert d.observe([10.0, 30.0]) == [50, 50]
+    assert d.observe([10.0, 30.0]) == [50, 50]
+    assert d.observe([10.0, 30.0]) == [75, 25]
+
+
+def test_per_worker_bounds_in_the_stateless_step():
+    b = oc.controller_step([1.0, 1.0, 4.0], [40, 40, 40], 120, deadband=0.0, b_hi=[45, 120, 120])
+    assert sum(b) == 120 and b[0] <= 45 and b[2] < 40
+    with pytest.raises(oc.ControllerError):
+        oc.controller_step([1.0, 1.0], [50, 50], 100, b_hi=[40, 40])
