@@ -169,6 +169,52 @@ int dynb_model_sgd_update(dynb_model* m, const float* g, float lr, float mu, flo
 int dynb_controller_step(const double* iter_times, const int32_t* b, int32_t K,
                          int32_t global_batch, const dynb_gains* gains, int32_t* b_next);
 
+/* ---- the controller with its state between iterations ---------------------------
+ * Subsection "Control stability": the smoothed iteration times are an EWMA over the
+ * iterations since the last readjustment, and a worker whose throughput fell after its
+ * batch size was raised keeps the size it had before as its upper bound.  The object
+ * holds the sizes b[K], the smoothed times mu[K], the learnt upper bounds and the sizes
+ * and throughputs replaced by the last readjustment.  Host memory only; not thread-safe.
+ *   adaptive_b_max   != 0: learn upper bounds from throughput drops
+ *   drop_tolerance   relative drop of the smoothed throughput b_k/mu_k that counts as a
+ *                    drop (0: any); should exceed the noise of the iteration times
+ *   min_observations iterations that must have been smoothed since the last readjustment
+ *                    before the next one is considered (>= 1; 1 = check every iteration) */
+typedef struct {
+  dynb_gains gains;
+  double drop_tolerance;
+  int32_t min_observations;
+  int32_t adaptive_b_max;
+} dynb_controller_config;
+
+typedef struct dynb_controller dynb_controller;
+
+/* b0[K] (host) are the starting sizes, sum = global_batch.  Errors as for
+ * dynb_controller_step, plus ewma_alpha outside [0,1], drop_tolerance < 0 or not finite,
+ * min_observations < 1.  *out is owned by the caller (dynb_controller_destroy). */
+int dynb_controller_create(const dynb_controller_config* cfg, const int32_t* b0, int32_t K,
+                           int32_t global_batch, dynb_controller** out);
+void dynb_controller_destroy(dynb_controller* c);
+
+/* Feed the iteration times t[K] > 0 (host) of the iteration that just ran with the current
+ * sizes; b_next[K] (host) receives the sizes for the next iteration, *resized (may be null)
+ * whether they changed.  In order: (1) mu_k = t_k on the first iteration after a
+ * readjustment, else mu_k = alpha t_k + (1 - alpha) mu_k; (2) for a worker whose size was
+ * raised at the last readjustment from b_old and whose throughput b_k/mu_k is now below
+ * (1 - drop_tolerance) times the throughput it had then: upper bound = b_old, unless the
+ * bounds could then no longer hold the global batch (bounds only shrink); (3) once
+ * min_observations iterations are smoothed, or at once if a size exceeds its bound: the step
+ * of dynb_controller_step on mu with the per-worker bounds (a size above its bound overrides
+ * the dead-band); (4) after a change the smoothing restarts.  Bit-reproducible like
+ * dynb_controller_step.  DYNB_ERR_BADARG: null pointer, t_k not finite or <= 0 (state
+ * unchanged). */
+int dynb_controller_observe(dynb_controller* c, const double* iter_times, int32_t* b_next,
+                            int32_t* resized);
+
+/* Copy out the state; every output pointer may be null.  b, mu, b_hi: K entries (host). */
+int dynb_controller_read(const dynb_controller* c, int32_t* b, double* mu, int32_t* b_hi,
+                         int32_t* observations, int32_t* readjustments);
+
 /* Exponentially weighted moving average of iteration times since the last
  * readjustment ("Exponential Smoothing"): reset != 0 sets mu = t, otherwise
  * mu_k = alpha * t_k + (1 - alpha) * mu_k.  mu is caller-owned state. */

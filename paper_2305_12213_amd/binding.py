@@ -25,6 +25,8 @@ SYMBOLS = [
     "dynb_model_sync_weights", "dynb_model_worker_loss", "dynb_model_read_worker_loss", "dynb_forward_backward",
     "dynb_weighted_aggregate", "dynb_sgd_update", "dynb_sgd_momentum_update",
     "dynb_model_sgd_update", "dynb_controller_step", "dynb_ewma_update", "dynb_static_allocate",
+    "dynb_controller_create", "dynb_controller_destroy", "dynb_controller_observe",
+    "dynb_controller_read",
     "dynb_profile_enable", "dynb_profile_reset", "dynb_profile_collect",
     "dynb_profile_num_classes", "dynb_profile_name", "dynb_profile_get",
 ]
@@ -50,6 +52,11 @@ class ModelDesc(C.Structure):
 class Gains(C.Structure):
     _fields_ = [("kp", C.c_double), ("deadband", C.c_double), ("ewma_alpha", C.c_double),
                 ("b_min", C.c_int32), ("b_max", C.c_int32)]
+
+
+class ControllerConfig(C.Structure):
+    _fields_ = [("gains", Gains), ("drop_tolerance", C.c_double),
+                ("min_observations", C.c_int32), ("adaptive_b_max", C.c_int32)]
 
 
 _lib = None
@@ -88,6 +95,11 @@ def load():
         "dynb_controller_step": (C.c_int, [pf64, pi32, i32, i32, C.POINTER(Gains), pi32]),
         "dynb_ewma_update": (C.c_int, [pf64, pf64, i32, f64, i32]),
         "dynb_static_allocate": (C.c_int, [pf64, i32, i32, pi32]),
+        "dynb_controller_create": (C.c_int, [C.POINTER(ControllerConfig), pi32, i32, i32,
+                                             C.POINTER(vp)]),
+        "dynb_controller_destroy": (None, [vp]),
+        "dynb_controller_observe": (C.c_int, [vp, pf64, pi32, pi32]),
+        "dynb_controller_read": (C.c_int, [vp, pi32, pf64, pi32, pi32, pi32]),
         "dynb_profile_enable": (C.c_int, [i32]),
         "dynb_profile_reset": (C.c_int, []),
         "dynb_profile_collect": (C.c_int, []),
@@ -252,6 +264,42 @@ def static_allocate(X, b0):
     out = (C.c_int32 * K)()
     _check(load().dynb_static_allocate(_f64(X), K, int(b0), out))
     return [int(v) for v in out]
+
+
+class Controller:
+    """Handle of the stateful controller (dynb_controller_*)."""
+
+    def __init__(self, b0, global_batch, gains, drop_tolerance=0.0, min_observations=1,
+                 adaptive_b_max=True):
+        g = gains if isinstance(gains, Gains) else make_gains(**gains)
+        cfg = ControllerConfig(g, float(drop_tolerance), int(min_observations),
+                               int(bool(adaptive_b_max)))
+        self.K = len(b0)
+        self.handle = C.c_void_p()
+        _check(load().dynb_controller_create(C.byref(cfg), _i32(b0), self.K, int(global_batch),
+                                             C.byref(self.handle)))
+
+    def observe(self, iter_times):
+        if len(iter_times) != self.K:
+            raise ValueError("one iteration time per worker")
+        out = (C.c_int32 * self.K)()
+        resized = C.c_int32()
+        _check(load().dynb_controller_observe(self.handle, _f64(iter_times), out,
+                                              C.byref(resized)))
+        return [int(v) for v in out], bool(resized.value)
+
+    def read(self):
+        b = (C.c_int32 * self.K)(); mu = (C.c_double * self.K)(); hi = (C.c_int32 * self.K)()
+        obs = C.c_int32(); adj = C.c_int32()
+        _check(load().dynb_controller_read(self.handle, b, mu, hi, C.byref(obs), C.byref(adj)))
+        return {"b": [int(v) for v in b], "mu": [float(v) for v in mu],
+                "b_hi": [int(v) for v in hi], "observations": obs.value,
+                "readjustments": adj.value}
+
+    def __del__(self):
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.dynb_controller_destroy(self.handle)
+            self.handle = None
 
 
 def profile_enable(on):

@@ -140,3 +140,78 @@ def test_streaming_calls_validate_arguments_without_a_gpu():
         binding.sgd_update(0, 256, 8, 0.1)
     with pytest.raises(binding.DynbError):
         binding.sgd_momentum_update(256, 0, 256, 8, 0.1, 0.9)
+
+
+# ---- the stateful controller against the checker's DynamicBatcher, bit for bit ----
+def _drive_both(b0, G, s, steps, plant_kw, **kw):
+    ref = oc.DynamicBatcher(b0, G, **kw)
+    gains = dict(kp=kw.get("kp", 1.0), deadband=kw.get("deadband", 0.05),
+                 ewma_alpha=kw.get("ewma_alpha", 0.5), b_min=kw.get("b_min", 1),
+                 b_max=kw.get("b_max", G) if kw.get("b_max") is not None else G)
+    dev = binding.Controller(b0, G, gains, drop_tolerance=kw.get("drop_tolerance", 0.0),
+                             min_observations=kw.get("min_observations", 1),
+                             adaptive_b_max=kw.get("adaptive_b_max", True))
+    b = list(b0)
+    for it in range(steps):
+        if callable(s):
+            speeds = s(it)
+        else:
+            speeds = s
+        t = synth.plant_times(b, speeds, step=it, **plant_kw)
+        want = ref.observe(t)
+        got, resized = dev.observe(t)
+        st = dev.read()
+        assert got == want, (it, got, want)
+        assert resized == (want != b)
+        assert st["b"] == want and st["b_hi"] == ref.b_hi and st["mu"] == ref.mu   # exact doubles
+        assert st["observations"] == ref.observations and st["readjustments"] == ref.readjustments
+        b = want
+    return ref
+
+
+def test_stateful_controller_hand_worked_knee_trace():
+    ref = _drive_both([50, 50], 100, [1.0, 3.0], 6, dict(knee=[None, 60], knee_penalty=2.0),
+                      ewma_alpha=1.0, b_max=100)
+    assert ref.b == [50, 50] and ref.b_hi == [100, 50]
+
+
+def test_stateful_controller_matches_checker_on_random_plants():
+    rng = np.random.default_rng(2305)
+    total_adj = 0
+    for trial in range(60):
+        K = int(rng.integers(1, 17)); G = int(rng.integers(K * 8, K * 600))
+        s = [float(v) for v in rng.uniform(0.3, 12.0, K)]
+        c = [float(v) for v in rng.uniform(0.0, 2.0, K)]
+        knee = [int(v) for v in rng.integers(max(2, G // K // 2), G + 1, K)]
+        b_min = int(rng.integers(0, 3))
+        b_max = None if trial % 3 else max(-(-G // K) + 1, int(G * 0.6))
+        kw = dict(kp=float(rng.choice([1.0, 0.5, 0.8])), deadband=float(rng.choice([0.0, 0.02, 0.05])),
+                  ewma_alpha=float(rng.choice([1.0, 0.5, 0.25])), b_min=b_min, b_max=b_max,
+                  drop_tolerance=float(rng.choice([0.0, 0.05])),
+                  min_observations=int(rng.integers(1, 4)), adaptive_b_max=bool(trial % 4))
+        b0 = synth.ragged_split(G, K, 100 + trial)
+        if b_min and min(b0) < b_min or b_max and max(b0) > b_max:
+            b0 = [G // K + (1 if k < G % K else 0) for k in range(K)]
+        def speeds(it, s=s, trial=trial):
+            return [v * (0.25 if (it >= 15 and k == trial % len(s)) else 1.0) for k, v in enumerate(s)]
+        ref = _drive_both(b0, G, speeds, 30,
+                          dict(overhead=c, knee=knee, knee_penalty=2.5, noise=0.02, seed=trial), **kw)
+        total_adj += ref.readjustments
+    assert total_adj > 60
+
+
+def test_stateful_controller_rejects_bad_input():
+    g = dict(kp=1.0, deadband=0.05, ewma_alpha=0.5, b_min=1, b_max=100)
+    with pytest.raises(binding.DynbError):
+        binding.Controller([50, 49], 100, g)
+    with pytest.raises(binding.DynbError):
+        binding.Controller([50, 50], 100, dict(g, ewma_alpha=1.5))
+    with pytest.raises(binding.DynbError):
+        binding.Controller([50, 50], 100, g, min_observations=0)
+    with pytest.raises(binding.DynbError):
+        binding.Controller([50, 50], 100, g, drop_tolerance=-0.1)
+    c = binding.Controller([50, 50], 100, g)
+    with pytest.raises(binding.DynbError):
+        c.observe([1.0, float("nan")])
+    assert c.read()["observations"] == 0            # state untouched by the rejected call
+    assert c.observe([1.0, 1.0]) == ([50, 50], False)
