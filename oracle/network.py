@@ -280,5 +280,36 @@ def momentum_update(params, velocity, g, lr, mu):
     return p, v
 
 
+def adam_update(params, m, v, g, lr, beta1=0.9, beta2=0.999, eps=1e-8, t=1):
+    """Adam (Kingma & Ba, Algorithm 1; the optimizer the paper names for its MNIST workload),
+    step number t >= 1:
+        m <- beta1 m + (1 - beta1) g ;  v <- beta2 v + (1 - beta2) g^2
+        x <- x - lr * (m / (1 - beta1^t)) / (sqrt(v / (1 - beta2^t)) + eps)
+    Returns (params, m, v)."""
+    c1 = 1.0 - beta1 ** t
+    c2 = 1.0 - beta2 ** t
+    def one(x, mm, vv, gg):
+        x = np.asarray(x, np.float64); gg = np.asarray(gg, np.float64)
+        mm = beta1 * np.asarray(mm, np.float64) + (1.0 - beta1) * gg
+        vv = beta2 * np.asarray(vv, np.float64) + (1.0 - beta2) * gg * gg
+        return x - lr * (mm / c1) / (np.sqrt(vv / c2) + eps), mm, vv
+    out_p, out_m, out_v = [], [], []
+    for (W, b), (mW, mb), (vW, vb), (gW, gb) in zip(params, m, v, g):
+        pW, nmW, nvW = one(W, mW, vW, gW)
+        pb, nmb, nvb = one(b, mb, vb, gb)
+        out_p.append((pW, pb)); out_m.append((nmW, nmb)); out_v.append((nvW, nvb))
+    return out_p, out_m, out_v
+
+
+def stepwise_learning_rate(step, boundaries, values):
+    """Piecewise-constant schedule (the paper lists the values [0.1, 0.01, 0.001, 0.0002] for
+    its ResNet workload, not the switching points): values[i] holds for
+    boundaries[i-1] <= step < boundaries[i]."""
+    i = 0
+    while i < len(boundaries) and step >= boundaries[i]:
+        i += 1
+    return float(values[i])
+
+
 def zeros_like_params(params):
     return [(np.zeros(np.shape(W)), np.zeros(np.shape(b))) for W, b in params]

@@ -293,3 +293,43 @@ def test_forced_relu_masks_change_exactly_the_flipped_units_contribution():
     want = np.zeros_like(g0[1][0]); want[:, 2] = sign * a_in[1] * incoming[1, 2]
     np.testing.assert_allclose(g1[1][0] - g0[1][0], want, atol=1e-14)
     np.testing.assert_allclose(g1[2][0], g0[2][0], atol=0)          # layers above: untouched
+
+
+def test_adam_closed_forms():
+    rng = np.random.default_rng(9)
+    W = rng.normal(size=(5, 3)); b = rng.normal(size=3)
+    gW = rng.normal(size=(5, 3)); gb = rng.normal(size=3)
+    z = on.zeros_like_params([(W, b)])
+    # first step from zero state: bias correction makes m_hat = g, v_hat = g^2
+    p, m, v = on.adam_update([(W, b)], z, z, [(gW, gb)], lr=1e-2, eps=1e-8, t=1)
+    np.testing.assert_allclose(p[0][0], W - 1e-2 * gW / (np.abs(gW) + 1e-8), rtol=1e-12)
+    np.testing.assert_allclose(p[0][1], b - 1e-2 * gb / (np.abs(gb) + 1e-8), rtol=1e-12)
+    np.testing.assert_allclose(m[0][0], 0.1 * gW, rtol=1e-12)
+    np.testing.assert_allclose(v[0][0], 0.001 * gW * gW, rtol=1e-12)
+    # a constant gradient keeps m_hat = g and v_hat = g^2 at every step: x_t = x_0 - t lr g/(|g|+eps)
+    params, mm, vv = [(W, b)], z, z
+    for t in range(1, 8):
+        params, mm, vv = on.adam_update(params, mm, vv, [(gW, gb)], lr=1e-3, eps=1e-6, t=t)
+    np.testing.assert_allclose(params[0][0], W - 7 * 1e-3 * gW / (np.abs(gW) + 1e-6), rtol=1e-10)
+    # eps = 0: the step does not depend on the gradient's scale; its sign opposes the gradient
+    p1, _, _ = on.adam_update([(W, b)], z, z, [(gW, gb)], lr=1e-2, eps=0.0, t=1)
+    p2, _, _ = on.adam_update([(W, b)], z, z, [(1e3 * gW, 1e3 * gb)], lr=1e-2, eps=0.0, t=1)
+    np.testing.assert_allclose(p1[0][0], p2[0][0], rtol=1e-12)
+    assert np.all(np.sign(W - p1[0][0]) == np.sign(gW))
+    # two different gradients, second step, one scalar worked by hand:
+    # g1 = 1, g2 = 3: m = 0.9*0.1 + 0.1*3 = 0.39, v = 0.999*0.001 + 0.001*9 = 0.009999
+    # m_hat = 0.39/0.19, v_hat = 0.009999/0.001999
+    one = [(np.array([[0.0]]), np.array([0.0]))]
+    p, m, v = on.adam_update(one, on.zeros_like_params(one), on.zeros_like_params(one),
+                             [(np.array([[1.0]]), np.array([1.0]))], lr=0.0, t=1)
+    p, m, v = on.adam_update(p, m, v, [(np.array([[3.0]]), np.array([3.0]))], lr=0.5, eps=0.0, t=2)
+    want = -0.5 * (0.39 / 0.19) / np.sqrt(0.009999 / 0.001999)
+    assert abs(p[0][0][0, 0] - want) < 1e-12
+
+
+def test_stepwise_learning_rate_uses_the_papers_values():
+    values = [0.1, 0.01, 0.001, 0.0002]
+    bounds = [100, 150, 200]
+    got = [on.stepwise_learning_rate(s, bounds, values) for s in (0, 99, 100, 149, 150, 199, 200, 10**6)]
+    assert got == [0.1, 0.1, 0.01, 0.01, 0.001, 0.001, 0.0002, 0.0002]
+    assert on.stepwise_learning_rate(5, [], [0.3]) == 0.3
