@@ -50,6 +50,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--separate-update", action="store_true",
+                    help="weighted aggregate and update as two calls (aggregate written to HBM) "
+                         "instead of the one-pass dynb_model_aggregate_update")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="also run one plain device copy of MIB mebibytes (a dispatch of known "
                          "traffic to scale FETCH_SIZE / WRITE_SIZE counter readings by)")
@@ -78,6 +81,8 @@ def main():
     grads = torch.empty(K, Pp, device="cuda")
     out = torch.empty(Pp, device="cuda")
     velocity = torch.zeros(Pp, device="cuda") if cfg["momentum"] else None
+    opt = binding.make_optimizer("momentum" if cfg["momentum"] else "sgd", lr=cfg["lr"],
+                                 momentum=cfg["momentum"])
     xs, ys = [], []
     for s in range(n_batches):          # a fresh global batch per step, resident in HBM
         x, y = synth.make_batch(spec, cfg["x_dist"], G, seed, s)
@@ -90,8 +95,11 @@ def main():
         s = state["step"]
         b = state["b"]
         binding.forward_backward(model, xs[s % n_batches], ys[s % n_batches], b, grads)
-        binding.weighted_aggregate(grads, b, Pp, out)
-        binding.model_sgd_update(model, out, cfg["lr"], cfg["momentum"], velocity)
+        if args.separate_update:
+            binding.weighted_aggregate(grads, b, Pp, out)
+            binding.model_update(model, out, opt, velocity)
+        else:
+            binding.model_aggregate_update(model, grads, b, opt, velocity)
         t = synth.iteration_times(b, cfg["speeds"])
         state["b"] = binding.controller_step(t, b, G, cfg["gains"])
         state["trace"].append(b)

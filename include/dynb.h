@@ -114,7 +114,7 @@ int dynb_model_bind(dynb_model* m, float* params, void* workspace, size_t worksp
                     int32_t max_global_batch, int32_t max_workers, void* stream);
 
 /* Re-derives the weight copies used by the kernels from the bound master parameters.
- * Call after writing params by any means other than dynb_model_sgd_update. */
+ * Call after writing params by any means other than the dynb_model_*update calls. */
 int dynb_model_sync_weights(dynb_model* m, void* stream);
 
 /* Device pointer to float[max_workers]: mean loss of each worker's mini-batch from the
@@ -152,6 +152,55 @@ int dynb_sgd_momentum_update(float* params, float* velocity, const float* g, int
  * the next dynb_forward_backward reads.  velocity == NULL selects plain SGD (mu ignored). */
 int dynb_model_sgd_update(dynb_model* m, const float* g, float lr, float mu, float* velocity,
                           void* stream);
+
+/* Adam (Kingma & Ba, Algorithm 1; the optimizer of the paper's MNIST workload, Section
+ * "Experimental Evaluation"), step number `step` >= 1:
+ *   m = beta1 m + (1-beta1) g;  v = beta2 v + (1-beta2) g^2;
+ *   params -= lr * (m / (1-beta1^step)) / (sqrt(v / (1-beta2^step)) + eps).
+ * params, m, v, g: device fp32 [n], 16-byte aligned, n % 4 == 0.  fp32 arithmetic on the
+ * device; the betas are doubles so that 1 - beta and the bias corrections are formed in
+ * double on the host before they are rounded to fp32 (0.999 is not a float: 1 - 0.999f is
+ * off by 1.3e-5 relative). */
+int dynb_adam_update(float* params, float* m, float* v, const float* g, int64_t n, float lr,
+                     double beta1, double beta2, float eps, int64_t step, void* stream);
+
+/* Choice of optimizer for the model-level updates.  momentum is read by
+ * DYNB_OPT_MOMENTUM; beta1, beta2, eps and step (1-based) by DYNB_OPT_ADAM. */
+enum { DYNB_OPT_SGD = 0, DYNB_OPT_MOMENTUM = 1, DYNB_OPT_ADAM = 2 };
+typedef struct {
+  int32_t kind;
+  float lr;
+  float momentum;
+  float eps;
+  double beta1, beta2;
+  int64_t step;
+} dynb_optimizer;
+
+/* One optimizer step on the model's bound parameters from the finished gradient g (device
+ * fp32 [P_pad], 16-byte aligned), followed by the refresh of the weight copies the next
+ * dynb_forward_backward reads.  state1: velocity (momentum) or first moment (Adam); state2:
+ * second moment (Adam); device fp32 [P_pad], 16-byte aligned, caller-owned, zero before the
+ * first step; ignored (may be NULL) when the optimizer has no such state.
+ * DYNB_ERR_BADARG: null/misaligned pointers, unknown kind, missing state, Adam step < 1 or
+ * betas outside [0,1).  DYNB_ERR_STATE: model not bound. */
+int dynb_model_update(dynb_model* m, const float* g, const dynb_optimizer* opt, float* state1,
+                      float* state2, void* stream);
+
+/* Eq. 2 and Eq. 3 in one pass: the same result as dynb_weighted_aggregate(grads, b, K,
+ * P_pad, tmp) followed by dynb_model_update(m, tmp, ...), but every parameter's K per-worker
+ * gradients are read and summed (ascending k, fp32) where the step is applied, so the
+ * aggregate is never written to or re-read from device memory.  grads: device fp32
+ * [K][P_pad] as written by dynb_forward_backward; b: host int32 [K], sum(b) > 0. */
+int dynb_model_aggregate_update(dynb_model* m, const float* grads, const int32_t* b, int32_t K,
+                                const dynb_optimizer* opt, float* state1, float* state2,
+                                void* stream);
+
+/* Piecewise-constant learning rate (the paper gives the values 0.1, 0.01, 0.001, 0.0002 for
+ * its ResNet workload, Section "Experimental Evaluation"): *lr = values[i] for
+ * boundaries[i-1] <= step < boundaries[i].  values: host [n_values], boundaries: host
+ * [n_values - 1], non-decreasing (may be NULL when n_values == 1). */
+int dynb_lr_schedule(int64_t step, const int64_t* boundaries, const double* values,
+                     int32_t n_values, double* lr);
 
 /* ---- controller (host only) ---------------------------------------------------- */
 

@@ -25,6 +25,7 @@ SYMBOLS = [
     "dynb_model_sync_weights", "dynb_model_worker_loss", "dynb_model_read_worker_loss", "dynb_forward_backward",
     "dynb_weighted_aggregate", "dynb_sgd_update", "dynb_sgd_momentum_update",
     "dynb_model_sgd_update", "dynb_controller_step", "dynb_ewma_update", "dynb_static_allocate",
+    "dynb_adam_update", "dynb_model_update", "dynb_model_aggregate_update", "dynb_lr_schedule",
     "dynb_controller_create", "dynb_controller_destroy", "dynb_controller_observe",
     "dynb_controller_read",
     "dynb_profile_enable", "dynb_profile_reset", "dynb_profile_collect",
@@ -52,6 +53,15 @@ class ModelDesc(C.Structure):
 class Gains(C.Structure):
     _fields_ = [("kp", C.c_double), ("deadband", C.c_double), ("ewma_alpha", C.c_double),
                 ("b_min", C.c_int32), ("b_max", C.c_int32)]
+
+
+OPT_SGD, OPT_MOMENTUM, OPT_ADAM = 0, 1, 2
+
+
+class Optimizer(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("lr", C.c_float), ("momentum", C.c_float),
+                ("eps", C.c_float), ("beta1", C.c_double), ("beta2", C.c_double),
+                ("step", C.c_int64)]
 
 
 class ControllerConfig(C.Structure):
@@ -95,6 +105,11 @@ def load():
         "dynb_controller_step": (C.c_int, [pf64, pi32, i32, i32, C.POINTER(Gains), pi32]),
         "dynb_ewma_update": (C.c_int, [pf64, pf64, i32, f64, i32]),
         "dynb_static_allocate": (C.c_int, [pf64, i32, i32, pi32]),
+        "dynb_adam_update": (C.c_int, [vp, vp, vp, vp, i64, f32, f64, f64, f32, i64, vp]),
+        "dynb_model_update": (C.c_int, [vp, vp, C.POINTER(Optimizer), vp, vp, vp]),
+        "dynb_model_aggregate_update": (C.c_int, [vp, vp, pi32, i32, C.POINTER(Optimizer), vp, vp,
+                                                  vp]),
+        "dynb_lr_schedule": (C.c_int, [i64, C.POINTER(i64), pf64, i32, pf64]),
         "dynb_controller_create": (C.c_int, [C.POINTER(ControllerConfig), pi32, i32, i32,
                                              C.POINTER(vp)]),
         "dynb_controller_destroy": (None, [vp]),
@@ -237,6 +252,36 @@ def sgd_momentum_update(params, velocity, g, n, lr, mu, stream=None):
 def model_sgd_update(model, g, lr, mu=0.0, velocity=None, stream=None):
     _check(load().dynb_model_sgd_update(model.handle, _ptr(g), lr, mu, _ptr(velocity),
                                         _stream(stream)))
+
+
+def make_optimizer(kind="sgd", lr=0.0, momentum=0.0, beta1=0.9, beta2=0.999, eps=1e-8, step=1):
+    kinds = {"sgd": OPT_SGD, "momentum": OPT_MOMENTUM, "adam": OPT_ADAM}
+    return Optimizer(kinds[kind] if isinstance(kind, str) else int(kind), float(lr),
+                     float(momentum), float(eps), float(beta1), float(beta2), int(step))
+
+
+def adam_update(params, m, v, g, n, lr, beta1=0.9, beta2=0.999, eps=1e-8, step=1, stream=None):
+    _check(load().dynb_adam_update(_ptr(params), _ptr(m), _ptr(v), _ptr(g), n, lr, beta1, beta2,
+                                   eps, int(step), _stream(stream)))
+
+
+def model_update(model, g, opt, state1=None, state2=None, stream=None):
+    _check(load().dynb_model_update(model.handle, _ptr(g), C.byref(opt), _ptr(state1),
+                                    _ptr(state2), _stream(stream)))
+
+
+def model_aggregate_update(model, grads, b, opt, state1=None, state2=None, stream=None):
+    _check(load().dynb_model_aggregate_update(model.handle, _ptr(grads), _i32(b), len(b),
+                                              C.byref(opt), _ptr(state1), _ptr(state2),
+                                              _stream(stream)))
+
+
+def lr_schedule(step, boundaries, values):
+    n = len(values)
+    bd = (C.c_int64 * max(1, n - 1))(*[int(v) for v in boundaries]) if n > 1 else None
+    out = C.c_double()
+    _check(load().dynb_lr_schedule(int(step), bd, _f64(values), n, C.byref(out)))
+    return out.value
 
 
 def make_gains(kp=1.0, deadband=0.05, ewma_alpha=1.0, b_min=1, b_max=1 << 30, **_ignored):

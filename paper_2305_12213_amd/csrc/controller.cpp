@@ -298,3 +298,17 @@ extern "C" int dynb_static_allocate(const double* X, int32_t K, int32_t b0, int3
   for (int k = 0; k < K; ++k) b_out[k] = (int32_t)f[k];
   return DYNB_OK;
 }
+
+extern "C" int dynb_lr_schedule(int64_t step, const int64_t* boundaries, const double* values,
+                                int32_t n_values, double* lr) {
+  if (!values || !lr || (n_values > 1 && !boundaries))
+    return dynb::fail(DYNB_ERR_BADARG, "lr_schedule: null pointer");
+  if (n_values < 1) return dynb::fail(DYNB_ERR_BADARG, "lr_schedule: no values");
+  for (int i = 1; i + 1 < n_values; ++i)
+    if (boundaries[i] < boundaries[i - 1])
+      return dynb::fail(DYNB_ERR_BADARG, "lr_schedule: boundaries must not decrease");
+  int i = 0;
+  while (i < n_values - 1 && step >= boundaries[i]) ++i;
+  *lr = values[i];
+  return DYNB_OK;
+}

@@ -124,13 +124,37 @@ int launch_momentum(float* params, float* v, const float* g, int64_t n, float lr
 int launch_weight_cast(int dtype, const float* W, int R, int C, void* Wn, int64_t ldn, void* Wt,
                        int64_t ldt, void* stream);
 
-// dense weight W fp32 [R][C]: SGD (vel == nullptr) or momentum update from g, fused with the
-// refresh of Wn T [R][ldn] and Wt T [C][ldt]
-int launch_update_cast(int dtype, float* W, const float* g, float* vel, int R, int C, float lr,
-                       float mu, void* Wn, int64_t ldn, void* Wt, int64_t ldt, void* stream);
-// element-wise update of n parameters (any alignment)
-int launch_update_range(float* p, const float* g, float* vel, int64_t n, float lr, float mu,
-                        void* stream);
+// One optimizer step per parameter.  kind: DYNB_OPT_*.  s1 = velocity (momentum) or first
+// moment (Adam), s2 = second moment (Adam).  Adam's bias corrections are passed as
+// inv_c1 = 1/(1 - beta1^t), inv_c2 = 1/(1 - beta2^t), and omb = 1 - beta, all formed in double.
+struct UpdateRule {
+  int kind;
+  float lr, mu;
+  float beta1, beta2, omb1, omb2, eps, inv_c1, inv_c2;
+};
+// Fills the Adam fields of r for step t (t >= 1, betas in [0, 1)).
+void set_adam(UpdateRule& r, double beta1, double beta2, float eps, int64_t t);
+// Where the gradient of a parameter comes from: a finished vector g (lam.K == 0), or the K
+// per-worker gradients g + k*worker_stride, summed with weights lam.w[k] in ascending k
+// (the weighted aggregation of Eq. 2 done on the fly).
+struct GradSource {
+  const float* g;
+  int64_t worker_stride;
+  Lambdas lam;
+};
+
+// dense weight W fp32 [R][C] at parameter offset `off`: optimizer step fused with the refresh
+// of Wn T [R][ldn] and Wt T [C][ldt]; s1/s2 point at the state of parameter 0 (may be null
+// when the rule has no such state)
+int launch_update_cast(int dtype, float* params, int64_t off, const GradSource& src,
+                       const UpdateRule& rule, float* s1, float* s2, int R, int C, void* Wn,
+                       int64_t ldn, void* Wt, int64_t ldt, void* stream);
+// element-wise step of parameters [off, off + n) (any alignment)
+int launch_update_range(float* params, int64_t off, const GradSource& src, const UpdateRule& rule,
+                        float* s1, float* s2, int64_t n, void* stream);
+// plain streaming Adam over n parameters (n a multiple of 4, 16-byte aligned pointers)
+int launch_adam(float* params, float* m, float* v, const float* g, int64_t n,
+                const UpdateRule& rule, void* stream);
 // out[g*group_stride + e] = sum_{c < split} partial[(g*split + c)*partial_stride + e], e < n
 int launch_wgrad_reduce(const float* partial, int split, int64_t partial_stride, int64_t n,
                         float* out, int64_t group_stride, int K, void* stream);

@@ -183,94 +183,6 @@ __global__ __launch_bounds__(256) void weight_cast_kernel(const float* __restric
   }
 }
 
-// ---- SGD / momentum update of one dense weight matrix fused with its two 16-bit copies ----
-// W[r][c] -= lr * g  (or v = mu*v + g; W -= lr*v), then Wn[r][c] = T(W), Wt[c][r] = T(W).
-// One pass over the parameters: 16-byte accesses on the fp32 side, the transposed copy goes
-// through an LDS tile so that its stores are 16 bytes per lane, 128 contiguous bytes per 8 lanes.
-template <typename T, bool MOM>
-__global__ __launch_bounds__(256) void update_cast_kernel(float* __restrict__ W,
-                                                          const float* __restrict__ g,
-                                                          float* __restrict__ vel, int R, int C,
-                                                          float lr, float mu, T* __restrict__ Wn,
-                                                          int64_t ldn, T* __restrict__ Wt,
-                                                          int64_t ldt) {
-  constexpr int G = 16 / sizeof(T);
-  typedef T vecT __attribute__((ext_vector_type(G)));
-  typedef T vec4T __attribute__((ext_vector_type(4)));
-  typedef float f4 __attribute__((ext_vector_type(4)));
-  __shared__ float tile[64][65];
-  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
-  const bool vec = (C & 3) == 0;   // rows of W are 16-byte aligned
-  for (int idx = threadIdx.x; idx < 64 * 16; idx += 256) {
-    const int r = idx >> 4, cq = (idx & 15) * 4;
-    const int gr = r0 + r, gc = c0 + cq;
-    f4 w = {0.f, 0.f, 0.f, 0.f};
-    if (gr < R && gc < C) {
-      const int64_t o = (int64_t)gr * C + gc;
-      if (vec) {
-        w = *(const f4*)(W + o);
-        f4 d = *(const f4*)(g + o);
-        if (MOM) {
-          f4 v = *(const f4*)(vel + o);
-          v = mu * v + d;
-          *(f4*)(vel + o) = v;
-          d = v;
-        }
-        w -= lr * d;
-        *(f4*)(W + o) = w;
-        const vec4T q = {from_float<T>(w[0]), from_float<T>(w[1]), from_float<T>(w[2]), from_float<T>(w[3])};
-        *(vec4T*)(Wn + (int64_t)gr * ldn + gc) = q;
-      } else {
-        for (int e = 0; e < 4 && gc + e < C; ++e) {
-          float d = g[o + e];
-          if (MOM) {
-            const float v = mu * vel[o + e] + d;
-            vel[o + e] = v;
-            d = v;
-          }
-          w[e] = W[o + e] - lr * d;
-          W[o + e] = w[e];
-          Wn[(int64_t)gr * ldn + gc + e] = from_float<T>(w[e]);
-        }
-      }
-    }
-#pragma unroll
-    for (int e = 0; e < 4; ++e) tile[r][cq + e] = w[e];
-  }
-  __syncthreads();
-  constexpr int GR = 64 / G;   // granules of rows per tile column
-  for (int idx = threadIdx.x; idx < 64 * GR; idx += 256) {
-    const int rg = idx % GR, c = idx / GR;
-    if (c0 + c >= C) continue;
-    if (r0 + rg * G + G <= R) {
-      vecT v;
-#pragma unroll
-      for (int e = 0; e < G; ++e) v[e] = from_float<T>(tile[rg * G + e][c]);
-      *(vecT*)(Wt + (int64_t)(c0 + c) * ldt + r0 + rg * G) = v;
-    } else {
-      for (int e = 0; e < G && r0 + rg * G + e < R; ++e)
-        Wt[(int64_t)(c0 + c) * ldt + r0 + rg * G + e] = from_float<T>(tile[rg * G + e][c]);
-    }
-  }
-}
-
-// plain element-wise update of params[off, off + n) (biases, convolution weights)
-template <bool MOM>
-__global__ __launch_bounds__(256) void update_range_kernel(float* __restrict__ p,
-                                                           const float* __restrict__ g,
-                                                           float* __restrict__ vel, int64_t n,
-                                                           float lr, float mu) {
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
-    float d = g[i];
-    if (MOM) {
-      const float v = mu * vel[i] + d;
-      vel[i] = v;
-      d = v;
-    }
-    p[i] -= lr * d;
-  }
-}
-
 // ---- sum of the split weight-gradient chunks, fixed order -------------------------------
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restrict__ partial,
                                                            int split, int64_t pstride, int64_t n,
@@ -347,37 +259,6 @@ int launch_finalize(const float* rowloss, float* loss, float* grads, int64_t P, 
   hipLaunchKernelGGL(finalize_kernel, dim3(s.K), dim3(64), 0, (hipStream_t)stream, rowloss, loss,
                      grads, P, P_pad, s);
   return ok("finalize");
-}
-
-int launch_update_cast(int dtype, float* W, const float* g, float* vel, int R, int C, float lr,
-                       float mu, void* Wn, int64_t ldn, void* Wt, int64_t ldt, void* stream) {
-  const int es = dtype == DYNB_BF16 ? 2 : 4;
-  Timed t(KC_UPDATE, stream, (vel ? 4.0 : 2.0) * R * C, (double)R * C * ((vel ? 20 : 12) + 2 * es));
-  dim3 grid((C + 63) / 64, (R + 63) / 64);
-  if (vel)
-    DISPATCH_T(dtype, hipLaunchKernelGGL((update_cast_kernel<T, true>), grid, dim3(256), 0,
-                                         (hipStream_t)stream, W, g, vel, R, C, lr, mu, (T*)Wn, ldn,
-                                         (T*)Wt, ldt));
-  else
-    DISPATCH_T(dtype, hipLaunchKernelGGL((update_cast_kernel<T, false>), grid, dim3(256), 0,
-                                         (hipStream_t)stream, W, g, vel, R, C, lr, mu, (T*)Wn, ldn,
-                                         (T*)Wt, ldt));
-  return ok("update_cast");
-}
-
-int launch_update_range(float* p, const float* g, float* vel, int64_t n, float lr, float mu,
-                        void* stream) {
-  if (n <= 0) return DYNB_OK;
-  Timed t(KC_UPDATE, stream, (vel ? 4.0 : 2.0) * n, (double)n * (vel ? 20 : 12));
-  int64_t bx = (n + 255) / 256;
-  if (bx > 2048) bx = 2048;
-  if (vel)
-    hipLaunchKernelGGL(update_range_kernel<true>, dim3((unsigned)bx), dim3(256), 0,
-                       (hipStream_t)stream, p, g, vel, n, lr, mu);
-  else
-    hipLaunchKernelGGL(update_range_kernel<false>, dim3((unsigned)bx), dim3(256), 0,
-                       (hipStream_t)stream, p, g, vel, n, lr, mu);
-  return ok("update_range");
 }
 
 int launch_wgrad_reduce(const float* partial, int split, int64_t partial_stride, int64_t n,

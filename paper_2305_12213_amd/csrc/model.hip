@@ -13,6 +13,7 @@
 // padding columns are written as zero.
 #include <hip/hip_runtime.h>
 
+#include <cmath>
 #include <new>
 #include <vector>
 
@@ -447,32 +448,106 @@ extern "C" int dynb_forward_backward(dynb_model* m, const float* x, const int32_
   return launch_finalize(m->rowloss, m->loss, grads, m->P, m->P_pad, s1, stream);
 }
 
-extern "C" int dynb_model_sgd_update(dynb_model* m, const float* g, float lr, float mu,
-                                     float* velocity, void* stream) {
-  if (!m || !g) return fail(DYNB_ERR_BADARG, "model_sgd_update: null pointer");
-  if (!m->bound) return fail(DYNB_ERR_STATE, "model_sgd_update: model not bound");
-  if (((uintptr_t)g & 15) || (velocity && ((uintptr_t)velocity & 15)))
-    return fail(DYNB_ERR_BADARG, "model_sgd_update: pointers must be 16-byte aligned");
-  // one pass per dense weight matrix (update + both 16-bit copies); biases and convolution
-  // weights are small: element-wise update, then the convolution's weight layouts
+namespace {
+
+int make_rule(const dynb_optimizer* opt, const float* s1, const float* s2, UpdateRule& r) {
+  if (!opt) return fail(DYNB_ERR_BADARG, "update: null optimizer");
+  r = UpdateRule{};
+  r.kind = opt->kind;
+  r.lr = opt->lr;
+  r.mu = opt->momentum;
+  switch (opt->kind) {
+    case DYNB_OPT_SGD:
+      break;
+    case DYNB_OPT_MOMENTUM:
+      if (!s1) return fail(DYNB_ERR_BADARG, "update: momentum needs state1 (velocity)");
+      break;
+    case DYNB_OPT_ADAM: {
+      if (!s1 || !s2) return fail(DYNB_ERR_BADARG, "update: Adam needs state1 and state2");
+      if (opt->step < 1) return fail(DYNB_ERR_BADARG, "update: Adam step numbers start at 1");
+      if (!(opt->beta1 >= 0.0 && opt->beta1 < 1.0 && opt->beta2 >= 0.0 && opt->beta2 < 1.0))
+        return fail(DYNB_ERR_BADARG, "update: Adam betas must lie in [0, 1)");
+      set_adam(r, opt->beta1, opt->beta2, opt->eps, opt->step);
+      break;
+    }
+    default:
+      return fail(DYNB_ERR_BADARG, "update: unknown optimizer kind %d", opt->kind);
+  }
+  if (((uintptr_t)s1 & 15) || ((uintptr_t)s2 & 15))
+    return fail(DYNB_ERR_BADARG, "update: optimizer state must be 16-byte aligned");
+  return DYNB_OK;
+}
+
+// One step over all layers: one fused pass per dense weight matrix (step + both 16-bit
+// copies); biases and convolution weights are small: element-wise step, then the
+// convolution's weight layouts.
+int update_layers(dynb_model* m, const GradSource& src, const UpdateRule& rule, float* s1,
+                  float* s2, void* stream) {
   for (Layer& L : m->layers) {
     if (!L.has_params) continue;
-    float* vw = velocity ? velocity + L.w_off : nullptr;
-    float* vb = velocity ? velocity + L.b_off : nullptr;
     int rc;
     if (L.kind == DYNB_LAYER_DENSE) {
-      rc = launch_update_cast(m->dtype, m->params + L.w_off, g + L.w_off, vw, L.n_in, L.n_out, lr,
-                              mu, L.Wn, L.ld_out, L.Wt, L.ld_in, stream);
+      rc = launch_update_cast(m->dtype, m->params, L.w_off, src, rule, s1, s2, L.n_in, L.n_out,
+                              L.Wn, L.ld_out, L.Wt, L.ld_in, stream);
     } else {
-      rc = launch_update_range(m->params + L.w_off, g + L.w_off, vw, (int64_t)9 * L.n_in * L.n_out,
-                               lr, mu, stream);
+      rc = launch_update_range(m->params, L.w_off, src, rule, s1, s2,
+                               (int64_t)9 * L.n_in * L.n_out, stream);
       if (!rc)
         rc = launch_conv_weight_cast(m->params + L.w_off, L.n_in, L.n_out, L.cin_p, L.cout_p, L.Wt,
                                      L.kf, L.Wn, L.kd, stream);
     }
     if (rc) return rc;
-    rc = launch_update_range(m->params + L.b_off, g + L.b_off, vb, L.n_out, lr, mu, stream);
+    rc = launch_update_range(m->params, L.b_off, src, rule, s1, s2, L.n_out, stream);
     if (rc) return rc;
   }
   return DYNB_OK;
+}
+
+}  // namespace
+
+extern "C" int dynb_model_update(dynb_model* m, const float* g, const dynb_optimizer* opt,
+                                 float* state1, float* state2, void* stream) {
+  if (!m || !g) return fail(DYNB_ERR_BADARG, "model_update: null pointer");
+  if (!m->bound) return fail(DYNB_ERR_STATE, "model_update: model not bound");
+  if ((uintptr_t)g & 15) return fail(DYNB_ERR_BADARG, "model_update: g must be 16-byte aligned");
+  UpdateRule rule;
+  if (int rc = make_rule(opt, state1, state2, rule)) return rc;
+  GradSource src;
+  src.g = g;
+  src.worker_stride = 0;
+  src.lam.K = 0;
+  return update_layers(m, src, rule, state1, state2, stream);
+}
+
+extern "C" int dynb_model_aggregate_update(dynb_model* m, const float* grads, const int32_t* b,
+                                           int32_t K, const dynb_optimizer* opt, float* state1,
+                                           float* state2, void* stream) {
+  if (!m || !grads || !b) return fail(DYNB_ERR_BADARG, "model_aggregate_update: null pointer");
+  if (!m->bound) return fail(DYNB_ERR_STATE, "model_aggregate_update: model not bound");
+  if (K < 1 || K > DYNB_MAX_WORKERS) return fail(DYNB_ERR_BADARG, "model_aggregate_update: K out of range");
+  if ((uintptr_t)grads & 15)
+    return fail(DYNB_ERR_BADARG, "model_aggregate_update: grads must be 16-byte aligned");
+  int64_t total = 0;
+  for (int k = 0; k < K; ++k) {
+    if (b[k] < 0) return fail(DYNB_ERR_BADARG, "model_aggregate_update: negative batch size");
+    total += b[k];
+  }
+  if (total <= 0) return fail(DYNB_ERR_BADARG, "model_aggregate_update: sum(b) must be positive");
+  UpdateRule rule;
+  if (int rc = make_rule(opt, state1, state2, rule)) return rc;
+  GradSource src;
+  src.g = grads;
+  src.worker_stride = m->P_pad;
+  src.lam.K = K;
+  for (int k = 0; k < K; ++k) src.lam.w[k] = (float)((double)b[k] / (double)total);   // Eq. 2
+  return update_layers(m, src, rule, state1, state2, stream);
+}
+
+extern "C" int dynb_model_sgd_update(dynb_model* m, const float* g, float lr, float mu,
+                                     float* velocity, void* stream) {
+  dynb_optimizer opt{};
+  opt.kind = velocity ? DYNB_OPT_MOMENTUM : DYNB_OPT_SGD;
+  opt.lr = lr;
+  opt.momentum = mu;
+  return dynb_model_update(m, g, &opt, velocity, nullptr, stream);
 }

@@ -215,3 +215,16 @@ def test_stateful_controller_rejects_bad_input():
         c.observe([1.0, float("nan")])
     assert c.read()["observations"] == 0            # state untouched by the rejected call
     assert c.observe([1.0, 1.0]) == ([50, 50], False)
+
+
+def test_lr_schedule_matches_checker_and_rejects_bad_input():
+    from oracle import network as on
+    values = [0.1, 0.01, 0.001, 0.0002]            # the paper's ResNet schedule values
+    bounds = [30000, 45000, 60000]
+    for step in (0, 1, 29999, 30000, 44999, 45000, 59999, 60000, 10**9):
+        assert binding.lr_schedule(step, bounds, values) == on.stepwise_learning_rate(step, bounds, values)
+    assert binding.lr_schedule(7, [], [0.5]) == 0.5
+    with pytest.raises(binding.DynbError):
+        binding.lr_schedule(0, [5, 3, 9], values)
+    with pytest.raises(binding.DynbError):
+        binding.lr_schedule(0, [], [])
