@@ -331,42 +331,71 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
     const int ib0 = i0 + wm * (BM / WM) + rc, jb0 = j0 + wn * (BN / WN) + rr;
     float* base = Cg + (int64_t)jb0 * p.ldcf + ib0;
     const int64_t row8 = (int64_t)8 * p.ldcf;
+    // Sub-tile n = (b, a): b (32-row blocks) outside, a (128-byte column blocks) inside, so the
+    // four sub-tiles that complete 512 contiguous bytes of each row are written back to back.
+    auto put = [&](int a, int b) {        // accumulators -> patch (j = lane % 32 rows, i columns)
 #pragma unroll
-    for (int a = 0; a < TM; ++a)
+      for (int q = 0; q < 4; ++q) {
+        const f32x4 o = {acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2],
+                         acc[a][b][4 * q + 3]};
+        *(f32x4*)&patch[l31 * SPITCH + 8 * q + hi4] = o;
+      }
+    };
+    auto get = [&](f32x4 (&o)[4]) {       // patch -> 8 rows x 128 bytes per instruction
 #pragma unroll
-      for (int b = 0; b < TN; ++b) {
+      for (int t = 0; t < 4; ++t) o[t] = *(const f32x4*)&patch[(rr + 8 * t) * SPITCH + rc];
+    };
+    if (interior) {
+      // Software pipeline over the sub-tiles.  LDS operations of one wave execute in order, so
+      // sub-tile n+1 may be written to the patch as soon as the reads of sub-tile n are
+      // *issued*; its read-back is issued before the global stores of sub-tile n, which
+      // therefore wait only for data requested a whole sub-tile earlier.  Without this the
+      // tile store is a chain of exposed LDS latencies (one per store instruction).
+      f32x4 o[2][4];
+      put(0, 0);
+      __builtin_amdgcn_wave_barrier();
+      get(o[0]);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const f32x4 o = {acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2],
-                           acc[a][b][4 * q + 3]};
-          *(f32x4*)&patch[l31 * SPITCH + 8 * q + hi4] = o;
+      for (int n = 0; n < TM * TN; ++n) {
+        const int a = n % TM, b = n / TM;
+        if (n + 1 < TM * TN) {
+          __builtin_amdgcn_wave_barrier();
+          put((n + 1) % TM, (n + 1) / TM);
+          __builtin_amdgcn_wave_barrier();
+          get(o[(n + 1) & 1]);
         }
+        __builtin_amdgcn_sched_barrier(0);
+        float* d = base + (int64_t)(4 * b) * row8 + a * 32;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) __builtin_nontemporal_store(o[n & 1][t], (f32x4*)(d + t * row8));
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      return;
+    }
+#pragma unroll
+    for (int b = 0; b < TN; ++b)
+#pragma unroll
+      for (int a = 0; a < TM; ++a) {
+        __builtin_amdgcn_wave_barrier();
+        put(a, b);
         __builtin_amdgcn_wave_barrier();
         float* d = base + (int64_t)(4 * b) * row8 + a * 32;
-        if (interior) {
+        const int ib = ib0 + a * 32;
+        f32x4 o[4];
+        get(o);
 #pragma unroll
-          for (int t = 0; t < 4; ++t) {
-            const f32x4 o = *(const f32x4*)&patch[(rr + 8 * t) * SPITCH + rc];
-            __builtin_nontemporal_store(o, (f32x4*)(d + t * row8));
-          }
-        } else {
-          const int ib = ib0 + a * 32;
+        for (int t = 0; t < 4; ++t) {
+          if (jb0 + b * 32 + 8 * t < p.N) {
+            float* dst = d + t * row8;
+            if (vec_ok && ib + 3 < p.M) {
+              __builtin_nontemporal_store(o[t], (f32x4*)dst);
+            } else {
 #pragma unroll
-          for (int t = 0; t < 4; ++t) {
-            const f32x4 o = *(const f32x4*)&patch[(rr + 8 * t) * SPITCH + rc];
-            if (jb0 + b * 32 + 8 * t < p.N) {
-              float* dst = d + t * row8;
-              if (vec_ok && ib + 3 < p.M) {
-                __builtin_nontemporal_store(o, (f32x4*)dst);
-              } else {
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-                  if (ib + r < p.M) dst[r] = o[r];
-              }
+              for (int r = 0; r < 4; ++r)
+                if (ib + r < p.M) dst[r] = o[t][r];
             }
           }
         }
-        __builtin_amdgcn_wave_barrier();
       }
   };
 
