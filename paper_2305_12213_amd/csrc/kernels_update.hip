@@ -33,7 +33,7 @@ __device__ inline float step_one(const UpdateRule& r, float w, float g, float& s
 template <bool AGG>
 __device__ inline f4 gradient4(const GradSource& src, int64_t o) {
   if (!AGG) return *(const f4*)(src.g + o);
-  constexpr int U = 6;   // loads in flight per lane
+  constexpr int U = 8;   // loads in flight per lane
   f4 acc = {0.f, 0.f, 0.f, 0.f};
   int k = 0;
   for (; k + U <= src.lam.K; k += U) {

@@ -96,6 +96,33 @@ def test_cnn_odd_image_size_and_wide_channels():
     check_worker_gradients(spec, params, x, y, [5, 6], label="cnn odd")
 
 
+def test_sixty_four_workers():
+    # the largest worker count the interface takes, most workers tiny, some idle
+    for dtype in ("f32", "bf16"):
+        spec = synth.mlp_spec([48, 40, 6], dtype)
+        params = synth.init_params(spec, "he", 41)
+        b = synth.ragged_split(300, 64, 9)
+        assert len(b) == 64 and 0 in b
+        x, y = synth.make_batch(spec, "normal", sum(b), 41, 0)
+        check_worker_gradients(spec, params, x, y, b, label="K=64 " + dtype)
+
+
+def test_large_tile_kernels_on_ragged_edges(capsys):
+    # sizes that select the 256 x 256 tile kernels for the forward, input-gradient and
+    # weight-gradient products (at least 192 tiles of 256 x 256: layer 1 forward 13 x 16, layer 2
+    # input gradient 13 x 16, layer 2 weight gradient 14 x 16) while no dimension is a multiple
+    # of the tile: 3100 rows, widths 3900 and 3340, a reduction length (600) that ends inside a
+    # stage, workers of 1265, 1023, 1, 0, 257 and 554 rows (segment tails inside 16-byte
+    # granules, an idle worker)
+    spec = synth.mlp_spec([600, 3900, 3340, 24], "bf16")
+    params = synth.init_params(spec, "he", 43)
+    b = [1265, 1023, 1, 0, 257, 554]
+    x, y = synth.make_batch(spec, "normal", sum(b), 43, 0)
+    with capsys.disabled():
+        print("large ragged tiles: checker at work (about a minute)", flush=True)
+    check_worker_gradients(spec, params, x, y, b, label="256-tile ragged")
+
+
 def test_same_handle_serves_changing_batch_splits():
     # batch sizes change every step; nothing is rebuilt per size and stale padding is harmless
     spec = synth.mlp_spec([128, 96, 10], "bf16")
