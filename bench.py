@@ -120,6 +120,32 @@ def main():
     ms_per_step = 1e3 * elapsed / args.steps
     timed_splits = state["trace"][args.warmup:]
 
+    # the same step on two fixed splits: uniform (no raggedness) and an adversarial one whose
+    # sizes straddle every tile and granule boundary (workload 4 only: both sum to 4096)
+    other = {}
+    if cfg["index"] == 4 and not args.copy_calibration:
+        fixed = {"uniform": [G // K] * K,
+                 "adversarial": [1, 2, 3, 17, 31, 33, 63, 65, 127, 129, 255, 257, 511, 513, 1023, 1066]}
+        for name, bs in fixed.items():
+            assert sum(bs) == G and len(bs) == K
+            def fixed_step(bs=bs):
+                binding.forward_backward(model, xs[0], ys[0], bs, grads)
+                if args.separate_update:
+                    binding.weighted_aggregate(grads, bs, Pp, out)
+                    binding.model_update(model, out, opt, velocity)
+                else:
+                    binding.model_aggregate_update(model, grads, bs, opt, velocity)
+                binding.controller_step(synth.iteration_times(bs, cfg["speeds"]), bs, G, cfg["gains"])
+            for _ in range(args.warmup):
+                fixed_step()
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for _ in range(args.steps):
+                fixed_step()
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t1) / args.steps
+            other[name] = {"b": bs, "ms_per_step": 1e3 * dt, "samples_per_s": G / dt}
+
     if args.copy_calibration:
         n = args.copy_calibration * (1 << 20) // 4
         src = torch.ones(n, device="cuda"); dst = torch.empty_like(src)
@@ -170,6 +196,7 @@ def main():
                    "workers": K, "b_timed_first": timed_splits[0], "b_timed_last": timed_splits[-1],
                    "params": P},
         "roofline": roofline,
+        "other_splits": other,
         "kernels": kernels,
     }
     if not args.no_cpu_baseline:
@@ -197,7 +224,7 @@ def cpu_baseline(cfg, b):
         on.sgd_update(params, agg, cfg["lr"])
         return time.perf_counter() - t0
 
-    # calibrate on the smallest workers, then take as many whole workers (largest last) as fit ~20 s
+    # calibrate on the smallest workers, then take as many whole workers (largest last) as fit the budget
     order = sorted(range(len(b)), key=lambda k: b[k])
     small = [k for k in order if b[k] > 0][:max(1, len(b) // 2)]
     off = np.concatenate([[0], np.cumsum(b)])
@@ -207,7 +234,7 @@ def cpu_baseline(cfg, b):
     xs, ys = rows(small)
     dt = step([b[k] for k in small], xs, ys)
     per_sample = dt / max(1, sum(b[k] for k in small))
-    budget, chosen, used = 20.0, [], 0.0
+    budget, chosen, used = 30.0, [], 0.0
     for k in order:
         if b[k] == 0:
             continue
