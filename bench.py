@@ -54,9 +54,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--separate-update", action="store_true",
-                    help="weighted aggregate and update as two calls (aggregate written to HBM) "
-                         "instead of the one-pass dynb_model_aggregate_update")
+    ap.add_argument("--aggregate", choices=["gradient", "update", "pass"], default="gradient",
+                    help="where the weighted aggregation runs: inside the weight-gradient kernel "
+                         "(dynb_forward_backward_aggregate, default), inside the update kernel "
+                         "(dynb_model_aggregate_update), or as a pass of its own")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="also run one plain device copy of MIB mebibytes (a dispatch of known "
                          "traffic to scale FETCH_SIZE / WRITE_SIZE counter readings by)")
@@ -98,12 +99,17 @@ def main():
     def one_step():
         s = state["step"]
         b = state["b"]
-        binding.forward_backward(model, xs[s % n_batches], ys[s % n_batches], b, grads)
-        if args.separate_update:
+        if args.aggregate == "pass":          # three calls: gradients, aggregate, update
+            binding.forward_backward(model, xs[s % n_batches], ys[s % n_batches], b, grads)
             binding.weighted_aggregate(grads, b, Pp, out)
             binding.model_update(model, out, opt, velocity)
-        else:
+        elif args.aggregate == "update":      # aggregate folded into the update kernel
+            binding.forward_backward(model, xs[s % n_batches], ys[s % n_batches], b, grads)
             binding.model_aggregate_update(model, grads, b, opt, velocity)
+        else:                                 # aggregate folded into the weight-gradient kernel
+            binding.forward_backward_aggregate(model, xs[s % n_batches], ys[s % n_batches], b,
+                                               grads, out)
+            binding.model_update(model, out, opt, velocity)
         t = synth.iteration_times(b, cfg["speeds"])
         state["b"] = binding.controller_step(t, b, G, cfg["gains"])
         state["trace"].append(b)
@@ -129,12 +135,8 @@ def main():
         for name, bs in fixed.items():
             assert sum(bs) == G and len(bs) == K
             def fixed_step(bs=bs):
-                binding.forward_backward(model, xs[0], ys[0], bs, grads)
-                if args.separate_update:
-                    binding.weighted_aggregate(grads, bs, Pp, out)
-                    binding.model_update(model, out, opt, velocity)
-                else:
-                    binding.model_aggregate_update(model, grads, bs, opt, velocity)
+                binding.forward_backward_aggregate(model, xs[0], ys[0], bs, grads, out)
+                binding.model_update(model, out, opt, velocity)
                 binding.controller_step(synth.iteration_times(bs, cfg["speeds"]), bs, G, cfg["gains"])
             for _ in range(args.warmup):
                 fixed_step()

@@ -22,7 +22,7 @@ MAX_WORKERS = 64
 SYMBOLS = [
     "dynb_last_error", "dynb_model_create", "dynb_model_destroy", "dynb_model_num_params",
     "dynb_model_padded_params", "dynb_model_workspace_bytes", "dynb_model_bind",
-    "dynb_model_sync_weights", "dynb_model_worker_loss", "dynb_model_read_worker_loss", "dynb_forward_backward",
+    "dynb_model_sync_weights", "dynb_model_worker_loss", "dynb_model_read_worker_loss", "dynb_forward_backward", "dynb_forward_backward_aggregate",
     "dynb_weighted_aggregate", "dynb_sgd_update", "dynb_sgd_momentum_update",
     "dynb_model_sgd_update", "dynb_controller_step", "dynb_ewma_update", "dynb_static_allocate",
     "dynb_adam_update", "dynb_model_update", "dynb_model_aggregate_update", "dynb_lr_schedule",
@@ -98,6 +98,7 @@ def load():
         "dynb_model_worker_loss": (vp, [vp]),
         "dynb_model_read_worker_loss": (C.c_int, [vp, C.POINTER(C.c_float), i32, vp]),
         "dynb_forward_backward": (C.c_int, [vp, vp, vp, pi32, i32, vp, vp]),
+        "dynb_forward_backward_aggregate": (C.c_int, [vp, vp, vp, pi32, i32, vp, vp, vp]),
         "dynb_weighted_aggregate": (C.c_int, [vp, pi32, i32, i64, vp, vp]),
         "dynb_sgd_update": (C.c_int, [vp, vp, i64, f32, vp]),
         "dynb_sgd_momentum_update": (C.c_int, [vp, vp, vp, i64, f32, f32, vp]),
@@ -233,6 +234,11 @@ def read_worker_loss(model, K, stream=None):
 def forward_backward(model, x, y, b, grads, stream=None):
     _check(load().dynb_forward_backward(model.handle, _ptr(x), _ptr(y), _i32(b), len(b),
                                         _ptr(grads), _stream(stream)))
+
+
+def forward_backward_aggregate(model, x, y, b, grads, out, stream=None):
+    _check(load().dynb_forward_backward_aggregate(model.handle, _ptr(x), _ptr(y), _i32(b), len(b),
+                                                  _ptr(grads), _ptr(out), _stream(stream)))
 
 
 def weighted_aggregate(grads, b, n, out, stream=None):

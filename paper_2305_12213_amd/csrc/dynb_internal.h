@@ -95,9 +95,19 @@ struct GemmArgs {
   int split, chunk;
   float* partial;
   int64_t partial_stride;
+  // WGRAD, bf16 kernel, optional: also write agg[j*ldcf + i] = sum_g lam[g] * (tile of worker g),
+  // summed in ascending g (the weighted aggregation of Eq. 2 while the per-worker tiles are still
+  // in registers).  Only when gemm_fuses_aggregate() says so.
+  float* agg;
+  float lam[DYNB_MAX_WORKERS];
 };
 
 int launch_gemm(int dtype, const GemmArgs& a, const Segs& s, void* stream);
+// Whether a weight-gradient launch of these dimensions can take GemmArgs::agg.
+bool gemm_fuses_aggregate(int dtype, const GemmArgs& a, const Segs& s);
+// out[e] = sum_k lam.w[k] * g[k*worker_stride + e], e < n, ascending k (any alignment)
+int launch_aggregate_range(const float* g, int64_t worker_stride, const Lambdas& lam, int64_t n,
+                           float* out, void* stream);
 
 // x fp32 [rows][D] -> out T [rows][ld]
 int launch_pack_rows(int dtype, const float* x, int rows, int D, void* out, int64_t ld,

@@ -133,8 +133,11 @@ struct PatchArea<0> {
 };
 
 // S = number of LDS stage buffers (ring).
-template <int BM, int BN, int WM, int WN, int MODE, bool GATHER, int S>
+// AGG (weight gradient only): the workgroup also accumulates sum_g lam[g] * tile_g in registers
+// and writes it to p.agg; it then owns all workers of its tile and walks them in ascending order.
+template <int BM, int BN, int WM, int WN, int MODE, bool GATHER, int S, bool AGG = false>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Segs segs) {
+  static_assert(!AGG || MODE == MODE_WGRAD, "aggregation belongs to the weight gradient");
   constexpr int NW = WM * WN;
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
   constexpr int LA = BM / 16 / NW, LB = BN / 16 / NW;   // 16-row blocks per wave and stage
@@ -178,7 +181,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
   // finish a worker at the same moment and all 256 tiles (64 MB) would hit the memory system
   // together while the MFMAs wait; rotated, the tile stores of some units overlap the MFMAs of
   // the others.  Position c.g in the walk is group gid(c.g).
-  const int rot = (g_hi - g_lo) > 1 ? (int)((blockIdx.x * 7u) % (unsigned)(g_hi - g_lo)) : 0;
+  const int rot = !AGG && (g_hi - g_lo) > 1 ? (int)((blockIdx.x * 7u) % (unsigned)(g_hi - g_lo)) : 0;
   auto gid = [&](int pos) {
     const int r = pos - g_lo + rot, span = g_hi - g_lo;
     return g_lo + (r >= span ? r - span : r);
@@ -289,6 +292,15 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
     for (int b = 0; b < TN; ++b) fb[set][b] = *(const bf16x8*)&sb[frow_b + b * 32 * GPR + g];
   };
 
+  f32x16 agg[AGG ? TM : 1][AGG ? TN : 1];   // weighted sum over the workers (AGG)
+  if constexpr (AGG) {
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+      for (int b = 0; b < TN; ++b)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) agg[a][b][v] = 0.f;
+  }
   f32x16 acc[TM][TN];
   auto clear_acc = [&]() {
 #pragma unroll
@@ -322,8 +334,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
   // a private LDS patch so that one store instruction writes 8 rows x 128 contiguous bytes
   // (whole lines) instead of 32 rows x 32 bytes: these stores are the largest HBM stream of a
   // step.  LDS operations of one wave execute in order, so the patch needs no barrier.
-  auto store_wgrad = [&](int g) {
-    float* Cg = tile_base(g);
+  auto store_tile = [&](float* Cg, f32x16 (&src)[TM][TN]) {
     float* patch = &sStage[wave * 32 * SPITCH];
     const bool vec_ok = (p.ldcf & 3) == 0 && (((uintptr_t)Cg) & 15) == 0;
     const bool interior = vec_ok && i0 + BM <= p.M && j0 + BN <= p.N;   // no edge checks needed
@@ -336,8 +347,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
     auto put = [&](int a, int b) {        // accumulators -> patch (j = lane % 32 rows, i columns)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const f32x4 o = {acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2],
-                         acc[a][b][4 * q + 3]};
+        const f32x4 o = {src[a][b][4 * q], src[a][b][4 * q + 1], src[a][b][4 * q + 2],
+                         src[a][b][4 * q + 3]};
         *(f32x4*)&patch[l31 * SPITCH + 8 * q + hi4] = o;
       }
     };
@@ -482,12 +493,20 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
       --ahead;
     }
     if (MODE == MODE_WGRAD) {
-      store_wgrad(gid(g));
+      if constexpr (AGG) {
+        const float w = p.lam[gid(g)];
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+          for (int b = 0; b < TN; ++b) agg[a][b] += w * acc[a][b];
+      }
+      store_tile(tile_base(gid(g)), acc);
       clear_acc();
       for (stored = g + 1; stored < (later ? ng.g : g_hi); ++stored) store_zero(gid(stored));
     }
     cc = ng;
   }
+  if constexpr (AGG) store_tile(p.agg, agg);
 
   if constexpr (MODE != MODE_WGRAD) {
     // Epilogue.  The stage ring is free now (every wave is past the last barrier and its last
@@ -661,6 +680,16 @@ void launch_bf16(GemmArgs a, const Segs& s, hipStream_t st) {
   }
 }
 
+// Weight gradient with the weighted aggregation folded in: 256 x 128 tiles leave room for a
+// second set of accumulators; every workgroup takes all workers of its tile.
+constexpr int AGG_BM = 256, AGG_BN = 128;
+void launch_bf16_wgrad_agg(GemmArgs a, const Segs& s, hipStream_t st) {
+  const int tiles = ((a.M + AGG_BM - 1) / AGG_BM) * ((a.N + AGG_BN - 1) / AGG_BN);
+  a.groups_per_block = s.K;
+  hipLaunchKernelGGL((gemm_bf16_kernel<AGG_BM, AGG_BN, 2, 2, MODE_WGRAD, false, 5, true>), dim3(tiles),
+                     dim3(256), 0, st, a, s);
+}
+
 // implicit-GEMM convolution (operand A gathered): 128 x 128 tiles
 void launch_bf16_gather(GemmArgs a, const Segs& s, hipStream_t st) {
   const int tiles = ((a.M + 127) / 128) * ((a.N + 127) / 128);
@@ -688,8 +717,17 @@ void launch_f32(const GemmArgs& a, const Segs& s, int groups, hipStream_t st) {
 
 }  // namespace
 
+bool gemm_fuses_aggregate(int dtype, const GemmArgs& a, const Segs& s) {
+  // enough tiles to occupy the compute units without splitting the workers over workgroups
+  const int64_t tiles = (int64_t)((a.M + AGG_BM - 1) / AGG_BM) * ((a.N + AGG_BN - 1) / AGG_BN);
+  return dtype == DYNB_BF16 && a.mode == MODE_WGRAD && !a.conv && a.split <= 1 && tiles >= 256 &&
+         s.K <= DYNB_MAX_WORKERS;
+}
+
 int launch_gemm(int dtype, const GemmArgs& a, const Segs& s, void* stream) {
   if (a.M <= 0 || a.N <= 0) return DYNB_OK;
+  if (a.agg && !gemm_fuses_aggregate(dtype, a, s))
+    return fail(DYNB_ERR_UNSUPPORTED, "gemm: this weight gradient cannot fold the aggregation in");
   const int es = dtype == DYNB_BF16 ? 2 : 4;
   const int gran = 16 / es;
   if ((a.lda % gran) || (a.ldb % gran) || ((uintptr_t)a.A & 15) || ((uintptr_t)a.B & 15))
@@ -702,6 +740,8 @@ int launch_gemm(int dtype, const GemmArgs& a, const Segs& s, void* stream) {
     if (dtype != DYNB_BF16 || a.mode == MODE_WGRAD || (a.cp & 7) || a.stride < 1)
       return fail(DYNB_ERR_UNSUPPORTED, "gemm: gathered operand needs bf16, forward/input-gradient mode");
     launch_bf16_gather(a, s, (hipStream_t)stream);
+  } else if (dtype == DYNB_BF16 && a.agg) {
+    launch_bf16_wgrad_agg(a, s, (hipStream_t)stream);
   } else if (dtype == DYNB_BF16) {
     // large tiles have the best LDS-traffic-to-MFMA ratio; small problems need more, smaller
     // tiles to occupy 256 compute units

@@ -14,8 +14,8 @@ typedef float f4 __attribute__((ext_vector_type(4)));
 // before they are consumed so that several 16-byte reads per lane are in flight.
 template <int UNROLL>
 __global__ __launch_bounds__(kThreads) void aggregate_kernel(const f4* __restrict__ grads,
-                                                             Lambdas lam, int64_t n4,
-                                                             f4* __restrict__ out) {
+                                                             int64_t stride4, Lambdas lam,
+                                                             int64_t n4, f4* __restrict__ out) {
   const int64_t stride = (int64_t)gridDim.x * kThreads;
   for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n4; i += stride) {
     f4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -24,16 +24,29 @@ __global__ __launch_bounds__(kThreads) void aggregate_kernel(const f4* __restric
       f4 v[UNROLL];
 #pragma unroll
       for (int u = 0; u < UNROLL; ++u)
-        v[u] = __builtin_nontemporal_load(&grads[(int64_t)(k + u) * n4 + i]);
+        v[u] = __builtin_nontemporal_load(&grads[(int64_t)(k + u) * stride4 + i]);
 #pragma unroll
       for (int u = 0; u < UNROLL; ++u) {
         acc += lam.w[k + u] * v[u];
       }
     }
     for (; k < lam.K; ++k) {
-      const f4 v = __builtin_nontemporal_load(&grads[(int64_t)k * n4 + i]);
+      const f4 v = __builtin_nontemporal_load(&grads[(int64_t)k * stride4 + i]);
       acc += lam.w[k] * v;
     }
+    out[i] = acc;
+  }
+}
+
+// The same sum over a range of any alignment (biases, small weights): one element per lane.
+__global__ __launch_bounds__(kThreads) void aggregate_range_kernel(const float* __restrict__ g,
+                                                                   int64_t worker_stride,
+                                                                   Lambdas lam, int64_t n,
+                                                                   float* __restrict__ out) {
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride) {
+    float acc = 0.f;
+    for (int k = 0; k < lam.K; ++k) acc += lam.w[k] * g[(int64_t)k * worker_stride + i];
     out[i] = acc;
   }
 }
@@ -90,7 +103,23 @@ int launch_aggregate(const float* grads, const Lambdas& lam, int64_t n, float* o
   if (n4 == 0) return DYNB_OK;
   Timed t(KC_AGGREGATE, stream, 2.0 * lam.K * n, 4.0 * (lam.K + 1) * n);
   hipLaunchKernelGGL(aggregate_kernel<4>, dim3(grid_for(n4)), dim3(kThreads), 0,
-                     (hipStream_t)stream, (const f4*)grads, lam, n4, (f4*)out);
+                     (hipStream_t)stream, (const f4*)grads, n4, lam, n4, (f4*)out);
+  return hipGetLastError() == hipSuccess ? DYNB_OK : fail(DYNB_ERR_HIP, "aggregate launch failed");
+}
+
+int launch_aggregate_range(const float* g, int64_t worker_stride, const Lambdas& lam, int64_t n,
+                           float* out, void* stream) {
+  if (n <= 0) return DYNB_OK;
+  Timed t(KC_AGGREGATE, stream, 2.0 * lam.K * n, 4.0 * (lam.K + 1) * n);
+  if (n >= 4096 && !(n & 3) && !(worker_stride & 3) && !(((uintptr_t)g | (uintptr_t)out) & 15)) {
+    hipLaunchKernelGGL(aggregate_kernel<4>, dim3(grid_for(n / 4)), dim3(kThreads), 0,
+                       (hipStream_t)stream, (const f4*)g, worker_stride / 4, lam, n / 4, (f4*)out);
+    return hipGetLastError() == hipSuccess ? DYNB_OK : fail(DYNB_ERR_HIP, "aggregate launch failed");
+  }
+  int64_t blocks = (n + kThreads - 1) / kThreads;
+  if (blocks > 256 * 16) blocks = 256 * 16;
+  hipLaunchKernelGGL(aggregate_range_kernel, dim3((unsigned)blocks), dim3(kThreads), 0,
+                     (hipStream_t)stream, g, worker_stride, lam, n, out);
   return hipGetLastError() == hipSuccess ? DYNB_OK : fail(DYNB_ERR_HIP, "aggregate launch failed");
 }
 

@@ -295,8 +295,30 @@ extern "C" int dynb_model_bind(dynb_model* m, float* params, void* ws, size_t ws
   return dynb_model_sync_weights(m, stream);
 }
 
+namespace {
+// Forward, loss, backward and the per-worker gradients; with `agg` also the weighted aggregate
+// agg[p] = sum_k (b_k / sum b) grads[k][p] (Eq. 2).
+int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const int32_t* b,
+                         int32_t K, float* grads, float* agg, void* stream);
+}  // namespace
+
 extern "C" int dynb_forward_backward(dynb_model* m, const float* x, const int32_t* y,
                                      const int32_t* b, int32_t K, float* grads, void* stream) {
+  return run_forward_backward(m, x, y, b, K, grads, nullptr, stream);
+}
+
+extern "C" int dynb_forward_backward_aggregate(dynb_model* m, const float* x, const int32_t* y,
+                                               const int32_t* b, int32_t K, float* grads,
+                                               float* out, void* stream) {
+  if (!out) return fail(DYNB_ERR_BADARG, "forward_backward_aggregate: null pointer");
+  if ((uintptr_t)out & 15)
+    return fail(DYNB_ERR_BADARG, "forward_backward_aggregate: out must be 16-byte aligned");
+  return run_forward_backward(m, x, y, b, K, grads, out, stream);
+}
+
+namespace {
+int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const int32_t* b,
+                         int32_t K, float* grads, float* agg, void* stream) {
   if (!m || !x || !y || !b || !grads) return fail(DYNB_ERR_BADARG, "forward_backward: null pointer");
   if (!m->bound) return fail(DYNB_ERR_STATE, "forward_backward: model not bound");
   if (K < 1 || K > m->max_workers)
@@ -411,6 +433,10 @@ extern "C" int dynb_forward_backward(dynb_model* m, const float* x, const int32_
     }
   }
   // ---- per-worker weight and bias gradients ----
+  Lambdas lam;                  // Eq. 2: lambda_k = b_k / sum_i b_i
+  lam.K = K;
+  for (int k = 0; k < K; ++k) lam.w[k] = B > 0 ? (float)((double)b[k] / (double)B) : 0.f;
+  if (agg && B <= 0) return fail(DYNB_ERR_BADARG, "forward_backward_aggregate: sum(b) must be positive");
   for (size_t l = 0; l < nL; ++l) {
     Layer& L = m->layers[l];
     if (!L.has_params) continue;
@@ -435,6 +461,13 @@ extern "C" int dynb_forward_backward(dynb_model* m, const float* x, const int32_
       g.partial = m->partial;
       g.partial_stride = round_up((int64_t)L.wg_rows * L.n_out, 64);
     }
+    // the aggregate of this weight: in the same kernel while the per-worker tiles are in
+    // registers where the launch shape allows it, else by a pass over what was written
+    const bool fold = agg && gemm_fuses_aggregate(dt, g, segs[l]);
+    if (fold) {
+      g.agg = agg + L.w_off;
+      for (int k = 0; k < K; ++k) g.lam[k] = lam.w[k];
+    }
     rc = launch_gemm(dt, g, segs[l], stream);
     if (rc) return rc;
     if (split > 1) {
@@ -444,9 +477,22 @@ extern "C" int dynb_forward_backward(dynb_model* m, const float* x, const int32_
     }
     rc = launch_bias_grad(dt, L.dyT, L.capT, L.n_out, grads + L.b_off, m->P_pad, segs[l], stream);
     if (rc) return rc;
+    if (agg) {
+      if (!fold) {
+        rc = launch_aggregate_range(grads + L.w_off, m->P_pad, lam, (int64_t)L.wg_rows * L.n_out,
+                                    agg + L.w_off, stream);
+        if (rc) return rc;
+      }
+      rc = launch_aggregate_range(grads + L.b_off, m->P_pad, lam, L.n_out, agg + L.b_off, stream);
+      if (rc) return rc;
+    }
   }
-  return launch_finalize(m->rowloss, m->loss, grads, m->P, m->P_pad, s1, stream);
+  rc = launch_finalize(m->rowloss, m->loss, grads, m->P, m->P_pad, s1, stream);
+  if (rc || !agg) return rc;
+  // the padding [P, P_pad) of the aggregate: zeros, like that of the gradients
+  return launch_aggregate_range(grads + m->P, m->P_pad, lam, m->P_pad - m->P, agg + m->P, stream);
 }
+}  // namespace
 
 namespace {
 

@@ -71,6 +71,15 @@ class GpuRun:
         t.cuda.synchronize()
         return self.grads[:len(b)]
 
+    def forward_backward_aggregate(self, x, y, b):
+        """Gradients and their weighted aggregate (self.out) from one call."""
+        t = self.torch
+        xd = t.from_numpy(np.ascontiguousarray(x, np.float32)).cuda() if isinstance(x, np.ndarray) else x
+        yd = t.from_numpy(np.ascontiguousarray(y, np.int32)).cuda() if isinstance(y, np.ndarray) else y
+        binding.forward_backward_aggregate(self.model, xd, yd, b, self.grads, self.out)
+        t.cuda.synchronize()
+        return self.grads[:len(b)]
+
     def aggregate(self, b):
         binding.weighted_aggregate(self.grads, b, self.Pp, self.out)
         return self.out

@@ -124,3 +124,35 @@ def test_update_argument_checks():
         binding.model_aggregate_update(run.model, run.grads, [0, 0], binding.make_optimizer("sgd", lr=0.1))
     with pytest.raises(binding.DynbError):
         binding.adam_update(g, s, s, g, run.Pp, 0.1, 1.0, 0.999, 1e-8, 1)
+
+
+def test_forward_backward_aggregate_equals_the_two_call_form():
+    # small models (aggregate by a pass over the written gradients) and one whose weight
+    # gradients are large enough for the in-kernel sum (>= 256 tiles of 256 x 128)
+    import torch
+    cases = [(synth.mlp_spec([96, 80, 12], "f32"), [13, 0, 7, 19, 1]),
+             (synth.mlp_spec([200, 136, 10], "bf16"), [5, 60, 0, 31]),
+             (SPECS[3][1](), [3, 9, 0, 4]),
+             (synth.mlp_spec([2500, 4200, 16], "bf16"), [700, 1, 0, 257, 66])]
+    for spec, b in cases:
+        G, K = sum(b), len(b)
+        p0 = synth.init_params(spec, "he", 11)
+        x, y = synth.make_batch(spec, "normal", G, 11, 0)
+        two = GpuRun(spec, p0, G, K); one = GpuRun(spec, p0, G, K)
+        xd = torch.from_numpy(np.ascontiguousarray(x, np.float32)).cuda()
+        yd = torch.from_numpy(np.ascontiguousarray(y, np.int32)).cuda()
+        two.forward_backward(xd, yd, b); two.aggregate(b)
+        binding.forward_backward_aggregate(one.model, xd, yd, b, one.grads, one.out)
+        torch.cuda.synchronize()
+        g2, g1 = two.grads[:K].cpu().numpy(), one.grads[:K].cpu().numpy()
+        o2, o1 = two.out.cpu().numpy(), one.out.cpu().numpy()
+        assert np.all(np.isfinite(o1)) and np.all(o1[one.P:] == 0.0)
+        # per-worker gradients: same arithmetic up to the tile shape of the large case
+        assert relerr(g1, g2) < 1e-6
+        # the aggregate: the same products summed in the same (ascending k) order
+        assert relerr(o1, o2) < 1e-6, spec["layers"][0]
+        # and against the checker's definition, given the gradients the GPU wrote
+        ref = np.zeros(one.Pp)
+        for k in range(K):
+            ref += (b[k] / G) * g1[k].astype(np.float64)
+        assert relerr(o1, ref) < 1e-6
