@@ -31,6 +31,15 @@ struct Lambdas {
   float w[DYNB_MAX_WORKERS];
 };
 
+// A list of index ranges [off, off + len) of the flat parameter vector, passed to kernels by
+// value: one launch serves all the small tensors (biases, padding) of a model.
+constexpr int MAX_RANGES = 48;
+struct Ranges {
+  int n;
+  int64_t off[MAX_RANGES];
+  int64_t len[MAX_RANGES];
+};
+
 // Kernel classes for the timing aid.
 enum KClass {
   KC_GEMM_FWD = 0,
@@ -108,6 +117,9 @@ bool gemm_fuses_aggregate(int dtype, const GemmArgs& a, const Segs& s);
 // out[e] = sum_k lam.w[k] * g[k*worker_stride + e], e < n, ascending k (any alignment)
 int launch_aggregate_range(const float* g, int64_t worker_stride, const Lambdas& lam, int64_t n,
                            float* out, void* stream);
+// the same over every range r: out[off_r + e] from g[k*worker_stride + off_r + e]
+int launch_aggregate_ranges(const float* g, int64_t worker_stride, const Lambdas& lam,
+                            const Ranges& r, float* out, void* stream);
 
 // x fp32 [rows][D] -> out T [rows][ld]
 int launch_pack_rows(int dtype, const float* x, int rows, int D, void* out, int64_t ld,
@@ -162,6 +174,9 @@ int launch_update_cast(int dtype, float* params, int64_t off, const GradSource& 
 // element-wise step of parameters [off, off + n) (any alignment)
 int launch_update_range(float* params, int64_t off, const GradSource& src, const UpdateRule& rule,
                         float* s1, float* s2, int64_t n, void* stream);
+// element-wise step of every range of r
+int launch_update_ranges(float* params, const Ranges& r, const GradSource& src, const UpdateRule& rule,
+                         float* s1, float* s2, void* stream);
 // plain streaming Adam over n parameters (n a multiple of 4, 16-byte aligned pointers)
 int launch_adam(float* params, float* m, float* v, const float* g, int64_t n,
                 const UpdateRule& rule, void* stream);

@@ -51,6 +51,20 @@ __global__ __launch_bounds__(kThreads) void aggregate_range_kernel(const float* 
   }
 }
 
+// ... and over a list of such ranges (blockIdx.y = range)
+__global__ __launch_bounds__(kThreads) void aggregate_ranges_kernel(const float* __restrict__ g,
+                                                                    int64_t worker_stride,
+                                                                    Lambdas lam, Ranges r,
+                                                                    float* __restrict__ out) {
+  const int64_t off = r.off[blockIdx.y], n = r.len[blockIdx.y];
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride) {
+    float acc = 0.f;
+    for (int k = 0; k < lam.K; ++k) acc += lam.w[k] * g[(int64_t)k * worker_stride + off + i];
+    out[off + i] = acc;
+  }
+}
+
 __global__ __launch_bounds__(kThreads) void sgd_kernel(float4* __restrict__ x,
                                                        const float4* __restrict__ g, int64_t n4,
                                                        float lr) {
@@ -120,6 +134,22 @@ int launch_aggregate_range(const float* g, int64_t worker_stride, const Lambdas&
   if (blocks > 256 * 16) blocks = 256 * 16;
   hipLaunchKernelGGL(aggregate_range_kernel, dim3((unsigned)blocks), dim3(kThreads), 0,
                      (hipStream_t)stream, g, worker_stride, lam, n, out);
+  return hipGetLastError() == hipSuccess ? DYNB_OK : fail(DYNB_ERR_HIP, "aggregate launch failed");
+}
+
+int launch_aggregate_ranges(const float* g, int64_t worker_stride, const Lambdas& lam,
+                            const Ranges& r, float* out, void* stream) {
+  int64_t longest = 0, total = 0;
+  for (int i = 0; i < r.n; ++i) {
+    longest = r.len[i] > longest ? r.len[i] : longest;
+    total += r.len[i];
+  }
+  if (r.n <= 0 || longest <= 0) return DYNB_OK;
+  Timed t(KC_AGGREGATE, stream, 2.0 * lam.K * total, 4.0 * (lam.K + 1) * total);
+  int64_t bx = (longest + kThreads - 1) / kThreads;
+  if (bx > 1024) bx = 1024;
+  hipLaunchKernelGGL(aggregate_ranges_kernel, dim3((unsigned)bx, r.n), dim3(kThreads), 0,
+                     (hipStream_t)stream, g, worker_stride, lam, r, out);
   return hipGetLastError() == hipSuccess ? DYNB_OK : fail(DYNB_ERR_HIP, "aggregate launch failed");
 }
 

@@ -149,6 +149,23 @@ __global__ __launch_bounds__(256) void update_range_kernel(float* __restrict__ p
   }
 }
 
+// the same over a list of ranges (blockIdx.y = range)
+template <int KIND, bool AGG>
+__global__ __launch_bounds__(256) void update_ranges_kernel(float* __restrict__ params, Ranges r,
+                                                            GradSource src, UpdateRule rule,
+                                                            float* __restrict__ s1,
+                                                            float* __restrict__ s2) {
+  const int64_t off = r.off[blockIdx.y], n = r.len[blockIdx.y];
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const int64_t o = off + i;
+    float a = KIND != DYNB_OPT_SGD ? s1[o] : 0.f;
+    float b = KIND == DYNB_OPT_ADAM ? s2[o] : 0.f;
+    params[o] = step_one<KIND>(rule, params[o], gradient1<AGG>(src, o), a, b);
+    if (KIND != DYNB_OPT_SGD) s1[o] = a;
+    if (KIND == DYNB_OPT_ADAM) s2[o] = b;
+  }
+}
+
 // ---- plain streaming Adam ----------------------------------------------------------------------
 __global__ __launch_bounds__(256) void adam_kernel(f4* __restrict__ x, f4* __restrict__ m,
                                                    f4* __restrict__ v, const f4* __restrict__ g,
@@ -276,6 +293,42 @@ void set_adam(UpdateRule& r, double beta1, double beta2, float eps, int64_t t) {
   r.eps = eps;
   r.inv_c1 = (float)(1.0 / (1.0 - std::pow(beta1, (double)t)));
   r.inv_c2 = (float)(1.0 / (1.0 - std::pow(beta2, (double)t)));
+}
+
+namespace {
+template <int KIND>
+void launch_update_ranges_k(float* params, const Ranges& r, const GradSource& src, const UpdateRule& rule,
+                            float* s1, float* s2, dim3 grid, hipStream_t st) {
+  if (src.lam.K > 0)
+    hipLaunchKernelGGL((update_ranges_kernel<KIND, true>), grid, dim3(256), 0, st, params, r, src, rule, s1, s2);
+  else
+    hipLaunchKernelGGL((update_ranges_kernel<KIND, false>), grid, dim3(256), 0, st, params, r, src, rule, s1, s2);
+}
+}  // namespace
+
+int launch_update_ranges(float* params, const Ranges& r, const GradSource& src, const UpdateRule& rule,
+                         float* s1, float* s2, void* stream) {
+  int64_t longest = 0, total = 0;
+  for (int i = 0; i < r.n; ++i) {
+    longest = r.len[i] > longest ? r.len[i] : longest;
+    total += r.len[i];
+  }
+  if (r.n <= 0 || longest <= 0) return DYNB_OK;
+  Timed t(KC_UPDATE, stream, flops_per_param(rule, src) * total, bytes_per_param(rule, src) * total);
+  int64_t bx = (longest + 255) / 256;
+  if (bx > 1024) bx = 1024;
+  const dim3 grid((unsigned)bx, r.n);
+  switch (rule.kind) {
+    case DYNB_OPT_SGD:
+      launch_update_ranges_k<DYNB_OPT_SGD>(params, r, src, rule, s1, s2, grid, (hipStream_t)stream);
+      break;
+    case DYNB_OPT_MOMENTUM:
+      launch_update_ranges_k<DYNB_OPT_MOMENTUM>(params, r, src, rule, s1, s2, grid, (hipStream_t)stream);
+      break;
+    default:
+      launch_update_ranges_k<DYNB_OPT_ADAM>(params, r, src, rule, s1, s2, grid, (hipStream_t)stream);
+  }
+  return ok("update_ranges");
 }
 
 int launch_adam(float* params, float* m, float* v, const float* g, int64_t n,

@@ -437,6 +437,20 @@ int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const 
   lam.K = K;
   for (int k = 0; k < K; ++k) lam.w[k] = B > 0 ? (float)((double)b[k] / (double)B) : 0.f;
   if (agg && B <= 0) return fail(DYNB_ERR_BADARG, "forward_backward_aggregate: sum(b) must be positive");
+  // aggregates of the small tensors (biases, small weights, padding): one launch for all
+  Ranges small;
+  small.n = 0;
+  auto flush_small = [&]() {
+    const int r = small.n ? launch_aggregate_ranges(grads, m->P_pad, lam, small, agg, stream) : DYNB_OK;
+    small.n = 0;
+    return r;
+  };
+  auto add_small = [&](int64_t off, int64_t len) {
+    if (len <= 0) return (int)DYNB_OK;
+    small.off[small.n] = off;
+    small.len[small.n] = len;
+    return ++small.n == MAX_RANGES ? flush_small() : (int)DYNB_OK;
+  };
   for (size_t l = 0; l < nL; ++l) {
     Layer& L = m->layers[l];
     if (!L.has_params) continue;
@@ -478,19 +492,23 @@ int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const 
     rc = launch_bias_grad(dt, L.dyT, L.capT, L.n_out, grads + L.b_off, m->P_pad, segs[l], stream);
     if (rc) return rc;
     if (agg) {
-      if (!fold) {
-        rc = launch_aggregate_range(grads + L.w_off, m->P_pad, lam, (int64_t)L.wg_rows * L.n_out,
-                                    agg + L.w_off, stream);
+      const int64_t nw = (int64_t)L.wg_rows * L.n_out;
+      if (!fold && nw >= 65536) {
+        rc = launch_aggregate_range(grads + L.w_off, m->P_pad, lam, nw, agg + L.w_off, stream);
+        if (rc) return rc;
+      } else if (!fold) {
+        rc = add_small(L.w_off, nw);
         if (rc) return rc;
       }
-      rc = launch_aggregate_range(grads + L.b_off, m->P_pad, lam, L.n_out, agg + L.b_off, stream);
+      rc = add_small(L.b_off, L.n_out);
       if (rc) return rc;
     }
   }
   rc = launch_finalize(m->rowloss, m->loss, grads, m->P, m->P_pad, s1, stream);
   if (rc || !agg) return rc;
   // the padding [P, P_pad) of the aggregate: zeros, like that of the gradients
-  return launch_aggregate_range(grads + m->P, m->P_pad, lam, m->P_pad - m->P, agg + m->P, stream);
+  rc = add_small(m->P, m->P_pad - m->P);
+  return rc ? rc : flush_small();
 }
 }  // namespace
 
@@ -529,21 +547,36 @@ int make_rule(const dynb_optimizer* opt, const float* s1, const float* s2, Updat
 // convolution's weight layouts.
 int update_layers(dynb_model* m, const GradSource& src, const UpdateRule& rule, float* s1,
                   float* s2, void* stream) {
+  // all the small tensors (biases, convolution weights) in one launch per MAX_RANGES of them
+  Ranges r;
+  r.n = 0;
+  auto flush = [&]() {
+    const int rc = r.n ? launch_update_ranges(m->params, r, src, rule, s1, s2, stream) : DYNB_OK;
+    r.n = 0;
+    return rc;
+  };
+  auto add = [&](int64_t off, int64_t len) {
+    if (len <= 0) return (int)DYNB_OK;
+    r.off[r.n] = off;
+    r.len[r.n] = len;
+    return ++r.n == MAX_RANGES ? flush() : (int)DYNB_OK;
+  };
+  for (Layer& L : m->layers) {
+    if (!L.has_params) continue;
+    int rc = add(L.b_off, L.n_out);
+    if (!rc && L.kind != DYNB_LAYER_DENSE) rc = add(L.w_off, (int64_t)9 * L.n_in * L.n_out);
+    if (rc) return rc;
+  }
+  if (int rc = flush()) return rc;
   for (Layer& L : m->layers) {
     if (!L.has_params) continue;
     int rc;
-    if (L.kind == DYNB_LAYER_DENSE) {
+    if (L.kind == DYNB_LAYER_DENSE)
       rc = launch_update_cast(m->dtype, m->params, L.w_off, src, rule, s1, s2, L.n_in, L.n_out,
                               L.Wn, L.ld_out, L.Wt, L.ld_in, stream);
-    } else {
-      rc = launch_update_range(m->params, L.w_off, src, rule, s1, s2,
-                               (int64_t)9 * L.n_in * L.n_out, stream);
-      if (!rc)
-        rc = launch_conv_weight_cast(m->params + L.w_off, L.n_in, L.n_out, L.cin_p, L.cout_p, L.Wt,
-                                     L.kf, L.Wn, L.kd, stream);
-    }
-    if (rc) return rc;
-    rc = launch_update_range(m->params, L.b_off, src, rule, s1, s2, L.n_out, stream);
+    else
+      rc = launch_conv_weight_cast(m->params + L.w_off, L.n_in, L.n_out, L.cin_p, L.cout_p, L.Wt,
+                                   L.kf, L.Wn, L.kd, stream);
     if (rc) return rc;
   }
   return DYNB_OK;
