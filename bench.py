@@ -24,14 +24,12 @@ PEAK = {"mfma_bf16": 2500.0, "fp32": 157.3, "hbm": 8000.0}   # TFLOP/s, TFLOP/s,
 # size; profiles/bench_workload4_rocprofv3.md), valid for workload 4 and only as long as the
 # kernel source they were taken from is unchanged (sha1 of the file, first 12 hex digits).
 MEASURED_TRAFFIC = {
-    "gemm_wgrad": {"bytes_per_launch": 1.1099e9, "source": "paper_2305_12213_amd/csrc/gemm.hip",
-                   "sha1": "fce7f4d68b84"},
-    # the class has 8 launches per step: 4 fused aggregate+update passes (1.0475e9 bytes each on
-    # average) and 4 bias updates (a few KB)
-    "sgd_update": {"bytes_per_launch": 0.5238e9,
-                   "source": "paper_2305_12213_amd/csrc/kernels_update.hip", "sha1": "3d35c38762f8"},
-    "weighted_aggregate": {"bytes_per_launch": 3.7018e9,
-                           "source": "paper_2305_12213_amd/csrc/kernels_stream.hip", "sha1": "966a046ba1f7"},
+    "gemm_wgrad": {"bytes_per_launch": 1.2230e9, "source": "paper_2305_12213_amd/csrc/gemm.hip",
+                   "sha1": "da6af894b9ce"},
+    # the class has 5 launches per step: 4 update + weight-copy passes (2.209e8 bytes each on
+    # average) and one launch for all biases (a few KB)
+    "sgd_update": {"bytes_per_launch": 1.767e8,
+                   "source": "paper_2305_12213_amd/csrc/kernels_update.hip", "sha1": "30c256f19332"},
 }
 
 

@@ -479,6 +479,7 @@ int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const 
     // registers where the launch shape allows it, else by a pass over what was written
     const bool fold = agg && gemm_fuses_aggregate(dt, g, segs[l]);
     if (fold) {
+      g.alg_bytes += (double)L.wg_rows * L.n_out * 4;   // the aggregated tile is written too
       g.agg = agg + L.w_off;
       for (int k = 0; k < K; ++k) g.lam[k] = lam.w[k];
     }
