@@ -91,7 +91,7 @@ __device__ inline void async_copy_1k(const void* src, uint32_t lds_base) {
                : "memory", "m0");
 }
 
-// Position in the stream of 64-deep stages that one workgroup walks: stage `kt` of group `g`.
+// Position in the stream of 32-deep stages that one workgroup walks: stage `kt` of group `g`.
 // FWD/DGRAD have one group; WGRAD has one group per worker, and a workgroup runs through its
 // workers back to back so that the load pipeline never drains between them.
 struct StageCursor {

@@ -467,7 +467,7 @@ int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const 
       const int d = segs[l].poff[k + 1] - segs[l].poff[k];
       deepest = d > deepest ? d : deepest;
     }
-    int split = (deepest + 255) / 256;               // chunks of at least four 64-deep stages
+    int split = (deepest + 255) / 256;               // chunks of at least eight 32-deep stages
     split = split > L.max_split ? L.max_split : split;
     if (split > 1) {
       g.split = split;
