@@ -50,17 +50,31 @@ enum {
 };
 
 enum { DYNB_F32 = 0, DYNB_BF16 = 1 };
-enum { DYNB_LAYER_DENSE = 0, DYNB_LAYER_CONV3X3 = 1, DYNB_LAYER_GAP = 2 };
+enum {
+  DYNB_LAYER_DENSE = 0,
+  DYNB_LAYER_CONV3X3 = 1,
+  DYNB_LAYER_GAP = 2,
+  DYNB_LAYER_BN = 3,
+  DYNB_LAYER_ADD = 4
+};
 
 /* One layer.  DENSE: n_in -> n_out.  CONV3X3: c_in = n_in, c_out = n_out, 3x3 kernel,
  * zero padding 1, `stride` 1 or 2, NHWC.  GAP: global average pool over H x W (n_in,
- * n_out, stride ignored).  relu != 0 applies max(., 0) to the layer output. */
+ * n_out, stride ignored).  BN: batch normalisation of n_in = n_out channels over the rows
+ * (samples x pixels) of each worker's OWN mini-batch (biased variance, `eps` under the root),
+ * learnable scale and shift: parameters [scale n_out][shift n_out] in the flat vector.
+ * ADD: adds the stored output of layer `skip_from` (an earlier layer of the same shape; at
+ * most one ADD per source layer).  relu != 0 applies max(., 0) to the layer output.
+ * The ResNet-style blocks these two serve are the shape of the paper's first workload
+ * (Section "Experimental Evaluation"). */
 typedef struct {
   int32_t kind;
   int32_t n_in;
   int32_t n_out;
   int32_t stride;
   int32_t relu;
+  int32_t skip_from; /* ADD */
+  float eps;         /* BN */
 } dynb_layer_desc;
 
 /* dtype DYNB_F32: fp32 storage and arithmetic.  DYNB_BF16: weights (not biases),

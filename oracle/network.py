@@ -105,8 +105,33 @@ def softmax_xent(z, y):
 
 
 def _f64_params(params, emulate):
-    return [(_q(np.asarray(W, np.float64), emulate), np.asarray(b, np.float64))
+    # 16-bit copies exist of the matrix weights only; biases and batch-norm scale/shift stay fp32
+    return [(_q(np.asarray(W, np.float64), emulate and np.ndim(W) > 1), np.asarray(b, np.float64))
             for W, b in params]
+
+
+def batchnorm_forward(x, gamma, beta, eps):
+    """Batch normalisation (Ioffe & Szegedy, Algorithm 1) over all axes but the last:
+    mu, var (biased) per channel; xhat = (x - mu) / sqrt(var + eps); y = gamma xhat + beta.
+    The statistics are those of the given mini-batch, i.e. of one worker's own samples.
+    Returns (y, xhat, rstd)."""
+    axes = tuple(range(x.ndim - 1))
+    mu = x.mean(axis=axes)
+    var = ((x - mu) ** 2).mean(axis=axes)
+    rstd = 1.0 / np.sqrt(var + eps)
+    xhat = (x - mu) * rstd
+    return gamma * xhat + beta, xhat, rstd
+
+
+def batchnorm_backward(dy, xhat, rstd, gamma):
+    """Gradients of batch normalisation given dL/dy: (dx, dgamma, dbeta) with
+    dx = gamma rstd (dy - mean(dy) - xhat mean(dy xhat)) (means over the batch axes)."""
+    axes = tuple(range(dy.ndim - 1))
+    dbeta = dy.sum(axis=axes)
+    dgamma = (dy * xhat).sum(axis=axes)
+    n = dy.size // dy.shape[-1]
+    dx = gamma * rstd * (dy - dbeta / n - xhat * (dgamma / n))
+    return dx, dgamma, dbeta
 
 
 def forward(spec, params, x, emulate_bf16=False):
@@ -126,6 +151,11 @@ def forward(spec, params, x, emulate_bf16=False):
             a = conv3x3_forward(a, W, b, L["stride"])
         elif L["kind"] == "gap":
             a = a.mean(axis=(1, 2))
+        elif L["kind"] == "bn":
+            gamma, beta = P[pi]; pi += 1
+            a = batchnorm_forward(a, gamma, beta, L["eps"])[0]
+        elif L["kind"] == "add":
+            a = a + stored[L["skip_from"] + 1]   # stored[i + 1] is the stored output of layer i
         else:
             raise ValueError(L["kind"])
         if L.get("relu"):
@@ -155,6 +185,7 @@ def ambiguous_relu_units(spec, params, x, emulate_bf16=False, band=8.0):
     da = np.zeros_like(a)
     n = a.shape[0]
     out, pi = {}, 0
+    kept = {}                                   # layer index -> (stored output, its uncertainty)
     n_layers = len(spec["layers"])
     for li, L in enumerate(spec["layers"]):
         if L["kind"] == "dense":
@@ -168,6 +199,20 @@ def ambiguous_relu_units(spec, params, x, emulate_bf16=False, band=8.0):
             z = conv3x3_forward(a, W, b, L["stride"])
             noise = np.sqrt(conv3x3_forward(a * a, W * W, 0.0, L["stride"])) * np.sqrt(9 * W.shape[2])
             dz = band * 2.0 ** -24 * noise + conv3x3_forward(da, np.abs(W), 0.0, L["stride"])
+        elif L["kind"] == "bn":
+            # y = gamma (x - mu) rstd + beta.  An input uncertainty dx moves x - mu by at most
+            # dx + mean(dx) and the standard deviation by at most sqrt(mean(dx^2)); the fp32
+            # statistics of an implementation add a relative 2^-20.
+            gamma, beta = P[pi]; pi += 1
+            z, xhat, rstd = batchnorm_forward(a, gamma, beta, L["eps"])
+            axes = tuple(range(a.ndim - 1))
+            rel = rstd * np.sqrt((da * da).mean(axis=axes)) + 2.0 ** -20
+            dz = np.abs(gamma) * (rstd * (da + da.mean(axis=axes)) + np.abs(xhat) * rel) \
+                + 2.0 ** -22 * np.abs(z)
+        elif L["kind"] == "add":
+            s_a, s_da = kept[L["skip_from"]]
+            z = a + s_a
+            dz = da + s_da + 2.0 ** -23 * np.abs(z)
         else:                                   # global average pool
             z = a.mean(axis=(1, 2))
             dz = da.mean(axis=(1, 2)) + 2.0 ** -22 * np.abs(z)
@@ -179,6 +224,7 @@ def ambiguous_relu_units(spec, params, x, emulate_bf16=False, band=8.0):
             break
         a = _q(z, emulate_bf16)
         da = _q(hi, emulate_bf16) - _q(lo, emulate_bf16)
+        kept[li] = (a, da)
     return out
 
 
@@ -204,10 +250,13 @@ def loss_and_gradient(spec, params, x, y, emulate_bf16=False, relu_masks=None, t
     grads = [None] * len(P)
     pi = len(P)
     first_param_layer = next(i for i, L in enumerate(spec["layers"])
-                             if L["kind"] in ("dense", "conv3x3"))
+                             if L["kind"] in ("dense", "conv3x3", "bn"))
+    skip_grad = {}                            # layer index -> stored gradient arriving by a skip
     for li in range(len(spec["layers"]) - 1, -1, -1):
         L = spec["layers"][li]
         a_in, a_out = stored[li], stored[li + 1]
+        if li in skip_grad:                   # two consumers: both stored gradients, summed, stored
+            da = _q(da + skip_grad.pop(li), emulate_bf16)
         if L.get("relu"):
             if trace is not None:
                 trace[li] = (a_in, da)
@@ -231,6 +280,18 @@ def loss_and_gradient(spec, params, x, y, emulate_bf16=False, relu_masks=None, t
         elif L["kind"] == "gap":
             _, H, Wd, _ = a_in.shape
             da = _q(np.broadcast_to(da[:, None, None, :] / (H * Wd), a_in.shape), emulate_bf16)
+        elif L["kind"] == "bn":
+            pi -= 1
+            gamma, beta = P[pi]
+            _, xhat, rstd = batchnorm_forward(a_in, gamma, beta, L["eps"])
+            dx, dgamma, dbeta = batchnorm_backward(da, xhat, rstd, gamma)
+            grads[pi] = (dgamma, dbeta)
+            if need_dx:
+                da = _q(dx, emulate_bf16)
+        elif L["kind"] == "add":
+            src = L["skip_from"]
+            assert src not in skip_grad, "one skip connection per source layer"
+            skip_grad[src] = da               # (already a stored value; the main branch keeps da)
     return loss, grads
 
 

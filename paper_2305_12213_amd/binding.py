@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libdynb.so")
 
 F32, BF16 = 0, 1
-LAYER_DENSE, LAYER_CONV3X3, LAYER_GAP = 0, 1, 2
+LAYER_DENSE, LAYER_CONV3X3, LAYER_GAP, LAYER_BN, LAYER_ADD = 0, 1, 2, 3, 4
 MAX_WORKERS = 64
 
 SYMBOLS = [
@@ -41,7 +41,8 @@ class DynbError(RuntimeError):
 
 class LayerDesc(C.Structure):
     _fields_ = [("kind", C.c_int32), ("n_in", C.c_int32), ("n_out", C.c_int32),
-                ("stride", C.c_int32), ("relu", C.c_int32)]
+                ("stride", C.c_int32), ("relu", C.c_int32), ("skip_from", C.c_int32),
+                ("eps", C.c_float)]
 
 
 class ModelDesc(C.Structure):
@@ -172,6 +173,11 @@ def model_desc_from_spec(spec):
             layers[i] = LayerDesc(LAYER_CONV3X3, L["cin"], L["cout"], L["stride"], int(L["relu"]))
         elif L["kind"] == "gap":
             layers[i] = LayerDesc(LAYER_GAP, 0, 0, 1, 0)
+        elif L["kind"] == "bn":
+            layers[i] = LayerDesc(LAYER_BN, L["channels"], L["channels"], 1, int(L["relu"]), -1,
+                                  L["eps"])
+        elif L["kind"] == "add":
+            layers[i] = LayerDesc(LAYER_ADD, 0, 0, 1, int(L["relu"]), L["skip_from"], 0.0)
         else:
             raise ValueError(L["kind"])
     inp = tuple(spec["input"])

@@ -40,6 +40,15 @@ struct Layer {
   void* dyT = nullptr;               // T [n_out][cap]
   int64_t capT = 0;                  // padded row capacity of inT / dyT
   int max_split = 1;                 // most chunks a worker's weight-gradient reduction is cut into
+  // batch normalisation: scale at w_off, shift at b_off (n_out floats each); per-worker statistics
+  float eps = 0.f;
+  float* bn_mean = nullptr;          // fp32 [max_workers][n_out]
+  float* bn_rstd = nullptr;
+  // residual addition: this layer adds the stored output of layer skip_from; the source layer
+  // receives the gradient of that branch in dy_skip and merges it into dy
+  int skip_from = -1;
+  bool skip_source = false;
+  void* dy_skip = nullptr;           // T [rows_out][ld_out]
 };
 
 struct dynb_model {
@@ -91,6 +100,11 @@ size_t carve(dynb_model* m, void* base, int max_batch, int max_workers) {
     const int64_t rows_out = (int64_t)max_batch * L.hw_out;
     if (!last) L.out = c.take((size_t)rows_out * L.ld_out * es);
     L.dy = c.take((size_t)rows_out * L.ld_out * es);
+    if (L.skip_source) L.dy_skip = c.take((size_t)rows_out * L.ld_out * es);
+    if (L.kind == DYNB_LAYER_BN) {
+      L.bn_mean = (float*)c.take((size_t)max_workers * L.n_out * 4);
+      L.bn_rstd = (float*)c.take((size_t)max_workers * L.n_out * 4);
+    }
     if (L.has_params) {
       L.capT = padded_cap(max_batch, L.hw_out, max_workers);
       L.inT = c.take((size_t)L.wg_rows * L.capT * es);
@@ -163,7 +177,8 @@ extern "C" int dynb_model_create(const dynb_model_desc* d, dynb_model** out) {
   m->n_classes = d->n_classes;
   m->in_h = d->in_h; m->in_w = d->in_w; m->in_c = d->in_c;
   bool has_conv = false;
-  for (int l = 0; l < d->n_layers; ++l) has_conv |= d->layers[l].kind != DYNB_LAYER_DENSE;
+  for (int l = 0; l < d->n_layers; ++l)
+    has_conv |= d->layers[l].kind == DYNB_LAYER_CONV3X3 || d->layers[l].kind == DYNB_LAYER_GAP;
   // current activation geometry: h x w pixels of c channels per sample; a dense-only model
   // treats the whole input as one row of h*w*c features
   int h = has_conv ? d->in_h : 1, w = has_conv ? d->in_w : 1;
@@ -171,7 +186,7 @@ extern "C" int dynb_model_create(const dynb_model_desc* d, dynb_model** out) {
   if (!has_conv) { m->in_c = c; m->in_h = 1; m->in_w = 1; }
   m->ld0 = round_up(c, COL_PAD);
   int64_t off = 0;
-  bool seen_param = false;
+  bool seen_param = false, norm_params = false;
   for (int l = 0; l < d->n_layers; ++l) {
     const dynb_layer_desc& S = d->layers[l];
     Layer L;
@@ -207,13 +222,32 @@ extern "C" int dynb_model_create(const dynb_model_desc* d, dynb_model** out) {
       if (S.relu) return bad_model(m, DYNB_ERR_UNSUPPORTED, "ReLU on a pooling layer", l);
       L.n_out = c;
       h = 1; w = 1;
+    } else if (S.kind == DYNB_LAYER_BN) {
+      if (d->dtype != DYNB_BF16) return bad_model(m, DYNB_ERR_UNSUPPORTED, "batch normalisation is built for bf16 models only", l);
+      if (S.n_in != c || S.n_out != c) return bad_model(m, DYNB_ERR_BADARG, "channel count does not match the incoming channels", l);
+      if (!(S.eps >= 0.f) || !std::isfinite(S.eps)) return bad_model(m, DYNB_ERR_BADARG, "eps must be finite and >= 0", l);
+      L.n_out = c;
+      L.eps = S.eps;
+      L.w_off = off; L.b_off = off + c;
+      off = L.b_off + c;
+      norm_params = true;
+    } else if (S.kind == DYNB_LAYER_ADD) {
+      if (d->dtype != DYNB_BF16) return bad_model(m, DYNB_ERR_UNSUPPORTED, "residual additions are built for bf16 models only", l);
+      if (S.skip_from < 0 || S.skip_from > l - 2) return bad_model(m, DYNB_ERR_BADARG, "skip_from must name a layer at least two below", l);
+      Layer& Src = m->layers[S.skip_from];
+      if (Src.n_out != c || Src.h_out != h || Src.w_out != w) return bad_model(m, DYNB_ERR_BADARG, "the skipped output has another shape", l);
+      if (Src.skip_source) return bad_model(m, DYNB_ERR_UNSUPPORTED, "one residual addition per source layer", l);
+      Src.skip_source = true;
+      L.skip_from = S.skip_from;
+      L.n_out = c;
     } else {
       return bad_model(m, DYNB_ERR_BADARG, "unknown layer kind", l);
     }
     L.h_out = h; L.w_out = w; L.hw_out = h * w;
     L.ld_out = round_up(L.n_out, COL_PAD);
     c = L.n_out;
-    if (L.has_params && !seen_param) { m->first_param_layer = l; seen_param = true; }
+    if ((L.has_params || norm_params) && !seen_param) { m->first_param_layer = l; seen_param = true; }
+    norm_params = false;
     m->layers.push_back(L);
   }
   if (!seen_param) return bad_model(m, DYNB_ERR_BADARG, "model has no parameters", 0);
@@ -353,6 +387,19 @@ int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const 
         if (rc) return rc;
         continue;
       }
+      if (L.kind == DYNB_LAYER_BN) {
+        rc = launch_bn_forward(in_act(l), L.ld_in, L.n_out, m->params + L.w_off, m->params + L.b_off,
+                               L.eps, L.relu, L.bn_mean, L.bn_rstd, L.out, L.ld_out, segs[l], stream);
+        if (rc) return rc;
+        continue;
+      }
+      if (L.kind == DYNB_LAYER_ADD) {
+        const Layer& Src = m->layers[L.skip_from];
+        rc = launch_add_forward(in_act(l), L.ld_in, Src.out, Src.ld_out, L.n_out, rows_out, L.relu,
+                                L.out, L.ld_out, stream);
+        if (rc) return rc;
+        continue;
+      }
       GemmArgs g = {};
       g.mode = MODE_FWD;
       g.M = rows_out;
@@ -393,13 +440,38 @@ int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const 
     // ---- backward: gradient wrt every layer's output, masked by that layer's ReLU ----
     for (size_t l = nL; l-- > 0;) {
       Layer& L = m->layers[l];
+      if (L.skip_source) {   // the gradient that arrived over the residual branch joins in
+        rc = launch_grad_route(L.dy_skip, L.ld_out, nullptr, 0, L.n_out, (int64_t)B * L.hw_out, 0, 1,
+                               L.dy, L.ld_out, stream);
+        if (rc) return rc;
+      }
       if (L.has_params) {
         rc = launch_transpose(dt, L.dy, L.ld_out, L.n_out, L.dyT, L.capT, segs[l], stream);
         if (rc) return rc;
       }
-      if ((int)l <= m->first_param_layer) continue;   // nothing below needs a gradient
+      const bool below = (int)l > m->first_param_layer;   // does anything below need a gradient?
+      if (L.kind == DYNB_LAYER_BN) {
+        Layer* Lq = l > 0 ? &m->layers[l - 1] : nullptr;
+        rc = launch_bn_backward(L.dy, L.ld_out, in_act(l), L.ld_in, L.n_out, m->params + L.w_off,
+                                L.bn_mean, L.bn_rstd, grads + L.w_off, grads + L.b_off, m->P_pad,
+                                below, Lq ? Lq->relu : 0, Lq ? Lq->dy : nullptr, Lq ? Lq->ld_out : 0,
+                                segs[l], stream);
+        if (rc) return rc;
+        continue;
+      }
+      if (!below) continue;
       Layer& Lp = m->layers[l - 1];                   // producer of this layer's input
       const int rows_in = B * L.hw_in;
+      if (L.kind == DYNB_LAYER_ADD) {                 // the same gradient goes down both branches
+        Layer& Src = m->layers[L.skip_from];
+        rc = launch_grad_route(L.dy, L.ld_out, Lp.out, Lp.ld_out, L.n_out, rows_in, Lp.relu, 0, Lp.dy,
+                               Lp.ld_out, stream);
+        if (rc) return rc;
+        rc = launch_grad_route(L.dy, L.ld_out, Src.out, Src.ld_out, L.n_out, rows_in, Src.relu, 0,
+                               Src.dy_skip, Src.ld_out, stream);
+        if (rc) return rc;
+        continue;
+      }
       if (L.kind == DYNB_LAYER_GAP) {
         rc = launch_gap_backward(L.dy, L.ld_out, Lp.out, Lp.ld_out, L.hw_in, L.n_in, B, Lp.relu,
                                  Lp.dy, Lp.ld_out, stream);
@@ -453,6 +525,19 @@ int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const 
   };
   for (size_t l = 0; l < nL; ++l) {
     Layer& L = m->layers[l];
+    if (L.kind == DYNB_LAYER_BN) {
+      if (B == 0) {   // no backward pass ran: the scale / shift gradients of idle workers are zero
+        rc = launch_bn_backward(L.dy, L.ld_out, in_act(l), L.ld_in, L.n_out, m->params + L.w_off,
+                                L.bn_mean, L.bn_rstd, grads + L.w_off, grads + L.b_off, m->P_pad, 0,
+                                0, nullptr, 0, segs[l], stream);
+        if (rc) return rc;
+      }
+      if (agg) {
+        rc = add_small(L.w_off, 2 * (int64_t)L.n_out);
+        if (rc) return rc;
+      }
+      continue;
+    }
     if (!L.has_params) continue;
     GemmArgs g = {};
     g.mode = MODE_WGRAD;
@@ -563,6 +648,10 @@ int update_layers(dynb_model* m, const GradSource& src, const UpdateRule& rule, 
     return ++r.n == MAX_RANGES ? flush() : (int)DYNB_OK;
   };
   for (Layer& L : m->layers) {
+    if (L.kind == DYNB_LAYER_BN) {
+      if (int rc = add(L.w_off, 2 * (int64_t)L.n_out)) return rc;
+      continue;
+    }
     if (!L.has_params) continue;
     int rc = add(L.b_off, L.n_out);
     if (!rc && L.kind != DYNB_LAYER_DENSE) rc = add(L.w_off, (int64_t)9 * L.n_in * L.n_out);

@@ -31,6 +31,32 @@ def gap():
     return {"kind": "gap"}
 
 
+def batchnorm(channels, relu, eps=1e-5):
+    """Batch normalisation over each worker's own rows (samples x pixels), learnable scale
+    and shift per channel, optional ReLU."""
+    return {"kind": "bn", "channels": int(channels), "relu": bool(relu), "eps": float(eps)}
+
+
+def add(skip_from, relu):
+    """Residual connection: adds the output of layer `skip_from` (same shape), optional ReLU."""
+    return {"kind": "add", "skip_from": int(skip_from), "relu": bool(relu)}
+
+
+def resnet_block_spec(channels=16, image=(8, 8, 3), classes=10, blocks=1):
+    """conv stem, then `blocks` basic residual blocks (conv-BN-ReLU-conv-BN, + skip, ReLU),
+    global average pool and a linear classifier (the shape of the paper's ResNet workload,
+    scaled down; bf16)."""
+    C = int(channels)
+    layers = [conv3x3(image[2], C, 1, relu=True)]
+    for _ in range(blocks):
+        src = len(layers) - 1
+        layers += [conv3x3(C, C, 1, relu=False), batchnorm(C, relu=True),
+                   conv3x3(C, C, 1, relu=False), batchnorm(C, relu=False),
+                   add(src, relu=True)]
+    layers += [gap(), dense(C, classes, relu=False)]
+    return {"dtype": "bf16", "input": tuple(image), "layers": layers, "classes": int(classes)}
+
+
 def mlp_spec(dims, dtype):
     layers = [dense(dims[i], dims[i + 1], relu=(i + 2 < len(dims)))
               for i in range(len(dims) - 1)]
@@ -97,6 +123,8 @@ def param_shapes(spec):
             shapes.append(((L["in"], L["out"]), (L["out"],)))
         elif L["kind"] == "conv3x3":
             shapes.append(((3, 3, L["cin"], L["cout"]), (L["cout"],)))
+        elif L["kind"] == "bn":                      # scale ("W") and shift ("bias")
+            shapes.append(((L["channels"],), (L["channels"],)))
     return shapes
 
 
@@ -113,6 +141,9 @@ def init_params(spec, init, seed):
     rng = np.random.Generator(np.random.PCG64([int(seed), 1]))
     out = []
     for wshape, bshape in param_shapes(spec):
+        if len(wshape) == 1:                         # batch-norm scale 1, shift 0
+            out.append((np.ones(wshape, np.float32), np.zeros(bshape, np.float32)))
+            continue
         fan_in = int(np.prod(wshape[:-1]))
         std = np.sqrt(2.0 / fan_in) if init == "he" else 0.01
         W = (rng.standard_normal(wshape) * std).astype(np.float32)

@@ -19,8 +19,67 @@ import numpy as np
 from oracle import network as on
 
 
+PARAM_KINDS = ("dense", "conv3x3", "bn")
+
+
 def _param_index(spec, li):
-    return sum(1 for L in spec["layers"][:li] if L["kind"] in ("dense", "conv3x3"))
+    return sum(1 for L in spec["layers"][:li] if L["kind"] in PARAM_KINDS)
+
+
+def _needs_generic(spec):
+    """The column signatures below exist for ReLUs that sit directly on a dense or convolution
+    layer; anything else (batch normalisation, residual additions) takes the generic route."""
+    return any(L["kind"] in ("bn", "add") for L in spec["layers"])
+
+
+def _resolved_generic(spec, params, x, y, got, emulate_bf16, band):
+    """Same idea with signatures obtained by re-evaluation: flipping one ambiguous unit of a ReLU
+    layer changes the gradient by a fixed vector (the backward pass is linear in the gradient
+    signal, so the flips of one layer add up).  That vector is measured on the parameters between
+    this ReLU layer and the next one below -- they feel this layer's decisions and none of the
+    lower layers' -- and the flips are fitted to the residual there."""
+    loss, base = on.loss_and_gradient(spec, params, x, y, emulate_bf16)
+    amb = on.ambiguous_relu_units(spec, params, x, emulate_bf16, band)
+    n_amb = int(sum(a.sum() for a in amb.values()))
+    if n_amb == 0:
+        return base, loss, 0, 0
+    masks = on.relu_masks_of(spec, params, x, emulate_bf16)
+    relu_layers = sorted(masks)
+    flipped = 0
+
+    def flat(g, pis):
+        return np.concatenate([np.concatenate([np.ravel(g[pi][0]), np.ravel(g[pi][1])]) for pi in pis])
+
+    for li in sorted(amb, reverse=True):
+        units = [tuple(t) for t in np.argwhere(amb[li])]
+        if not units:
+            continue
+        lower = max([r for r in relu_layers if r < li], default=-1)
+        pis = [_param_index(spec, l) for l in range(lower + 1, li + 1)
+               if spec["layers"][l]["kind"] in PARAM_KINDS]
+        if not pis:
+            continue
+        _, cur = on.loss_and_gradient(spec, params, x, y, emulate_bf16, relu_masks=masks)
+        resid = flat([(np.asarray(W, np.float64), np.asarray(b, np.float64)) for W, b in got], pis) \
+            - flat(cur, pis)
+        cols = []
+        for t in units:
+            masks[li][t] ^= True
+            _, g1 = on.loss_and_gradient(spec, params, x, y, emulate_bf16, relu_masks=masks)
+            masks[li][t] ^= True
+            cols.append(flat(g1, pis) - flat(cur, pis))
+        S = np.stack(cols, axis=1)
+        live = np.abs(S).max(axis=0) > 0
+        if not live.any():
+            continue
+        c = np.zeros(S.shape[1])
+        c[live] = np.linalg.lstsq(S[:, live], resid, rcond=None)[0]
+        for t, cj in zip(units, c):
+            if cj > 0.5:
+                masks[li][t] ^= True
+                flipped += 1
+    _, final = on.loss_and_gradient(spec, params, x, y, emulate_bf16, relu_masks=masks)
+    return final, loss, n_amb, flipped
 
 
 def resolved_reference(spec, params, x, y, got, emulate_bf16=False, band=8.0):
@@ -31,6 +90,8 @@ def resolved_reference(spec, params, x, y, got, emulate_bf16=False, band=8.0):
     loss, base = on.loss_and_gradient(spec, params, x, y, emulate_bf16)
     if np.shape(x)[0] == 0:
         return base, loss, 0, 0
+    if _needs_generic(spec):
+        return _resolved_generic(spec, params, x, y, got, emulate_bf16, band)
     amb = on.ambiguous_relu_units(spec, params, x, emulate_bf16, band)
     n_amb = int(sum(a.sum() for a in amb.values()))
     if n_amb == 0:

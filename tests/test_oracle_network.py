@@ -21,6 +21,13 @@ def tiny_cnn():
                        synth.dense(4, 3, relu=False)]}
 
 
+def tiny_resnet():
+    # stem, one residual block (conv-BN-ReLU-conv-BN, + skip, ReLU), pool, classifier
+    spec = synth.resnet_block_spec(channels=3, image=(4, 4, 2), classes=3)
+    spec["dtype"] = "f32"
+    return spec
+
+
 def rand_params(spec, seed, bias=True):
     rng = np.random.default_rng(seed)
     out = []
@@ -36,7 +43,7 @@ def mean_loss(spec, params, x, y):
     return float(np.mean(lse - z[np.arange(len(y)), y]))
 
 
-@pytest.mark.parametrize("make_spec", [tiny_mlp, tiny_cnn])
+@pytest.mark.parametrize("make_spec", [tiny_mlp, tiny_cnn, tiny_resnet])
 def test_gradient_matches_central_finite_differences(make_spec):
     spec = make_spec()
     rng = np.random.default_rng(3)
@@ -333,3 +340,76 @@ def test_stepwise_learning_rate_uses_the_papers_values():
     got = [on.stepwise_learning_rate(s, bounds, values) for s in (0, 99, 100, 149, 150, 199, 200, 10**6)]
     assert got == [0.1, 0.1, 0.01, 0.01, 0.001, 0.001, 0.0002, 0.0002]
     assert on.stepwise_learning_rate(5, [], [0.3]) == 0.3
+
+
+def test_batchnorm_textbook_properties():
+    rng = np.random.default_rng(12)
+    x = rng.standard_normal((6, 3, 2, 5)) * 3.0 + 1.5
+    gamma, beta = rng.standard_normal(5), rng.standard_normal(5)
+    y, xhat, rstd = on.batchnorm_forward(x, gamma, beta, 0.0)
+    # normalised activations: zero mean, unit (biased) variance per channel; y is affine in xhat
+    np.testing.assert_allclose(xhat.mean(axis=(0, 1, 2)), 0.0, atol=1e-12)
+    np.testing.assert_allclose((xhat ** 2).mean(axis=(0, 1, 2)), 1.0, rtol=1e-12)
+    np.testing.assert_allclose(y, gamma * xhat + beta, rtol=1e-12)
+    # against the library routine (training mode, biased variance, eps as given)
+    t = torch.nn.functional.batch_norm(torch.from_numpy(x).permute(0, 3, 1, 2), None, None,
+                                       torch.from_numpy(gamma), torch.from_numpy(beta),
+                                       training=True, eps=1e-5)
+    y5 = on.batchnorm_forward(x, gamma, beta, 1e-5)[0]
+    np.testing.assert_allclose(y5, t.permute(0, 2, 3, 1).numpy(), rtol=1e-10, atol=1e-10)
+    # invariance: shifting and scaling a channel of the input does not change the output
+    y2 = on.batchnorm_forward(x * 7.0 - 3.0, gamma, beta, 0.0)[0]
+    np.testing.assert_allclose(y2, y, rtol=1e-10, atol=1e-10)
+    # the input gradient is orthogonal to the two directions the layer ignores
+    dy = rng.standard_normal(x.shape)
+    dx, dgamma, dbeta = on.batchnorm_backward(dy, xhat, rstd, gamma)
+    np.testing.assert_allclose(dx.sum(axis=(0, 1, 2)), 0.0, atol=1e-10)
+    np.testing.assert_allclose((dx * xhat).sum(axis=(0, 1, 2)), 0.0, atol=1e-10)
+    np.testing.assert_allclose(dbeta, dy.sum(axis=(0, 1, 2)), rtol=1e-12)
+    # and matches autograd of the library routine
+    xt = torch.from_numpy(x).permute(0, 3, 1, 2).clone().requires_grad_(True)
+    gt = torch.from_numpy(gamma).clone().requires_grad_(True)
+    bt = torch.from_numpy(beta).clone().requires_grad_(True)
+    out = torch.nn.functional.batch_norm(xt, None, None, gt, bt, training=True, eps=1e-5)
+    out.backward(torch.from_numpy(dy).permute(0, 3, 1, 2))
+    _, xhat5, rstd5 = on.batchnorm_forward(x, gamma, beta, 1e-5)
+    dx5, dgamma5, _ = on.batchnorm_backward(dy, xhat5, rstd5, gamma)
+    np.testing.assert_allclose(dx5, xt.grad.permute(0, 2, 3, 1).numpy(), rtol=1e-8, atol=1e-10)
+    np.testing.assert_allclose(dgamma5, gt.grad.numpy(), rtol=1e-10)
+
+
+def test_batchnorm_statistics_are_per_worker_so_split_invariance_is_lost():
+    # the weighted average over workers is NOT the whole-batch gradient once a layer normalises
+    # over each worker's own samples; with a single worker it trivially is
+    spec = tiny_resnet()
+    params = rand_params(spec, 2)
+    rng = np.random.default_rng(4)
+    x = rng.standard_normal((8,) + tuple(spec["input"])); y = rng.integers(0, 3, 8)
+    _, whole = on.worker_gradients(spec, params, x, y, [8])
+    _, parts = on.worker_gradients(spec, params, x, y, [5, 3])
+    agg = on.weighted_aggregate(parts, [5, 3])
+    diff = max(np.max(np.abs(a[0] - w[0])) for a, w in zip(agg, whole[0]))
+    assert diff > 1e-3
+    one = on.weighted_aggregate(whole, [8])
+    assert max(np.max(np.abs(a[0] - w[0])) for a, w in zip(one, whole[0])) < 1e-15
+
+
+def test_residual_add_sends_the_same_gradient_down_both_branches():
+    # y = a + skip with no ReLU anywhere in between: d/d(skip source) gets the sum of both paths
+    spec = {"dtype": "f32", "input": (3, 3, 2), "classes": 2,
+            "layers": [synth.conv3x3(2, 2, 1, relu=False), synth.conv3x3(2, 2, 1, relu=False),
+                       synth.add(0, relu=False), synth.gap(), synth.dense(2, 2, relu=False)]}
+    rng = np.random.default_rng(6)
+    params = rand_params(spec, 7)
+    x = rng.standard_normal((2, 3, 3, 2)); y = rng.integers(0, 2, 2)
+    _, g = on.loss_and_gradient(spec, params, x, y)
+    # zeroing the second convolution leaves the identity path: layer 0's gradient is then the
+    # gradient of the network conv -> pool -> classifier
+    params0 = [params[0], (np.zeros_like(params[1][0]), np.zeros_like(params[1][1])), params[2]]
+    plain = {"dtype": "f32", "input": (3, 3, 2), "classes": 2,
+             "layers": [synth.conv3x3(2, 2, 1, relu=False), synth.gap(), synth.dense(2, 2, relu=False)]}
+    _, g0 = on.loss_and_gradient(spec, params0, x, y)
+    _, gp = on.loss_and_gradient(plain, [params[0], params[2]], x, y)
+    np.testing.assert_allclose(g0[0][0], gp[0][0], rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(g0[2][0], gp[1][0], rtol=1e-12, atol=1e-14)
+    assert np.max(np.abs(g[0][0] - gp[0][0])) > 1e-6      # with the branch it differs

@@ -75,3 +75,63 @@ def test_planted_tie_in_a_conv_layer_is_resolved():
     _, got = on.loss_and_gradient(spec, params, x, y, relu_masks=other)
     ref, _, _, n_flip = resolved_reference(spec, params, x, y, got)
     assert n_flip == 1 and maxdiff(got, ref) < 1e-13
+
+
+def _resnet_case():
+    spec = synth.resnet_block_spec(channels=4, image=(6, 6, 2), classes=3)
+    rng = np.random.default_rng(8)
+    params = []
+    for ws, bs in synth.param_shapes(spec):
+        if len(ws) == 1:
+            params.append((1.0 + 0.2 * rng.standard_normal(ws), 0.2 * rng.standard_normal(bs)))
+        else:
+            params.append((rng.standard_normal(ws) * 0.4, 0.1 * rng.standard_normal(bs)))
+    x = rng.standard_normal((12, 6, 6, 2)); y = rng.integers(0, 3, 12)
+    return spec, params, x, y
+
+
+def test_ties_behind_batchnorm_and_residual_layers_are_resolved():
+    # bfloat16 storage makes a good share of the units ambiguous; decide some of them, in the
+    # ReLU behind the batch normalisation and in the one behind the residual addition, the other
+    # way and let the generic route find them
+    spec, params, x, y = _resnet_case()
+    relu_layers = [li for li, L in enumerate(spec["layers"]) if L.get("relu")]
+    assert relu_layers == [0, 2, 5]
+    # put two units behind the first batch normalisation (channels 1 and 3) next to zero by
+    # moving the shift of their channels
+    _, stored = on.forward(spec, params, x, True)
+    gamma, beta = params[2]
+    z2 = on.batchnorm_forward(stored[2], gamma, beta, spec["layers"][2]["eps"])[0]
+    beta = beta.copy()
+    beta[1] -= z2[3, 2, 4, 1] - 1e-9
+    beta[3] -= z2[7, 0, 1, 3] + 1e-9
+    params[2] = (gamma, beta)
+    amb = on.ambiguous_relu_units(spec, params, x, True)
+    assert amb[2][3, 2, 4, 1] and amb[2][7, 0, 1, 3]
+    masks = on.relu_masks_of(spec, params, x, True)
+    other = {k: v.copy() for k, v in masks.items()}
+    planted = 0
+    for li in (2, 5):
+        cand = np.argwhere(amb[li])
+        assert len(cand) >= 2, (li, len(cand))
+        for t in cand[:2]:
+            other[li][tuple(t)] ^= True
+            planted += 1
+    _, got = on.loss_and_gradient(spec, params, x, y, True, relu_masks=other)
+    _, base = on.loss_and_gradient(spec, params, x, y, True)
+    assert maxdiff(got, base) > 1e-6
+    ref, _, n_amb, n_flip = resolved_reference(spec, params, x, y, got, True)
+    assert n_flip == planted and n_amb >= planted
+    assert maxdiff(got, ref) < 1e-12
+
+
+def test_generic_route_does_not_explain_away_a_wrong_clear_cut_unit():
+    spec, params, x, y = _resnet_case()
+    amb = on.ambiguous_relu_units(spec, params, x, True)
+    masks = on.relu_masks_of(spec, params, x, True)
+    t = tuple(np.argwhere(~amb[2] & masks[2])[0])
+    wrong = {k: v.copy() for k, v in masks.items()}
+    wrong[2][t] = False
+    _, got = on.loss_and_gradient(spec, params, x, y, True, relu_masks=wrong)
+    ref, _, _, _ = resolved_reference(spec, params, x, y, got, True)
+    assert maxdiff(got, ref) > 1e-6
