@@ -39,7 +39,7 @@ extern "C" {
 #endif
 
 #define DYNB_MAX_WORKERS 64
-#define DYNB_MAX_LAYERS 16
+#define DYNB_MAX_LAYERS 64
 
 enum {
   DYNB_OK = 0,

@@ -54,6 +54,7 @@ enum KClass {
   KC_UPDATE,
   KC_WEIGHT_CAST,
   KC_CONV_AUX,
+  KC_NORM,
   KC_COUNT
 };
 
@@ -195,23 +196,29 @@ int launch_gap_backward(const void* dpooled, int64_t ldp, const void* act, int64
 int launch_conv_weight_cast(const float* W, int Cin, int Cout, int cin_p, int cout_p, void* Wf,
                             int kf, void* Wd, int kd, void* stream);
 
-// ---- batch normalisation over each worker's rows, residual additions (bf16 storage) ----
-// y = relu?(gamma * (x - mean_k) / sqrt(var_k + eps) + beta); mean / rstd: fp32 [K][C] (kept
-// for the backward pass)
+// Batch normalisation over each worker's own rows (bf16; x: T [rows][ldx], y: T [rows][ldy]):
+// writes mean / rstd [k][C] (kept for the backward pass).  `scratch`: row_scratch_floats() floats
+// (the partial results of the row chunks), shared by forward and backward.
+constexpr int BN_CHUNK_ROWS = 256;
+int64_t row_scratch_floats(int64_t max_rows, int max_workers, int C);
 int launch_bn_forward(const void* x, int64_t ldx, int C, const float* gamma, const float* beta,
-                      float eps, int relu, float* mean, float* rstd, void* y, int64_t ldy,
-                      const Segs& s, void* stream);
+                      float eps, int relu, float* mean, float* rstd, float* scratch, void* y,
+                      int64_t ldy, const Segs& s, void* stream);
 // dgamma / dbeta[k * group_stride + c] (fp32, per worker) from dy (already masked by the layer's
 // own ReLU); with need_dx also dx (T [rows][ldo]), masked by x > 0 when relu_below
 int launch_bn_backward(const void* dy, int64_t ldd, const void* x, int64_t ldx, int C,
-                       const float* gamma, const float* mean, const float* rstd, float* dgamma,
-                       float* dbeta, int64_t group_stride, int need_dx, int relu_below, void* dx,
-                       int64_t ldo, const Segs& s, void* stream);
-// out = relu?(a + b)
-int launch_add_forward(const void* a, int64_t lda, const void* b, int64_t ldb, int C, int64_t rows,
-                       int relu, void* out, int64_t ldo, void* stream);
-// dst = (accumulate ? dst : 0) + (relu ? src where act > 0 : src)
-int launch_grad_route(const void* src, int64_t lds_, const void* act, int64_t lda, int C,
+                       const float* gamma, const float* mean, const float* rstd, float* scratch,
+                       float* dgamma, float* dbeta, int64_t group_stride, int need_dx,
+                       int relu_below, void* dx, int64_t ldo, const Segs& s, void* stream);
+// out[k * group_stride + c] = sum of dy[row][c] over worker k's rows (bf16 dy, T [rows][ldd]):
+// the bias gradient of a layer whose rows are pixels; same scratch as above
+int launch_column_sums(const void* dy, int64_t ldd, int C, float* scratch, float* out,
+                       int64_t group_stride, const Segs& s, void* stream);
+// out = relu?(a + b) over `width` (padded, a multiple of 8) columns of `rows` rows
+int launch_add_forward(const void* a, int64_t lda, const void* b, int64_t ldb, int64_t width,
+                       int64_t rows, int relu, void* out, int64_t ldo, void* stream);
+// dst = (accumulate ? dst : 0) + (relu ? src where act > 0 : src), same extent convention
+int launch_grad_route(const void* src, int64_t lds_, const void* act, int64_t lda, int64_t width,
                       int64_t rows, int relu, int accumulate, void* dst, int64_t ldd, void* stream);
 
 }  // namespace dynb

@@ -3,13 +3,12 @@
 // pooling forward/backward, and the two 16-bit weight layouts of a convolution.
 #include <hip/hip_runtime.h>
 
+#include "device_rows.h"
 #include "dynb_internal.h"
 
 namespace dynb {
 namespace {
 
-typedef __bf16 bf16;
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 __device__ inline void locate_padded(const Segs& s, int prow, int& k, int& r) {
   k = 0;
@@ -19,61 +18,119 @@ __device__ inline void locate_padded(const Segs& s, int prow, int& k, int& r) {
 
 // out[(kh*3 + kw)*C + c][p] = in[(n, ho*stride + kh - 1, wo*stride + kw - 1)][c] for the output
 // pixel (n, ho, wo) that sits at padded position p (pixel-level segments `s`), zero for
-// padding positions and out-of-range taps.  One thread writes 8 consecutive positions.
+// padding positions and out-of-range taps.  A workgroup takes 64 positions x 64 channels and
+// walks the nine taps: the source rows are read as whole 128-byte lines (8 lanes x 16 bytes),
+// turned in LDS, and written as 128-byte runs of 64 positions per (tap, channel) row.
 __global__ __launch_bounds__(256) void im2col_t_kernel(const bf16* __restrict__ in, int64_t ldi,
                                                        int C, int H, int W, int Ho, int Wo,
                                                        int stride, bf16* __restrict__ out,
                                                        int64_t ldo, Segs s) {
+  // 33 dwords per position: the turned reads of 8 lanes (8 positions apart) fall in 8 banks
+  __shared__ uint32_t tile[64][33];
   const int P = s.poff[s.K];
-  const int pg = blockIdx.x * 256 + threadIdx.x;   // granule of 8 padded positions
-  const int row = blockIdx.y;                      // (kh*3 + kw)*C + c
-  if (pg * 8 >= P) return;
-  const int tap = row / C, c = row - tap * C;
-  const int kh = tap / 3, kw = tap - kh * 3;
-  bf16x8 v;
+  const int p0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
+  const int lo = threadIdx.x & 7, hi = threadIdx.x >> 3;
+  // reading: this thread fetches channels [c0 + 8*lo, +8) of positions hi and hi + 32
+  int img[2], ho[2], wo[2];
+  bool live[2];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const int p = pg * 8 + e;
-    float val = 0.f;
-    int k, r;
-    locate_padded(s, p, k, r);
-    if (r < s.off[k + 1] - s.off[k]) {
-      const int m = s.off[k] + r;                  // dense output pixel
-      const int n = m / (Ho * Wo), rem = m - n * (Ho * Wo);
-      const int ho = rem / Wo, wo = rem - ho * Wo;
-      const int y = ho * stride + kh - 1, x = wo * stride + kw - 1;
-      if (y >= 0 && y < H && x >= 0 && x < W)
-        val = (float)in[((int64_t)(n * H + y) * W + x) * ldi + c];
+  for (int q = 0; q < 2; ++q) {
+    const int p = p0 + hi + 32 * q;
+    live[q] = false;
+    img[q] = ho[q] = wo[q] = 0;
+    if (p < P) {
+      int k, r;
+      locate_padded(s, p, k, r);
+      if (r < s.off[k + 1] - s.off[k]) {
+        const int m = s.off[k] + r;                // dense output pixel
+        img[q] = m / (Ho * Wo);
+        const int rem = m - img[q] * (Ho * Wo);
+        ho[q] = rem / Wo;
+        wo[q] = rem - ho[q] * Wo;
+        live[q] = true;
+      }
     }
-    v[e] = (bf16)val;
   }
-  *(bf16x8*)(out + (int64_t)row * ldo + pg * 8) = v;
+  // writing: 8 positions [p0 + 8*lo, +8) of channels hi and hi + 32
+  const bool write_ok = p0 + 8 * lo < P;
+  for (int tap = 0; tap < 9; ++tap) {
+    const int kh = tap / 3, kw = tap - kh * 3;
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      uint4 v = make_uint4(0, 0, 0, 0);
+      const int y = ho[q] * stride + kh - 1, x = wo[q] * stride + kw - 1;
+      if (live[q] && y >= 0 && y < H && x >= 0 && x < W)
+        v = load8(in + ((int64_t)(img[q] * H + y) * W + x) * ldi + c0 + 8 * lo);
+      uint32_t* t = &tile[hi + 32 * q][4 * lo];
+      t[0] = v.x; t[1] = v.y; t[2] = v.z; t[3] = v.w;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const int c = hi + 32 * q;
+      if (write_ok && c0 + c < C) {
+        uint32_t w[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {              // positions 8*lo + 2e and + 2e + 1, channel c
+          const uint32_t a = tile[8 * lo + 2 * e][c >> 1], b = tile[8 * lo + 2 * e + 1][c >> 1];
+          w[e] = (c & 1) ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
+        }
+        store8(out + (int64_t)(tap * C + c0 + c) * ldo + p0 + 8 * lo, make_uint4(w[0], w[1], w[2], w[3]));
+      }
+    }
+    __syncthreads();
+  }
 }
 
-// pooled[n][c] = mean over the HW pixels of act[(n, pixel)][c]   (fp32 sum, bf16 store)
+// pooled[n][c] = mean over the HW pixels of act[(n, pixel)][c]   (fp32 sum in a fixed order,
+// bf16 store).  One workgroup per (sample, 64 channels); padding channels are written as zero.
 __global__ __launch_bounds__(256) void gap_forward_kernel(const bf16* __restrict__ act, int64_t lda,
-                                                          int HW, int C, int samples,
-                                                          bf16* __restrict__ pooled, int64_t ldp) {
-  const int c = blockIdx.x * 256 + threadIdx.x, n = blockIdx.y;
-  if (c >= C || n >= samples) return;
-  float acc = 0.f;
-  for (int px = 0; px < HW; ++px) acc += (float)act[((int64_t)n * HW + px) * lda + c];
-  pooled[(int64_t)n * ldp + c] = (bf16)(acc / (float)HW);
+                                                          int HW, int C, bf16* __restrict__ pooled,
+                                                          int64_t ldp) {
+  __shared__ float red[4][64];
+  const int cg = threadIdx.x & 7, rl = threadIdx.x >> 3;
+  const int n = blockIdx.x, c0 = blockIdx.y * 64 + cg * 8;
+  const bf16* base = act + (int64_t)n * HW * lda + c0;
+  float acc[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+  for (int px = rl; px < HW; px += 32) {
+    float v[8];
+    unpack8(load8(base + (int64_t)px * lda), v);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] += v[j];
+  }
+  sum_over_rows(acc, red);
+  if (rl == 0) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = c0 + j < C ? acc[j] / (float)HW : 0.f;
+    store8(pooled + (int64_t)n * ldp + c0, pack8(acc));
+  }
 }
 
 // d act[(n, pixel)][c] = d pooled[n][c] / HW, masked by act > 0 when the pooled layer's producer
-// applied a ReLU
+// applied a ReLU.  One lane per 8 channels of a row; `gpr` = 16-byte granules per row.
 __global__ __launch_bounds__(256) void gap_backward_kernel(const bf16* __restrict__ dpooled,
                                                            int64_t ldp, const bf16* __restrict__ act,
-                                                           int64_t lda, int HW, int C, int samples,
+                                                           int64_t lda, int HW, int gpr, int64_t total,
                                                            int relu, bf16* __restrict__ dact,
                                                            int64_t ldd) {
-  const int c = blockIdx.x * 256 + threadIdx.x;
-  const int64_t row = blockIdx.y;   // (n, pixel)
-  if (c >= C || row >= (int64_t)samples * HW) return;
-  float v = (float)dpooled[(row / HW) * ldp + c] / (float)HW;
-  if (relu && !((float)act[row * lda + c] > 0.f)) v = 0.f;
-  dact[row * ldd + c] = (bf16)v;
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int64_t row = i / gpr;   // (n, pixel)
+  const int c0 = (int)(i - row * gpr) * 8;
+  float v[8];
+  unpack8(load8(dpooled + (row / HW) * ldp + c0), v);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) v[j] = v[j] / (float)HW;
+  if (relu) {
+    float a[8];
+    unpack8(load8(act + row * lda + c0), a);
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (!(a[j] > 0.f)) v[j] = 0.f;
+  }
+  store8(dact + row * ldd + c0, pack8(v));
 }
 
 // W fp32 [3][3][Cin][Cout] ->
@@ -112,8 +169,10 @@ int launch_im2col_t(const void* in, int64_t ldi, int C, int H, int W, int Ho, in
                     void* out, int64_t ldo, const Segs& s, void* stream) {
   const int P = s.poff[s.K];
   if (P == 0) return DYNB_OK;
+  if (ldi % 64 || ldo % 64 || ldo < P)
+    return fail(DYNB_ERR_BADARG, "im2col_t: pitches must be multiples of 64 and cover the positions");
   Timed t(KC_CONV_AUX, stream, 0, 2.0 * 9 * C * (double)s.off[s.K] * 2);
-  dim3 grid((P / 8 + 255) / 256, 9 * C);
+  dim3 grid((P + 63) / 64, (C + 63) / 64);
   hipLaunchKernelGGL(im2col_t_kernel, grid, dim3(256), 0, (hipStream_t)stream, (const bf16*)in, ldi,
                      C, H, W, Ho, Wo, stride, (bf16*)out, ldo, s);
   return ok("im2col_t");
@@ -122,21 +181,25 @@ int launch_im2col_t(const void* in, int64_t ldi, int C, int H, int W, int Ho, in
 int launch_gap_forward(const void* act, int64_t lda, int HW, int C, int samples, void* pooled,
                        int64_t ldp, void* stream) {
   if (samples == 0) return DYNB_OK;
+  if (lda % 64 || ldp % 64 || lda < ldp) return fail(DYNB_ERR_BADARG, "gap_forward: bad pitches");
   Timed t(KC_CONV_AUX, stream, 0, (double)samples * HW * C * 2);
-  dim3 grid((C + 255) / 256, samples);
+  dim3 grid(samples, (unsigned)(ldp / 64));
   hipLaunchKernelGGL(gap_forward_kernel, grid, dim3(256), 0, (hipStream_t)stream, (const bf16*)act,
-                     lda, HW, C, samples, (bf16*)pooled, ldp);
+                     lda, HW, C, (bf16*)pooled, ldp);
   return ok("gap_forward");
 }
 
 int launch_gap_backward(const void* dpooled, int64_t ldp, const void* act, int64_t lda, int HW,
                         int C, int samples, int relu, void* dact, int64_t ldd, void* stream) {
   if (samples == 0) return DYNB_OK;
+  if (lda % 64 || ldp % 64 || ldd % 64 || ldp < ldd || lda < ldd)
+    return fail(DYNB_ERR_BADARG, "gap_backward: bad pitches");
+  const int gpr = (int)(ldd / 8);
+  const int64_t total = (int64_t)samples * HW * gpr;
   Timed t(KC_CONV_AUX, stream, 0, (double)samples * HW * C * 4);
-  dim3 grid((C + 255) / 256, samples * HW);
-  hipLaunchKernelGGL(gap_backward_kernel, grid, dim3(256), 0, (hipStream_t)stream,
-                     (const bf16*)dpooled, ldp, (const bf16*)act, lda, HW, C, samples, relu,
-                     (bf16*)dact, ldd);
+  hipLaunchKernelGGL(gap_backward_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
+                     (hipStream_t)stream, (const bf16*)dpooled, ldp, (const bf16*)act, lda, HW, gpr,
+                     total, relu, (bf16*)dact, ldd);
   return ok("gap_backward");
 }
 

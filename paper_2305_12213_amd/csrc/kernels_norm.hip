@@ -1,206 +1,463 @@
 // Batch normalisation over each worker's own rows and residual additions (bf16 storage).
-// A "row" is a sample or a pixel; worker k owns rows [off_k, off_{k+1}).  The statistics of
-// a worker never see another worker's rows, so every reduction here runs per (worker, channel):
-// one workgroup takes 64 channels of one worker, 4 row-lanes per channel, rows read as 128
-// contiguous bytes.  All sums are fp32 in a fixed order (deterministic).
+// A "row" is a sample or a pixel; worker k owns rows [off_k, off_{k+1}).  The statistics of a
+// worker never see another worker's rows, so every reduction here runs per (worker, channel).
+// The rows of a worker are cut into chunks of CHUNK_ROWS; one workgroup takes one chunk and 64
+// channels (a lane: 8 channels of a row = one 16-byte access, 8 lanes = the 128 bytes of a row,
+// 32 rows per pass), writes the chunk's partial result, and a second small kernel merges the
+// chunks of each worker in a fixed order.  All sums are fp32 and deterministic.
 #include <hip/hip_runtime.h>
 
+#include "device_rows.h"
 #include "dynb_internal.h"
 
 namespace dynb {
 namespace {
 
-typedef __bf16 bf16;
+constexpr int CHUNK_ROWS = BN_CHUNK_ROWS;
+constexpr int PASSES = CHUNK_ROWS / 32;
 
-__device__ inline int worker_of_row(const Segs& s, int row) {
-  int k = 0;
-  while (k + 1 < s.K && row >= s.off[k + 1]) ++k;
-  return k;
+// first[k] = index of worker k's first chunk; first[K] = number of chunks
+struct Chunks {
+  int first[DYNB_MAX_WORKERS + 1];
+};
+
+// worker, first row and row count of a chunk (chunk < first[K], so the scan ends)
+__device__ inline void chunk_span(const Segs& s, const Chunks& ch, int chunk, int& k, int& r0, int& n) {
+  k = 0;
+  while (k + 1 < s.K && chunk >= ch.first[k + 1]) ++k;
+  r0 = s.off[k] + (chunk - ch.first[k]) * CHUNK_ROWS;
+  n = min(CHUNK_ROWS, s.off[k + 1] - r0);
 }
 
-// Sum over the 4 row-lanes of a channel: threads are laid out [row-lane][channel], the partial
-// sums meet in LDS and every thread of the channel reads the total (fixed order 0..3).
-__device__ inline float sum4(float v, float (*red)[64], int rl, int cl) {
-  __syncthreads();
-  red[rl][cl] = v;
-  __syncthreads();
-  return ((red[0][cl] + red[1][cl]) + red[2][cl]) + red[3][cl];
-}
-
-// mean[k][c], rstd[k][c] of x over worker k's rows: two passes (mean, then centred squares).
-__global__ __launch_bounds__(256) void bn_stats_kernel(const bf16* __restrict__ x, int64_t ld, int C,
-                                                       float eps, float* __restrict__ mean,
-                                                       float* __restrict__ rstd, Segs s) {
+// Mean and sum of centred squares of one chunk (its values stay in registers between the two).
+__global__ __launch_bounds__(256) void bn_chunk_stats_kernel(const bf16* __restrict__ x, int64_t ld,
+                                                             int C, float* __restrict__ pmean,
+                                                             float* __restrict__ pm2, Segs s, Chunks ch) {
   __shared__ float red[4][64];
-  const int cl = threadIdx.x & 63, rl = threadIdx.x >> 6;
-  const int c = blockIdx.x * 64 + cl, k = blockIdx.y;
-  const int r0 = s.off[k], n = s.off[k + 1] - r0;
-  if (n <= 0) return;                         // (uniform over the workgroup)
-  const bool live = c < C;
-  float acc = 0.f;
-  if (live)
-    for (int r = rl; r < n; r += 4) acc += (float)x[(int64_t)(r0 + r) * ld + c];
-  const float mu = sum4(acc, red, rl, cl) / (float)n;
-  acc = 0.f;
-  if (live)
-    for (int r = rl; r < n; r += 4) {
-      const float d = (float)x[(int64_t)(r0 + r) * ld + c] - mu;
-      acc += d * d;
+  const int cg = threadIdx.x & 7, rl = threadIdx.x >> 3;
+  const int chunk = blockIdx.x, c0 = blockIdx.y * 64 + cg * 8;
+  int k, r0, n;
+  chunk_span(s, ch, chunk, k, r0, n);
+  const bf16* base = x + (int64_t)r0 * ld + c0;
+  float v[PASSES][8], acc[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+#pragma unroll
+  for (int i = 0; i < PASSES; ++i) {
+    const int r = rl + 32 * i;
+    const uint4 q = r < n ? load8(base + (int64_t)r * ld) : make_uint4(0, 0, 0, 0);
+    unpack8(q, v[i]);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] += v[i][j];
+  }
+  sum_over_rows(acc, red);
+  float mu[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) { mu[j] = acc[j] / (float)n; acc[j] = 0.f; }
+#pragma unroll
+  for (int i = 0; i < PASSES; ++i) {
+    if (rl + 32 * i < n) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) { const float d = v[i][j] - mu[j]; acc[j] += d * d; }
     }
-  const float var = sum4(acc, red, rl, cl) / (float)n;
-  if (live && rl == 0) {
+  }
+  sum_over_rows(acc, red);
+  if (rl == 0) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (c0 + j < C) {
+        pmean[(int64_t)chunk * C + c0 + j] = mu[j];
+        pm2[(int64_t)chunk * C + c0 + j] = acc[j];
+      }
+  }
+}
+
+// (n, mu, m2) <- (n, mu, m2) merged with (nb, mb, m2b): the pairwise update of Chan et al.
+__device__ inline void merge_moments(float& n, float& mu, float& m2, float nb, float mb, float m2b) {
+  if (nb <= 0.f) return;
+  const float tot = n + nb, d = mb - mu;
+  mu += d * (nb / tot);
+  m2 += m2b + d * d * (n * nb / tot);
+  n = tot;
+}
+
+// mean[k][c], rstd[k][c] from the chunk moments of worker k, merged in a fixed order
+// (4 lanes per channel take every 4th chunk, then the lanes are merged 0..3).
+__global__ __launch_bounds__(256) void bn_merge_stats_kernel(const float* __restrict__ pmean,
+                                                             const float* __restrict__ pm2, int C,
+                                                             float eps, float* __restrict__ mean,
+                                                             float* __restrict__ rstd, Segs s, Chunks ch) {
+  __shared__ float sn[4][64], sm[4][64], sq[4][64];
+  const int cl = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + cl, k = blockIdx.y;
+  const int rows = s.off[k + 1] - s.off[k];
+  if (rows <= 0) return;                      // (uniform over the workgroup)
+  const int first = ch.first[k], nc = ch.first[k + 1] - first;
+  float n = 0.f, mu = 0.f, m2 = 0.f;
+  if (c < C)
+    for (int j = q; j < nc; j += 4)
+      merge_moments(n, mu, m2, (float)min(CHUNK_ROWS, rows - j * CHUNK_ROWS),
+                    pmean[(int64_t)(first + j) * C + c], pm2[(int64_t)(first + j) * C + c]);
+  sn[q][cl] = n; sm[q][cl] = mu; sq[q][cl] = m2;
+  __syncthreads();
+  if (q == 0 && c < C) {
+    for (int j = 1; j < 4; ++j) merge_moments(n, mu, m2, sn[j][cl], sm[j][cl], sq[j][cl]);
     mean[(int64_t)k * C + c] = mu;
-    rstd[(int64_t)k * C + c] = 1.f / sqrtf(var + eps);
+    rstd[(int64_t)k * C + c] = 1.f / sqrtf(m2 / n + eps);
   }
 }
 
-// y = relu?(gamma * (x - mean_k) * rstd_k + beta)
-__global__ __launch_bounds__(256) void bn_forward_kernel(const bf16* __restrict__ x, int64_t ldx,
-                                                         int C, const float* __restrict__ gamma,
-                                                         const float* __restrict__ beta,
-                                                         const float* __restrict__ mean,
-                                                         const float* __restrict__ rstd, int relu,
-                                                         bf16* __restrict__ y, int64_t ldy, Segs s) {
-  const int c = blockIdx.x * 256 + threadIdx.x, row = blockIdx.y;
-  if (c >= C) return;
-  const int k = worker_of_row(s, row);
-  const float xh = ((float)x[(int64_t)row * ldx + c] - mean[(int64_t)k * C + c]) * rstd[(int64_t)k * C + c];
-  float v = gamma[c] * xh + beta[c];
-  if (relu) v = fmaxf(v, 0.f);
-  y[(int64_t)row * ldy + c] = (bf16)v;
-}
-
-// dgamma[k][c] = sum_rows dy * xhat, dbeta[k][c] = sum_rows dy  (dy already carries this
-// layer's ReLU mask) -> worker k's gradient vector
-__global__ __launch_bounds__(256) void bn_param_grad_kernel(const bf16* __restrict__ dy, int64_t ldd,
-                                                            const bf16* __restrict__ x, int64_t ldx,
-                                                            int C, const float* __restrict__ mean,
-                                                            const float* __restrict__ rstd,
-                                                            float* __restrict__ dgamma,
-                                                            float* __restrict__ dbeta,
-                                                            int64_t group_stride, Segs s) {
-  __shared__ float red[4][64];
-  const int cl = threadIdx.x & 63, rl = threadIdx.x >> 6;
-  const int c = blockIdx.x * 64 + cl, k = blockIdx.y;
-  const int r0 = s.off[k], n = s.off[k + 1] - r0;
-  const bool live = c < C;
-  float ag = 0.f, ab = 0.f;
-  if (live && n > 0) {
-    const float mu = mean[(int64_t)k * C + c], rs = rstd[(int64_t)k * C + c];
-    for (int r = rl; r < n; r += 4) {
-      const float d = (float)dy[(int64_t)(r0 + r) * ldd + c];
-      ab += d;
-      ag += d * (((float)x[(int64_t)(r0 + r) * ldx + c] - mu) * rs);
+// y = relu?(gamma * ((x - mean_k) * rstd_k) + beta); padding channels are written as zero
+__global__ __launch_bounds__(256) void bn_apply_kernel(const bf16* __restrict__ x, int64_t ldx, int C,
+                                                       const float* __restrict__ gamma,
+                                                       const float* __restrict__ beta,
+                                                       const float* __restrict__ mean,
+                                                       const float* __restrict__ rstd, int relu,
+                                                       bf16* __restrict__ y, int64_t ldy, Segs s,
+                                                       Chunks ch) {
+  const int cg = threadIdx.x & 7, rl = threadIdx.x >> 3;
+  const int chunk = blockIdx.x, c0 = blockIdx.y * 64 + cg * 8;
+  int k, r0, n;
+  chunk_span(s, ch, chunk, k, r0, n);
+  float mu[8], rs[8], ga[8], be[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const bool live = c0 + j < C;
+    mu[j] = live ? mean[(int64_t)k * C + c0 + j] : 0.f;
+    rs[j] = live ? rstd[(int64_t)k * C + c0 + j] : 0.f;
+    ga[j] = live ? gamma[c0 + j] : 0.f;
+    be[j] = live ? beta[c0 + j] : 0.f;
+  }
+  const bf16* xb = x + (int64_t)r0 * ldx + c0;
+  bf16* yb = y + (int64_t)r0 * ldy + c0;
+#pragma unroll
+  for (int i = 0; i < PASSES; ++i) {
+    const int r = rl + 32 * i;
+    if (r < n) {
+      float v[8];
+      unpack8(load8(xb + (int64_t)r * ldx), v);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        float t = ga[j] * ((v[j] - mu[j]) * rs[j]) + be[j];
+        if (relu) t = fmaxf(t, 0.f);
+        v[j] = c0 + j < C ? t : 0.f;
+      }
+      store8(yb + (int64_t)r * ldy, pack8(v));
     }
   }
-  const float tg = sum4(ag, red, rl, cl);
-  const float tb = sum4(ab, red, rl, cl);
-  if (live && rl == 0) {                      // an idle worker gets zeros
-    dgamma[(int64_t)k * group_stride + c] = tg;
-    dbeta[(int64_t)k * group_stride + c] = tb;
+}
+
+// Chunk sums of dy and of dy * xhat (dy already carries this layer's ReLU mask).
+__global__ __launch_bounds__(256) void bn_chunk_param_grad_kernel(
+    const bf16* __restrict__ dy, int64_t ldd, const bf16* __restrict__ x, int64_t ldx, int C,
+    const float* __restrict__ mean, const float* __restrict__ rstd, float* __restrict__ pdg,
+    float* __restrict__ pdb, Segs s, Chunks ch) {
+  __shared__ float red[4][64];
+  const int cg = threadIdx.x & 7, rl = threadIdx.x >> 3;
+  const int chunk = blockIdx.x, c0 = blockIdx.y * 64 + cg * 8;
+  int k, r0, n;
+  chunk_span(s, ch, chunk, k, r0, n);
+  float mu[8], rs[8], ag[8], ab[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const bool live = c0 + j < C;
+    mu[j] = live ? mean[(int64_t)k * C + c0 + j] : 0.f;
+    rs[j] = live ? rstd[(int64_t)k * C + c0 + j] : 0.f;
+    ag[j] = 0.f; ab[j] = 0.f;
+  }
+  const bf16* xb = x + (int64_t)r0 * ldx + c0;
+  const bf16* db = dy + (int64_t)r0 * ldd + c0;
+#pragma unroll
+  for (int i = 0; i < PASSES; ++i) {
+    const int r = rl + 32 * i;
+    if (r < n) {
+      float v[8], d[8];
+      unpack8(load8(xb + (int64_t)r * ldx), v);
+      unpack8(load8(db + (int64_t)r * ldd), d);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        ab[j] += d[j];
+        ag[j] += d[j] * ((v[j] - mu[j]) * rs[j]);
+      }
+    }
+  }
+  sum_over_rows(ag, red);
+  sum_over_rows(ab, red);
+  if (rl == 0) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (c0 + j < C) {
+        pdg[(int64_t)chunk * C + c0 + j] = ag[j];
+        pdb[(int64_t)chunk * C + c0 + j] = ab[j];
+      }
   }
 }
 
-// dx = gamma * rstd * (dy - dbeta/n - xhat * dgamma/n), masked by the producer's ReLU
+// dgamma[k][c], dbeta[k][c] = the chunk sums of worker k added in a fixed order, written into
+// worker k's gradient vector; a worker without rows gets zeros.
+__global__ __launch_bounds__(256) void bn_merge_param_grad_kernel(const float* __restrict__ pdg,
+                                                                  const float* __restrict__ pdb, int C,
+                                                                  float* __restrict__ dgamma,
+                                                                  float* __restrict__ dbeta,
+                                                                  int64_t group_stride, Chunks ch) {
+  __shared__ float sg[4][64], sb[4][64];
+  const int cl = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + cl, k = blockIdx.y;
+  const int first = ch.first[k], nc = ch.first[k + 1] - first;
+  float g = 0.f, b = 0.f;
+  if (c < C)
+    for (int j = q; j < nc; j += 4) {
+      g += pdg[(int64_t)(first + j) * C + c];
+      b += pdb[(int64_t)(first + j) * C + c];
+    }
+  sg[q][cl] = g; sb[q][cl] = b;
+  __syncthreads();
+  if (q == 0 && c < C) {
+    dgamma[(int64_t)k * group_stride + c] = ((sg[0][cl] + sg[1][cl]) + sg[2][cl]) + sg[3][cl];
+    dbeta[(int64_t)k * group_stride + c] = ((sb[0][cl] + sb[1][cl]) + sb[2][cl]) + sb[3][cl];
+  }
+}
+
+// Chunk sums of the columns of dy (the bias gradient of a layer whose rows are pixels).
+__global__ __launch_bounds__(256) void column_sum_chunk_kernel(const bf16* __restrict__ dy, int64_t ldd,
+                                                               int C, float* __restrict__ part,
+                                                               Segs s, Chunks ch) {
+  __shared__ float red[4][64];
+  const int cg = threadIdx.x & 7, rl = threadIdx.x >> 3;
+  const int chunk = blockIdx.x, c0 = blockIdx.y * 64 + cg * 8;
+  int k, r0, n;
+  chunk_span(s, ch, chunk, k, r0, n);
+  const bf16* db = dy + (int64_t)r0 * ldd + c0;
+  float acc[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+#pragma unroll
+  for (int i = 0; i < PASSES; ++i) {
+    const int r = rl + 32 * i;
+    if (r < n) {
+      float d[8];
+      unpack8(load8(db + (int64_t)r * ldd), d);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[j] += d[j];
+    }
+  }
+  sum_over_rows(acc, red);
+  if (rl == 0) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (c0 + j < C) part[(int64_t)chunk * C + c0 + j] = acc[j];
+  }
+}
+
+// out[k][c] = the chunk sums of worker k added in a fixed order; zeros for a worker without rows
+__global__ __launch_bounds__(256) void column_sum_merge_kernel(const float* __restrict__ part, int C,
+                                                               float* __restrict__ out,
+                                                               int64_t group_stride, Chunks ch) {
+  __shared__ float sp[4][64];
+  const int cl = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + cl, k = blockIdx.y;
+  const int first = ch.first[k], nc = ch.first[k + 1] - first;
+  float a = 0.f;
+  if (c < C)
+    for (int j = q; j < nc; j += 4) a += part[(int64_t)(first + j) * C + c];
+  sp[q][cl] = a;
+  __syncthreads();
+  if (q == 0 && c < C)
+    out[(int64_t)k * group_stride + c] = ((sp[0][cl] + sp[1][cl]) + sp[2][cl]) + sp[3][cl];
+}
+
+// dx = gamma * rstd * (dy - dbeta/n - xhat * dgamma/n), masked by the producer's ReLU (x > 0);
+// padding channels are written as zero
 __global__ __launch_bounds__(256) void bn_input_grad_kernel(
     const bf16* __restrict__ dy, int64_t ldd, const bf16* __restrict__ x, int64_t ldx, int C,
     const float* __restrict__ gamma, const float* __restrict__ mean, const float* __restrict__ rstd,
     const float* __restrict__ dgamma, const float* __restrict__ dbeta, int64_t group_stride,
-    int relu_below, bf16* __restrict__ dx, int64_t ldo, Segs s) {
-  const int c = blockIdx.x * 256 + threadIdx.x, row = blockIdx.y;
-  if (c >= C) return;
-  const int k = worker_of_row(s, row);
-  const float n = (float)(s.off[k + 1] - s.off[k]);
-  const float xv = (float)x[(int64_t)row * ldx + c];
-  const float rs = rstd[(int64_t)k * C + c];
-  const float xh = (xv - mean[(int64_t)k * C + c]) * rs;
-  float v = gamma[c] * rs * ((float)dy[(int64_t)row * ldd + c] - dbeta[(int64_t)k * group_stride + c] / n -
-                             xh * (dgamma[(int64_t)k * group_stride + c] / n));
-  if (relu_below && !(xv > 0.f)) v = 0.f;
-  dx[(int64_t)row * ldo + c] = (bf16)v;
+    int relu_below, bf16* __restrict__ dx, int64_t ldo, Segs s, Chunks ch) {
+  const int cg = threadIdx.x & 7, rl = threadIdx.x >> 3;
+  const int chunk = blockIdx.x, c0 = blockIdx.y * 64 + cg * 8;
+  int k, r0, n;
+  chunk_span(s, ch, chunk, k, r0, n);
+  const float rows = (float)(s.off[k + 1] - s.off[k]);
+  float mu[8], rs[8], gr[8], mg[8], mb[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const bool live = c0 + j < C;
+    mu[j] = live ? mean[(int64_t)k * C + c0 + j] : 0.f;
+    rs[j] = live ? rstd[(int64_t)k * C + c0 + j] : 0.f;
+    gr[j] = live ? gamma[c0 + j] * rs[j] : 0.f;
+    mg[j] = live ? dgamma[(int64_t)k * group_stride + c0 + j] / rows : 0.f;
+    mb[j] = live ? dbeta[(int64_t)k * group_stride + c0 + j] / rows : 0.f;
+  }
+  const bf16* xb = x + (int64_t)r0 * ldx + c0;
+  const bf16* db = dy + (int64_t)r0 * ldd + c0;
+  bf16* ob = dx + (int64_t)r0 * ldo + c0;
+#pragma unroll
+  for (int i = 0; i < PASSES; ++i) {
+    const int r = rl + 32 * i;
+    if (r < n) {
+      float v[8], d[8];
+      unpack8(load8(xb + (int64_t)r * ldx), v);
+      unpack8(load8(db + (int64_t)r * ldd), d);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        float t = gr[j] * (d[j] - mb[j] - ((v[j] - mu[j]) * rs[j]) * mg[j]);
+        if (relu_below && !(v[j] > 0.f)) t = 0.f;
+        d[j] = c0 + j < C ? t : 0.f;
+      }
+      store8(ob + (int64_t)r * ldo, pack8(d));
+    }
+  }
 }
+
+// Element-wise kernels: one lane takes 8 channels of a row; `gpr` = 16-byte granules per row
+// (the padded width / 8; padding channels hold zeros on both sides).
 
 // out = relu?(a + b)
 __global__ __launch_bounds__(256) void add_forward_kernel(const bf16* __restrict__ a, int64_t lda,
                                                           const bf16* __restrict__ b, int64_t ldb,
-                                                          int C, int relu, bf16* __restrict__ out,
-                                                          int64_t ldo) {
-  const int c = blockIdx.x * 256 + threadIdx.x;
-  const int64_t row = blockIdx.y;
-  if (c >= C) return;
-  float v = (float)a[row * lda + c] + (float)b[row * ldb + c];
-  if (relu) v = fmaxf(v, 0.f);
-  out[row * ldo + c] = (bf16)v;
+                                                          int gpr, int64_t total, int relu,
+                                                          bf16* __restrict__ out, int64_t ldo) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int64_t row = i / gpr;
+  const int c0 = (int)(i - row * gpr) * 8;
+  float u[8], v[8];
+  unpack8(load8(a + row * lda + c0), u);
+  unpack8(load8(b + row * ldb + c0), v);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    u[j] += v[j];
+    if (relu) u[j] = fmaxf(u[j], 0.f);
+  }
+  store8(out + row * ldo + c0, pack8(u));
 }
 
 // dst = (accumulate ? dst : 0) + src, masked by act > 0 when `relu` (act = the stored output of
 // the layer whose gradient dst is)
 __global__ __launch_bounds__(256) void grad_route_kernel(const bf16* __restrict__ src, int64_t lds_,
                                                          const bf16* __restrict__ act, int64_t lda,
-                                                         int C, int relu, int accumulate,
-                                                         bf16* __restrict__ dst, int64_t ldd) {
-  const int c = blockIdx.x * 256 + threadIdx.x;
-  const int64_t row = blockIdx.y;
-  if (c >= C) return;
-  float v = (float)src[row * lds_ + c];
-  if (relu && !((float)act[row * lda + c] > 0.f)) v = 0.f;
-  if (accumulate) v += (float)dst[row * ldd + c];
-  dst[row * ldd + c] = (bf16)v;
+                                                         int gpr, int64_t total, int relu,
+                                                         int accumulate, bf16* __restrict__ dst,
+                                                         int64_t ldd) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int64_t row = i / gpr;
+  const int c0 = (int)(i - row * gpr) * 8;
+  float v[8];
+  unpack8(load8(src + row * lds_ + c0), v);
+  if (relu) {
+    float a[8];
+    unpack8(load8(act + row * lda + c0), a);
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (!(a[j] > 0.f)) v[j] = 0.f;
+  }
+  if (accumulate) {
+    float d[8];
+    unpack8(load8(dst + row * ldd + c0), d);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] += d[j];
+  }
+  store8(dst + row * ldd + c0, pack8(v));
 }
 
 inline int ok(const char* what) {
   return hipGetLastError() == hipSuccess ? DYNB_OK : fail(DYNB_ERR_HIP, "%s: launch failed", what);
 }
 
+Chunks make_chunks(const Segs& s) {
+  Chunks ch;
+  ch.first[0] = 0;
+  for (int k = 0; k < s.K; ++k)
+    ch.first[k + 1] = ch.first[k] + (s.off[k + 1] - s.off[k] + CHUNK_ROWS - 1) / CHUNK_ROWS;
+  for (int k = s.K + 1; k <= DYNB_MAX_WORKERS; ++k) ch.first[k] = ch.first[s.K];
+  return ch;
+}
+
 }  // namespace
 
 int launch_bn_forward(const void* x, int64_t ldx, int C, const float* gamma, const float* beta,
-                      float eps, int relu, float* mean, float* rstd, void* y, int64_t ldy,
-                      const Segs& s, void* stream) {
+                      float eps, int relu, float* mean, float* rstd, float* scratch, void* y,
+                      int64_t ldy, const Segs& s, void* stream) {
   const int rows = s.off[s.K];
   if (rows == 0 || C == 0) return DYNB_OK;
-  Timed t(KC_CONV_AUX, stream, 0, (double)rows * C * 8);
-  hipLaunchKernelGGL(bn_stats_kernel, dim3((C + 63) / 64, s.K), dim3(256), 0, (hipStream_t)stream,
-                     (const bf16*)x, ldx, C, eps, mean, rstd, s);
-  hipLaunchKernelGGL(bn_forward_kernel, dim3((C + 255) / 256, rows), dim3(256), 0, (hipStream_t)stream,
-                     (const bf16*)x, ldx, C, gamma, beta, mean, rstd, relu, (bf16*)y, ldy, s);
+  const Chunks ch = make_chunks(s);
+  const int nch = ch.first[s.K], cb = (C + 63) / 64;
+  float* pmean = scratch;
+  float* pm2 = scratch + (int64_t)nch * C;
+  Timed t(KC_NORM, stream, 0, (double)rows * C * 6);     // x twice, y once
+  hipLaunchKernelGGL(bn_chunk_stats_kernel, dim3(nch, cb), dim3(256), 0, (hipStream_t)stream,
+                     (const bf16*)x, ldx, C, pmean, pm2, s, ch);
+  hipLaunchKernelGGL(bn_merge_stats_kernel, dim3(cb, s.K), dim3(256), 0, (hipStream_t)stream, pmean,
+                     pm2, C, eps, mean, rstd, s, ch);
+  hipLaunchKernelGGL(bn_apply_kernel, dim3(nch, (unsigned)(ldy / 64)), dim3(256), 0,
+                     (hipStream_t)stream, (const bf16*)x, ldx, C, gamma, beta, mean, rstd, relu,
+                     (bf16*)y, ldy, s, ch);
   return ok("bn_forward");
 }
 
 int launch_bn_backward(const void* dy, int64_t ldd, const void* x, int64_t ldx, int C,
-                       const float* gamma, const float* mean, const float* rstd, float* dgamma,
-                       float* dbeta, int64_t group_stride, int need_dx, int relu_below, void* dx,
-                       int64_t ldo, const Segs& s, void* stream) {
+                       const float* gamma, const float* mean, const float* rstd, float* scratch,
+                       float* dgamma, float* dbeta, int64_t group_stride, int need_dx,
+                       int relu_below, void* dx, int64_t ldo, const Segs& s, void* stream) {
   const int rows = s.off[s.K];
   if (C == 0) return DYNB_OK;
-  Timed t(KC_CONV_AUX, stream, 0, (double)rows * C * 10);
-  hipLaunchKernelGGL(bn_param_grad_kernel, dim3((C + 63) / 64, s.K), dim3(256), 0, (hipStream_t)stream,
-                     (const bf16*)dy, ldd, (const bf16*)x, ldx, C, mean, rstd, dgamma, dbeta,
-                     group_stride, s);
-  if (need_dx && rows > 0)
-    hipLaunchKernelGGL(bn_input_grad_kernel, dim3((C + 255) / 256, rows), dim3(256), 0,
+  const Chunks ch = make_chunks(s);
+  const int nch = ch.first[s.K], cb = (C + 63) / 64;
+  float* pdg = scratch;
+  float* pdb = scratch + (int64_t)nch * C;
+  Timed t(KC_NORM, stream, 0, (double)rows * C * (need_dx ? 10 : 4));   // dy, x twice; dx once
+  if (nch > 0)
+    hipLaunchKernelGGL(bn_chunk_param_grad_kernel, dim3(nch, cb), dim3(256), 0, (hipStream_t)stream,
+                       (const bf16*)dy, ldd, (const bf16*)x, ldx, C, mean, rstd, pdg, pdb, s, ch);
+  hipLaunchKernelGGL(bn_merge_param_grad_kernel, dim3(cb, s.K), dim3(256), 0, (hipStream_t)stream, pdg,
+                     pdb, C, dgamma, dbeta, group_stride, ch);
+  if (need_dx && nch > 0)
+    hipLaunchKernelGGL(bn_input_grad_kernel, dim3(nch, (unsigned)(ldo / 64)), dim3(256), 0,
                        (hipStream_t)stream, (const bf16*)dy, ldd, (const bf16*)x, ldx, C, gamma, mean,
-                       rstd, dgamma, dbeta, group_stride, relu_below, (bf16*)dx, ldo, s);
+                       rstd, dgamma, dbeta, group_stride, relu_below, (bf16*)dx, ldo, s, ch);
   return ok("bn_backward");
 }
 
-int launch_add_forward(const void* a, int64_t lda, const void* b, int64_t ldb, int C, int64_t rows,
-                       int relu, void* out, int64_t ldo, void* stream) {
-  if (rows == 0 || C == 0) return DYNB_OK;
-  Timed t(KC_CONV_AUX, stream, 0, (double)rows * C * 6);
-  hipLaunchKernelGGL(add_forward_kernel, dim3((C + 255) / 256, (unsigned)rows), dim3(256), 0,
-                     (hipStream_t)stream, (const bf16*)a, lda, (const bf16*)b, ldb, C, relu,
+int launch_column_sums(const void* dy, int64_t ldd, int C, float* scratch, float* out,
+                       int64_t group_stride, const Segs& s, void* stream) {
+  if (C == 0) return DYNB_OK;
+  const Chunks ch = make_chunks(s);
+  const int nch = ch.first[s.K], cb = (C + 63) / 64;
+  Timed t(KC_BIAS_GRAD, stream, 0, (double)s.off[s.K] * C * 2);
+  if (nch > 0)
+    hipLaunchKernelGGL(column_sum_chunk_kernel, dim3(nch, cb), dim3(256), 0, (hipStream_t)stream,
+                       (const bf16*)dy, ldd, C, scratch, s, ch);
+  hipLaunchKernelGGL(column_sum_merge_kernel, dim3(cb, s.K), dim3(256), 0, (hipStream_t)stream,
+                     scratch, C, out, group_stride, ch);
+  return ok("column_sums");
+}
+
+int64_t row_scratch_floats(int64_t max_rows, int max_workers, int C) {
+  return 2 * ((max_rows + CHUNK_ROWS - 1) / CHUNK_ROWS + max_workers) * (int64_t)C;
+}
+
+int launch_add_forward(const void* a, int64_t lda, const void* b, int64_t ldb, int64_t width,
+                       int64_t rows, int relu, void* out, int64_t ldo, void* stream) {
+  if (rows == 0 || width == 0) return DYNB_OK;
+  const int gpr = (int)(width / 8);
+  const int64_t total = rows * gpr;
+  Timed t(KC_NORM, stream, 0, (double)rows * width * 6);
+  hipLaunchKernelGGL(add_forward_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
+                     (hipStream_t)stream, (const bf16*)a, lda, (const bf16*)b, ldb, gpr, total, relu,
                      (bf16*)out, ldo);
   return ok("add_forward");
 }
 
-int launch_grad_route(const void* src, int64_t lds_, const void* act, int64_t lda, int C,
+int launch_grad_route(const void* src, int64_t lds_, const void* act, int64_t lda, int64_t width,
                       int64_t rows, int relu, int accumulate, void* dst, int64_t ldd, void* stream) {
-  if (rows == 0 || C == 0) return DYNB_OK;
-  Timed t(KC_CONV_AUX, stream, 0, (double)rows * C * 6);
-  hipLaunchKernelGGL(grad_route_kernel, dim3((C + 255) / 256, (unsigned)rows), dim3(256), 0,
-                     (hipStream_t)stream, (const bf16*)src, lds_, (const bf16*)act, lda, C, relu,
-                     accumulate, (bf16*)dst, ldd);
+  if (rows == 0 || width == 0) return DYNB_OK;
+  const int gpr = (int)(width / 8);
+  const int64_t total = rows * gpr;
+  Timed t(KC_NORM, stream, 0, (double)rows * width * (2 + 2 + (relu ? 2 : 0) + (accumulate ? 2 : 0)));
+  hipLaunchKernelGGL(grad_route_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
+                     (hipStream_t)stream, (const bf16*)src, lds_, (const bf16*)act, lda, gpr, total,
+                     relu, accumulate, (bf16*)dst, ldd);
   return ok("grad_route");
 }
 

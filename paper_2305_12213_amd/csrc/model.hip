@@ -68,6 +68,7 @@ struct dynb_model {
   float* loss = nullptr;
   float* partial = nullptr;          // scratch of the split weight-gradient reductions
   int64_t partial_floats = 0;
+  float* row_scratch = nullptr;       // chunk partials of the per-worker column reductions over pixel rows
 };
 
 namespace {
@@ -118,6 +119,13 @@ size_t carve(dynb_model* m, void* base, int max_batch, int max_workers) {
       }
     }
   }
+  int64_t bn_floats = 0;
+  for (Layer& L : m->layers)
+    if (L.kind == DYNB_LAYER_BN || L.kind == DYNB_LAYER_CONV3X3) {
+      const int64_t need = row_scratch_floats((int64_t)max_batch * L.hw_out, max_workers, L.n_out);
+      if (need > bn_floats) bn_floats = need;
+    }
+  m->row_scratch = bn_floats ? (float*)c.take((size_t)bn_floats * 4) : nullptr;
   const int64_t ldc = m->layers.back().ld_out;
   m->logits = (float*)c.take((size_t)max_batch * ldc * 4);
   m->rowloss = (float*)c.take((size_t)max_batch * 4);
@@ -389,13 +397,14 @@ int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const 
       }
       if (L.kind == DYNB_LAYER_BN) {
         rc = launch_bn_forward(in_act(l), L.ld_in, L.n_out, m->params + L.w_off, m->params + L.b_off,
-                               L.eps, L.relu, L.bn_mean, L.bn_rstd, L.out, L.ld_out, segs[l], stream);
+                               L.eps, L.relu, L.bn_mean, L.bn_rstd, m->row_scratch, L.out, L.ld_out,
+                               segs[l], stream);
         if (rc) return rc;
         continue;
       }
       if (L.kind == DYNB_LAYER_ADD) {
         const Layer& Src = m->layers[L.skip_from];
-        rc = launch_add_forward(in_act(l), L.ld_in, Src.out, Src.ld_out, L.n_out, rows_out, L.relu,
+        rc = launch_add_forward(in_act(l), L.ld_in, Src.out, Src.ld_out, L.ld_out, rows_out, L.relu,
                                 L.out, L.ld_out, stream);
         if (rc) return rc;
         continue;
@@ -441,7 +450,7 @@ int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const 
     for (size_t l = nL; l-- > 0;) {
       Layer& L = m->layers[l];
       if (L.skip_source) {   // the gradient that arrived over the residual branch joins in
-        rc = launch_grad_route(L.dy_skip, L.ld_out, nullptr, 0, L.n_out, (int64_t)B * L.hw_out, 0, 1,
+        rc = launch_grad_route(L.dy_skip, L.ld_out, nullptr, 0, L.ld_out, (int64_t)B * L.hw_out, 0, 1,
                                L.dy, L.ld_out, stream);
         if (rc) return rc;
       }
@@ -453,8 +462,8 @@ int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const 
       if (L.kind == DYNB_LAYER_BN) {
         Layer* Lq = l > 0 ? &m->layers[l - 1] : nullptr;
         rc = launch_bn_backward(L.dy, L.ld_out, in_act(l), L.ld_in, L.n_out, m->params + L.w_off,
-                                L.bn_mean, L.bn_rstd, grads + L.w_off, grads + L.b_off, m->P_pad,
-                                below, Lq ? Lq->relu : 0, Lq ? Lq->dy : nullptr, Lq ? Lq->ld_out : 0,
+                                L.bn_mean, L.bn_rstd, m->row_scratch, grads + L.w_off,
+                                grads + L.b_off, m->P_pad, below, Lq ? Lq->relu : 0, Lq ? Lq->dy : nullptr, Lq ? Lq->ld_out : 0,
                                 segs[l], stream);
         if (rc) return rc;
         continue;
@@ -464,10 +473,10 @@ int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const 
       const int rows_in = B * L.hw_in;
       if (L.kind == DYNB_LAYER_ADD) {                 // the same gradient goes down both branches
         Layer& Src = m->layers[L.skip_from];
-        rc = launch_grad_route(L.dy, L.ld_out, Lp.out, Lp.ld_out, L.n_out, rows_in, Lp.relu, 0, Lp.dy,
+        rc = launch_grad_route(L.dy, L.ld_out, Lp.out, Lp.ld_out, L.ld_out, rows_in, Lp.relu, 0, Lp.dy,
                                Lp.ld_out, stream);
         if (rc) return rc;
-        rc = launch_grad_route(L.dy, L.ld_out, Src.out, Src.ld_out, L.n_out, rows_in, Src.relu, 0,
+        rc = launch_grad_route(L.dy, L.ld_out, Src.out, Src.ld_out, L.ld_out, rows_in, Src.relu, 0,
                                Src.dy_skip, Src.ld_out, stream);
         if (rc) return rc;
         continue;
@@ -528,8 +537,8 @@ int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const 
     if (L.kind == DYNB_LAYER_BN) {
       if (B == 0) {   // no backward pass ran: the scale / shift gradients of idle workers are zero
         rc = launch_bn_backward(L.dy, L.ld_out, in_act(l), L.ld_in, L.n_out, m->params + L.w_off,
-                                L.bn_mean, L.bn_rstd, grads + L.w_off, grads + L.b_off, m->P_pad, 0,
-                                0, nullptr, 0, segs[l], stream);
+                                L.bn_mean, L.bn_rstd, m->row_scratch, grads + L.w_off,
+                                grads + L.b_off, m->P_pad, 0, 0, nullptr, 0, segs[l], stream);
         if (rc) return rc;
       }
       if (agg) {
@@ -575,7 +584,11 @@ int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const 
                                grads + L.w_off, m->P_pad, K, stream);
       if (rc) return rc;
     }
-    rc = launch_bias_grad(dt, L.dyT, L.capT, L.n_out, grads + L.b_off, m->P_pad, segs[l], stream);
+    if (L.kind == DYNB_LAYER_CONV3X3)   // rows are pixels: long columns, summed in row chunks
+      rc = launch_column_sums(L.dy, L.ld_out, L.n_out, m->row_scratch, grads + L.b_off, m->P_pad,
+                              segs[l], stream);
+    else
+      rc = launch_bias_grad(dt, L.dyT, L.capT, L.n_out, grads + L.b_off, m->P_pad, segs[l], stream);
     if (rc) return rc;
     if (agg) {
       const int64_t nw = (int64_t)L.wg_rows * L.n_out;

@@ -47,7 +47,7 @@ hipEvent_t get_event() {
 }
 const char* kNames[KC_COUNT] = {"gemm_fwd",  "gemm_dgrad", "gemm_wgrad", "pack_input",
                                 "transpose", "softmax_xent", "bias_grad", "finalize",
-                                "weighted_aggregate", "sgd_update", "weight_cast", "conv_aux"};
+                                "weighted_aggregate", "sgd_update", "weight_cast", "conv_aux", "norm_add"};
 }  // namespace
 
 Timed::Timed(KClass cls, void* s, double flops, double bytes) : slot(-1), stream(s) {

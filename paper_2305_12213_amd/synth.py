@@ -80,7 +80,8 @@ def _cfg2_speeds():
 
 
 def config(i):
-    """Workload i of the five benchmark/parity workloads."""
+    """Workload i: the five benchmark/parity workloads, and (5) a residual network with batch
+    normalisation at the image size of the paper's ResNet workload."""
     if i == 0:
         return dict(index=0, name="softmax-regression 64-10 fp32",
                     spec=mlp_spec([64, 10], "f32"), x_dist="normal", init="normal0.01",
@@ -112,7 +113,14 @@ def config(i):
                     init="he", K=16, speeds=_cfg4_speeds(), global_batch=4096, b0=[256] * 16,
                     gains=dict(kp=1.0, deadband=0.05, b_min=1, b_max=4096, ewma_alpha=1.0),
                     lr=0.01, momentum=0.0, steps=20)
-    raise ValueError("config index must be 0..4")
+    if i == 5:
+        return dict(index=5, name="residual CNN 3 blocks x 64 channels, 32x32x3, batch-norm, bf16 NHWC",
+                    spec=resnet_block_spec(64, (32, 32, 3), 10, 3), x_dist="uniform", init="he",
+                    K=8, speeds=[1.0, 1.0, 0.5, 0.5, 0.25, 0.25, 0.125, 0.0625],
+                    global_batch=512, b0=[64] * 8,
+                    gains=dict(kp=1.0, deadband=0.05, b_min=1, b_max=512, ewma_alpha=1.0),
+                    lr=0.1, momentum=0.9, steps=20)
+    raise ValueError("config index must be 0..5")
 
 
 def param_shapes(spec):
