@@ -1,0 +1,273 @@
+// Per-worker weight gradient of a 3x3 convolution (NHWC, zero padding 1, stride 1 or 2; bf16),
+// straight from the row-major activations:
+//   dW_k[kh][kw][ci][co] = sum over worker k's output pixels p of in[src(p, kh, kw)][ci] * dy[p][co]
+// The reduction runs over pixels, which are the *rows* of both operands, while an MFMA operand
+// wants 8 consecutive reduction indices per lane.  Instead of building transposed copies in
+// memory (a patch matrix nine times the activation), tiles are staged in LDS as they lie in
+// memory ([pixel][channel]) and fetched with the LDS transpose read of gfx950
+// (ds_read_b64_tr_b16): within 16 lanes, lane r supplies the address of 4 channels of pixel
+// r/4, and lane l receives channel l of 4 consecutive pixels.
+//
+// Work split: the rows of a worker are cut into chunks of `chunk_rows` pixels; one workgroup
+// takes one chunk, 64 input and 64 output channels, and all nine taps (4 waves: each owns a
+// 32 x 32 corner of the 64 x 64 tile for the nine taps, 144 accumulator registers).  A stage is
+// 32 pixels x one kernel row (3 taps): 3 x 4 KB of shifted input rows and 4 KB of dy, copied
+// global -> LDS asynchronously into a ring of 4 stage buffers.  Chunk results go to a scratch
+// area in register order and a second kernel adds the chunks of each worker in a fixed order
+// (deterministic, no atomics).
+#include <hip/hip_runtime.h>
+
+#include "dynb_internal.h"
+
+namespace dynb {
+namespace {
+
+typedef __bf16 bf16;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int S = 4;                         // stage buffers
+constexpr int TILE_BYTES = 32 * 128;         // 32 pixels x 64 channels
+constexpr int STAGE_BYTES = 4 * TILE_BYTES;  // three shifted input tiles + the dy tile
+constexpr int PER = 4;                       // copies per wave and stage
+constexpr int TILE_FLOATS = 9 * 64 * 64;     // one chunk result (per 64 x 64 channel block)
+
+__device__ uint4 g_zeros[1];                 // what lanes outside the image or the chunk fetch
+
+// 64 lanes x 16 bytes, global -> LDS: lane l lands at lds_base + 16 * l (lds_base wave-uniform)
+__device__ inline void async_copy_1k(const void* src, uint32_t lds_base) {
+  const uint32_t base = __builtin_amdgcn_readfirstlane(lds_base);
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(base), "v"(src)
+               : "memory", "m0");
+}
+
+__device__ inline void wait_copies(int stages) {   // at most `stages` stages of this wave pending
+  switch (stages) {
+    case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+    case 1: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PER) : "memory"); break;
+    default: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * PER) : "memory"); break;
+  }
+}
+
+__device__ inline s16x4 read_tr(uint32_t lds_addr) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (__attribute__((address_space(3))) s16x4*)(uintptr_t)lds_addr);
+}
+
+// worker, first row and row count of a chunk
+__device__ inline void chunk_span(const Segs& s, const RowChunks& ch, int chunk, int& k, int& r0, int& n) {
+  k = 0;
+  while (k + 1 < s.K && chunk >= ch.first[k + 1]) ++k;
+  r0 = s.off[k] + (chunk - ch.first[k]) * ch.rows;
+  n = min(ch.rows, s.off[k + 1] - r0);
+}
+
+struct ConvWgradArgs {
+  const bf16* in; int64_t ldi;       // [samples * H * W][ldi]
+  const bf16* dy; int64_t ldd;       // [samples * Ho * Wo][ldd]
+  int H, W, Ho, Wo, stride;
+  float* partial;                    // [chunk][cin block][cout block][TILE_FLOATS]
+};
+
+__global__ __launch_bounds__(256) void conv_wgrad_chunk_kernel(ConvWgradArgs p, Segs segs, RowChunks ch) {
+  __shared__ uint4 ring[S * STAGE_BYTES / 16];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int chunk = blockIdx.x, cib = blockIdx.y, cob = blockIdx.z;
+  int k, r0, n;
+  chunk_span(segs, ch, chunk, k, r0, n);
+  const int n_blocks = (n + 31) / 32;            // 32-pixel blocks
+  const int T = 3 * n_blocks;                    // stages
+
+  // ---- global -> LDS: this lane always moves granule (lane & 7) of pixel 8*wave + lane/8 of
+  // the block; pixel rows are 128 bytes, and the two 64-byte halves of rows 2,3,6,7,... are
+  // swapped so that the transpose reads of 4 neighbouring pixels fall into distinct banks.
+  const int prow = 8 * wave + (lane >> 3);
+  const int gq = (lane & 7) ^ (((lane >> 4) & 1) << 2);     // logical granule this lane fetches
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)&ring[0];
+  // output pixel of this lane in the current block: dense row, and (sample, y, x)
+  int row = r0 + prow;
+  int img = row / (p.Ho * p.Wo), rem = row - img * (p.Ho * p.Wo);
+  int oy = rem / p.Wo, ox = rem - oy * p.Wo;
+  int left = n - prow;                           // > 0 while this lane's pixel lies in the chunk
+  const bf16* in_c = p.in + cib * 64 + gq * 8;
+  const bf16* dy_c = p.dy + cob * 64 + gq * 8;
+
+  auto issue = [&](int t, int kh) {              // stage t = block t/3, kernel row kh = t%3
+    const uint32_t base = lds0 + (uint32_t)((t % S) * STAGE_BYTES + wave * 1024);
+    // both candidate addresses are formed unconditionally (coordinates clamped into the image,
+    // so always in bounds) and one is selected: no divergent branch around the copy, every
+    // stage issues exactly PER copies per wave
+    const bool valid = left > 0;
+    const int sy = oy * p.stride + kh - 1;
+    const bool row_ok = valid && sy >= 0 && sy < p.H;
+    const int csy = sy < 0 ? 0 : (sy >= p.H ? p.H - 1 : sy);
+    const int64_t line = valid ? (int64_t)(img * p.H + csy) * p.W : 0;
+#pragma unroll
+    for (int kw = 0; kw < 3; ++kw) {
+      const int sx = ox * p.stride + kw - 1;
+      const int csx = sx < 0 ? 0 : (sx >= p.W ? p.W - 1 : sx);
+      const bf16* a = in_c + (line + csx) * p.ldi;
+      const void* src = (row_ok && sx >= 0 && sx < p.W) ? (const void*)a : (const void*)g_zeros;
+      async_copy_1k(src, base + kw * TILE_BYTES);
+    }
+    const bf16* d = dy_c + (valid ? (int64_t)row * p.ldd : 0);
+    const void* src = valid ? (const void*)d : (const void*)g_zeros;
+    async_copy_1k(src, base + 3 * TILE_BYTES);
+  };
+  auto next_block = [&]() {                      // this lane's pixel, 32 pixels on
+    row += 32;
+    left -= 32;
+    ox += 32;
+    while (ox >= p.Wo) { ox -= p.Wo; ++oy; }
+    while (oy >= p.Ho) { oy -= p.Ho; ++img; }
+  };
+
+  // ---- LDS -> MFMA operands.  Wave (wci, wco) owns input channels [32*wci, +32) x output
+  // channels [32*wco, +32).  Lane l: group g = l/16 reads pixels 8*(g/2) + r/4 (+4 for the
+  // second half of the 8 reduction indices), channels 16*(g%2) + 4*(r%4), r = l%16.
+  const int wci = wave & 1, wco = wave >> 1;
+  const int g = lane >> 4, r = lane & 15;
+  const int fpix = 8 * (g >> 1) + (r >> 2);
+  const int fswap = (r >> 3) & 1;                // ((pixel >> 1) & 1) of every pixel this lane reads
+  const uint32_t fcol = (uint32_t)((16 * (g & 1) + 4 * (r & 3)) * 2);
+  const uint32_t foff_a = (uint32_t)(fpix * 128 + ((wci ^ fswap) * 64)) + fcol;
+  const uint32_t foff_b = (uint32_t)(fpix * 128 + ((wco ^ fswap) * 64)) + fcol;
+  auto frag = [&](uint32_t tile, uint32_t foff, int kk) {   // 8 reduction indices of k-step kk
+    const uint32_t a = tile + foff + (uint32_t)(kk * 16 * 128);
+    const s16x4 lo = read_tr(a), hi = read_tr(a + 4 * 128);
+    const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8, v);
+  };
+
+  f32x16 acc[9];
+#pragma unroll
+  for (int t = 0; t < 9; ++t)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
+
+  // ---- the stage pipeline: S - 1 stages in flight, one barrier per stage ----
+  int issued = 0;                                // stages issued so far (its kernel row = issued % 3)
+  auto issue_next = [&]() {
+    if (issued < T) {
+      const int kh = issued % 3;
+      issue(issued, kh);
+      if (kh == 2) next_block();
+      ++issued;
+    }
+  };
+#pragma unroll
+  for (int f = 0; f < S - 1; ++f) issue_next();
+  for (int blk = 0; blk < n_blocks; ++blk) {
+#pragma unroll
+    for (int kh = 0; kh < 3; ++kh) {
+      const int t = 3 * blk + kh;
+      wait_copies(issued - t - 1);               // stage t of this wave has landed
+      __syncthreads();                           // ... of all waves; stage t-1 is no longer read
+      issue_next();                              // into the buffer of stage t-1
+      const uint32_t stage = lds0 + (uint32_t)((t % S) * STAGE_BYTES);
+      const bf16x8 b0 = frag(stage + 3 * TILE_BYTES, foff_b, 0);
+      const bf16x8 b1 = frag(stage + 3 * TILE_BYTES, foff_b, 1);
+#pragma unroll
+      for (int kw = 0; kw < 3; ++kw) {
+        const bf16x8 a0 = frag(stage + kw * TILE_BYTES, foff_a, 0);
+        const bf16x8 a1 = frag(stage + kw * TILE_BYTES, foff_a, 1);
+        // first operand = the dimension that is contiguous in the result (output channels)
+        acc[kh * 3 + kw] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b0, a0, acc[kh * 3 + kw], 0, 0, 0);
+        acc[kh * 3 + kw] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b1, a1, acc[kh * 3 + kw], 0, 0, 0);
+      }
+    }
+  }
+
+  // ---- chunk result, in register order: [wave][tap][v/4][lane] x 4 floats ----
+  float* out = p.partial + ((int64_t)(chunk * gridDim.y + cib) * gridDim.z + cob) * TILE_FLOATS;
+#pragma unroll
+  for (int t = 0; t < 9; ++t)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const f32x4 o = {acc[t][4 * q], acc[t][4 * q + 1], acc[t][4 * q + 2], acc[t][4 * q + 3]};
+      *(f32x4*)&out[(((wave * 9 + t) * 4 + q) * 64 + lane) * 4] = o;
+    }
+}
+
+// dW_k[tap][ci][co .. co+3] = the chunk results of worker k added in ascending chunk order.
+// Accumulator element v of lane l belongs to output channel 8*(v/4) + 4*(l/32) + v%4 and input
+// channel l%32 of the wave's corner.
+__global__ __launch_bounds__(256) void conv_wgrad_reduce_kernel(const float* __restrict__ partial,
+                                                                int Cin, int Cout, int cibs, int cobs,
+                                                                float* __restrict__ grads,
+                                                                int64_t group_stride, RowChunks ch) {
+  const int k = blockIdx.y;
+  const int quads = (Cout + 3) / 4;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;    // (tap, ci, quad of co)
+  if (idx >= (int64_t)9 * Cin * quads) return;
+  const int quad = (int)(idx % quads);
+  const int ci = (int)((idx / quads) % Cin), tap = (int)(idx / ((int64_t)quads * Cin));
+  const int co = quad * 4;
+  const int cib = ci >> 6, cob = co >> 6, cil = ci & 63, col = co & 63;
+  const int wave = (cil >> 5) + 2 * (col >> 5);
+  const int c32 = col & 31;
+  const int q = c32 >> 3, lane = (cil & 31) + 32 * ((c32 & 7) >> 2);
+  const int64_t within = ((int64_t)((wave * 9 + tap) * 4 + q) * 64 + lane) * 4;
+  f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+  for (int c = ch.first[k]; c < ch.first[k + 1]; ++c)
+    sum += *(const f32x4*)&partial[((int64_t)(c * cibs + cib) * cobs + cob) * TILE_FLOATS + within];
+  float* dst = grads + (int64_t)k * group_stride + ((int64_t)tap * Cin + ci) * Cout + co;
+#pragma unroll
+  for (int e = 0; e < 4; ++e)
+    if (co + e < Cout) dst[e] = sum[e];
+}
+
+}  // namespace
+
+RowChunks make_row_chunks(const Segs& s, int rows) {
+  RowChunks ch;
+  ch.rows = rows;
+  ch.first[0] = 0;
+  for (int k = 0; k < s.K; ++k)
+    ch.first[k + 1] = ch.first[k] + (s.off[k + 1] - s.off[k] + rows - 1) / rows;
+  for (int k = s.K + 1; k <= DYNB_MAX_WORKERS; ++k) ch.first[k] = ch.first[s.K];
+  return ch;
+}
+
+int conv_wgrad_chunk_rows(int64_t max_rows) {
+  // about two chunks per compute unit at the largest batch, whole 32-pixel blocks, and long
+  // enough that a chunk's result (147 KB per channel block) is small against what it reads
+  int64_t rows = round_up((max_rows + 511) / 512, 32);
+  return (int)(rows < 256 ? 256 : rows);
+}
+
+int64_t conv_wgrad_scratch_floats(int64_t max_rows, int max_workers, int Cin, int Cout) {
+  const int64_t chunks = (max_rows + conv_wgrad_chunk_rows(max_rows) - 1) / conv_wgrad_chunk_rows(max_rows) +
+                         max_workers;
+  return chunks * ((Cin + 63) / 64) * ((Cout + 63) / 64) * TILE_FLOATS;
+}
+
+int launch_conv_wgrad(const void* in, int64_t ldi, int Cin, int H, int W, const void* dy, int64_t ldd,
+                      int Cout, int Ho, int Wo, int stride, int chunk_rows, float* scratch,
+                      int64_t scratch_floats, float* grads, int64_t group_stride, const Segs& s,
+                      double flops, double bytes, void* stream) {
+  if (Cin <= 0 || Cout <= 0) return DYNB_OK;
+  const int cibs = (Cin + 63) / 64, cobs = (Cout + 63) / 64;
+  if (ldi % 64 || ldd % 64 || ldi < 64 * cibs || ldd < 64 * cobs || chunk_rows < 32 || chunk_rows % 32 ||
+      (((uintptr_t)in | (uintptr_t)dy | (uintptr_t)scratch) & 15))
+    return fail(DYNB_ERR_BADARG, "conv_wgrad: pitches must cover whole 64-channel blocks, 16-byte aligned");
+  const RowChunks ch = make_row_chunks(s, chunk_rows);
+  const int nch = ch.first[s.K];
+  if ((int64_t)nch * cibs * cobs * TILE_FLOATS > scratch_floats)
+    return fail(DYNB_ERR_BADARG, "conv_wgrad: scratch area too small");
+  Timed t(KC_GEMM_WGRAD, stream, flops, bytes);
+  if (nch > 0) {
+    ConvWgradArgs a = {(const bf16*)in, ldi, (const bf16*)dy, ldd, H, W, Ho, Wo, stride, scratch};
+    hipLaunchKernelGGL(conv_wgrad_chunk_kernel, dim3(nch, cibs, cobs), dim3(256), 0,
+                       (hipStream_t)stream, a, s, ch);
+  }
+  const int64_t items = (int64_t)9 * Cin * ((Cout + 3) / 4);
+  hipLaunchKernelGGL(conv_wgrad_reduce_kernel, dim3((unsigned)((items + 255) / 256), s.K), dim3(256), 0,
+                     (hipStream_t)stream, scratch, Cin, Cout, cibs, cobs, grads, group_stride, ch);
+  return hipGetLastError() == hipSuccess ? DYNB_OK : fail(DYNB_ERR_HIP, "conv_wgrad: launch failed");
+}
+
+}  // namespace dynb

@@ -196,6 +196,25 @@ int launch_gap_backward(const void* dpooled, int64_t ldp, const void* act, int64
 int launch_conv_weight_cast(const float* W, int Cin, int Cout, int cin_p, int cout_p, void* Wf,
                             int kf, void* Wd, int kd, void* stream);
 
+// The rows of every worker cut into chunks of `rows` rows: first[k] = index of worker k's first
+// chunk, first[K] = number of chunks (chunk c of worker k starts at off[k] + (c - first[k]) * rows).
+struct RowChunks {
+  int rows;
+  int first[DYNB_MAX_WORKERS + 1];
+};
+RowChunks make_row_chunks(const Segs& s, int rows);
+
+// Per-worker weight gradient of a 3x3 convolution straight from the row-major activations
+// (bf16 in: [samples*H*W][ldi], dy: [samples*Ho*Wo][ldd]; grads[k * group_stride + (tap*Cin +
+// ci)*Cout + co], fp32).  chunk_rows = conv_wgrad_chunk_rows(largest row count of the model's
+// plan); scratch: conv_wgrad_scratch_floats() floats.
+int conv_wgrad_chunk_rows(int64_t max_rows);
+int64_t conv_wgrad_scratch_floats(int64_t max_rows, int max_workers, int Cin, int Cout);
+int launch_conv_wgrad(const void* in, int64_t ldi, int Cin, int H, int W, const void* dy, int64_t ldd,
+                      int Cout, int Ho, int Wo, int stride, int chunk_rows, float* scratch,
+                      int64_t scratch_floats, float* grads, int64_t group_stride, const Segs& s,
+                      double flops, double bytes, void* stream);
+
 // Batch normalisation over each worker's own rows (bf16; x: T [rows][ldx], y: T [rows][ldy]):
 // writes mean / rstd [k][C] (kept for the backward pass).  `scratch`: row_scratch_floats() floats
 // (the partial results of the row chunks), shared by forward and backward.

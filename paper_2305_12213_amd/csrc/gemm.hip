@@ -690,15 +690,26 @@ void launch_bf16_wgrad_agg(GemmArgs a, const Segs& s, hipStream_t st) {
                      dim3(256), 0, st, a, s);
 }
 
-// implicit-GEMM convolution (operand A gathered): 128 x 128 tiles
-void launch_bf16_gather(GemmArgs a, const Segs& s, hipStream_t st) {
-  const int tiles = ((a.M + 127) / 128) * ((a.N + 127) / 128);
+// implicit-GEMM convolution (operand A gathered).  The reduction is short (9 x channels), so a
+// tile spends much of its time filling and draining the load ring: the rings are kept shallow
+// enough (80 KB) for two workgroups per compute unit, whose phases then overlap.  Up to 64
+// output channels: 256 x 64 tiles (no half-empty MFMA columns); otherwise 128 x 128.
+template <int BM, int BN, int WM, int WN, int S>
+void launch_bf16_gather_as(GemmArgs a, const Segs& s, hipStream_t st) {
+  const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
   a.groups_per_block = 1;
-  dim3 grid(tiles, 1, 1), block(256);
+  dim3 grid(tiles, 1, 1), block(WM * WN * 64);
   if (a.mode == MODE_FWD)
-    hipLaunchKernelGGL((gemm_bf16_kernel<128, 128, 2, 2, MODE_FWD, true, 8>), grid, block, 0, st, a, s);
+    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, MODE_FWD, true, S>), grid, block, 0, st, a, s);
   else
-    hipLaunchKernelGGL((gemm_bf16_kernel<128, 128, 2, 2, MODE_DGRAD, true, 8>), grid, block, 0, st, a, s);
+    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, MODE_DGRAD, true, S>), grid, block, 0, st, a, s);
+}
+
+void launch_bf16_gather(const GemmArgs& a, const Segs& s, hipStream_t st) {
+  if (a.N <= 64)
+    launch_bf16_gather_as<256, 64, 4, 1, 4>(a, s, st);
+  else
+    launch_bf16_gather_as<128, 128, 2, 2, 5>(a, s, st);
 }
 
 void launch_f32(const GemmArgs& a, const Segs& s, int groups, hipStream_t st) {

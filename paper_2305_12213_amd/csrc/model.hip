@@ -35,11 +35,12 @@ struct Layer {
   void* Wn = nullptr;                // B operand of the input-gradient GEMM
   void* Wt = nullptr;                // B operand of the forward GEMM
   void* out = nullptr;               // T [rows_out][ld_out]: stored output (not for the last layer)
-  void* inT = nullptr;               // T [wg_rows][cap]: transposed input (dense) / patches (conv)
+  void* inT = nullptr;               // T [wg_rows][cap]: transposed input (dense layers)
   void* dy = nullptr;                // T [rows_out][ld_out]: gradient wrt the output, masked
   void* dyT = nullptr;               // T [n_out][cap]
   int64_t capT = 0;                  // padded row capacity of inT / dyT
   int max_split = 1;                 // most chunks a worker's weight-gradient reduction is cut into
+  int conv_chunk = 0;                // rows per chunk of a convolution's weight gradient
   // batch normalisation: scale at w_off, shift at b_off (n_out floats each); per-worker statistics
   float eps = 0.f;
   float* bn_mean = nullptr;          // fp32 [max_workers][n_out]
@@ -107,9 +108,11 @@ size_t carve(dynb_model* m, void* base, int max_batch, int max_workers) {
       L.bn_rstd = (float*)c.take((size_t)max_workers * L.n_out * 4);
     }
     if (L.has_params) {
-      L.capT = padded_cap(max_batch, L.hw_out, max_workers);
-      L.inT = c.take((size_t)L.wg_rows * L.capT * es);
-      L.dyT = c.take((size_t)L.n_out * L.capT * es);
+      if (L.kind == DYNB_LAYER_DENSE) {   // (a convolution's weight gradient reads the row-major tensors)
+        L.capT = padded_cap(max_batch, L.hw_out, max_workers);
+        L.inT = c.take((size_t)L.wg_rows * L.capT * es);
+        L.dyT = c.take((size_t)L.n_out * L.capT * es);
+      }
       if (L.kind == DYNB_LAYER_DENSE) {
         L.Wn = c.take((size_t)L.n_in * L.ld_out * es);
         L.Wt = c.take((size_t)L.n_out * L.ld_in * es);
@@ -130,18 +133,25 @@ size_t carve(dynb_model* m, void* base, int max_batch, int max_workers) {
   m->logits = (float*)c.take((size_t)max_batch * ldc * 4);
   m->rowloss = (float*)c.take((size_t)max_batch * 4);
   m->loss = (float*)c.take((size_t)DYNB_MAX_WORKERS * 4);
-  // A layer with few weight-gradient tiles has a deep reduction per tile (a convolution sums
-  // over every pixel of every sample): its reduction is cut into chunks that run on separate
-  // workgroups and are summed afterwards in a fixed order.  One scratch area serves all layers.
+  // Scratch of the weight gradients that are reduced in chunks (one area serves all layers): a
+  // dense layer with few weight-gradient tiles splits each worker's reduction over workgroups;
+  // a convolution sums over every pixel of every sample and always works in row chunks.  The
+  // chunk results are added afterwards in a fixed order.
   m->partial_floats = 0;
   for (Layer& L : m->layers) {
     if (!L.has_params || m->dtype != DYNB_BF16) continue;
-    const int64_t tiles = ((L.n_out + 127) / 128) * (int64_t)((L.wg_rows + 127) / 128);
-    L.max_split = tiles >= 32 ? 1 : (int)(256 / tiles > 64 ? 64 : 256 / tiles);
-    if (L.max_split > 1) {
-      const int64_t need = round_up((int64_t)L.wg_rows * L.n_out, 64) * L.max_split * max_workers;
-      if (need > m->partial_floats) m->partial_floats = need;
+    int64_t need = 0;
+    if (L.kind == DYNB_LAYER_CONV3X3) {
+      const int64_t rows = (int64_t)max_batch * L.hw_out;
+      L.conv_chunk = conv_wgrad_chunk_rows(rows);
+      need = conv_wgrad_scratch_floats(rows, max_workers, L.n_in, L.n_out);
+    } else {
+      const int64_t tiles = ((L.n_out + 127) / 128) * (int64_t)((L.wg_rows + 127) / 128);
+      L.max_split = tiles >= 32 ? 1 : (int)(256 / tiles > 64 ? 64 : 256 / tiles);
+      if (L.max_split > 1)
+        need = round_up((int64_t)L.wg_rows * L.n_out, 64) * L.max_split * max_workers;
     }
+    if (need > m->partial_floats) m->partial_floats = need;
   }
   m->partial = (float*)c.take((size_t)m->partial_floats * 4);
   return c.used;
@@ -426,9 +436,6 @@ int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const 
         g.alg_flops = 2.0 * rows_out * L.n_in * L.n_out;
         g.alg_bytes = ((double)rows_out * (L.n_in + L.n_out) + (double)L.n_in * L.n_out) * es;
       } else {
-        rc = launch_im2col_t(in_act(l), L.ld_in, L.n_in, L.h_in, L.w_in, L.h_out, L.w_out, L.stride,
-                             L.inT, L.capT, segs[l], stream);
-        if (rc) return rc;
         g.A = in_act(l); g.lda = L.ld_in;
         g.B = L.Wt; g.ldb = L.kf;
         g.K = L.kf;
@@ -454,7 +461,7 @@ int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const 
                                L.dy, L.ld_out, stream);
         if (rc) return rc;
       }
-      if (L.has_params) {
+      if (L.kind == DYNB_LAYER_DENSE) {
         rc = launch_transpose(dt, L.dy, L.ld_out, L.n_out, L.dyT, L.capT, segs[l], stream);
         if (rc) return rc;
       }
@@ -548,6 +555,25 @@ int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const 
       continue;
     }
     if (!L.has_params) continue;
+    if (L.kind == DYNB_LAYER_CONV3X3) {
+      rc = launch_conv_wgrad(in_act(l), L.ld_in, L.n_in, L.h_in, L.w_in, L.dy, L.ld_out, L.n_out,
+                             L.h_out, L.w_out, L.stride, L.conv_chunk, m->partial, m->partial_floats,
+                             grads + L.w_off, m->P_pad, segs[l],
+                             2.0 * B * L.hw_out * L.wg_rows * L.n_out,
+                             (double)K * L.wg_rows * L.n_out * 4 +
+                                 (double)B * (L.hw_in * L.n_in + L.hw_out * L.n_out) * es,
+                             stream);
+      if (rc) return rc;
+      rc = launch_column_sums(L.dy, L.ld_out, L.n_out, m->row_scratch, grads + L.b_off, m->P_pad,
+                              segs[l], stream);
+      if (rc) return rc;
+      if (agg) {
+        rc = add_small(L.w_off, (int64_t)L.wg_rows * L.n_out);
+        if (!rc) rc = add_small(L.b_off, L.n_out);
+        if (rc) return rc;
+      }
+      continue;
+    }
     GemmArgs g = {};
     g.mode = MODE_WGRAD;
     g.A = L.dyT; g.lda = L.capT; g.M = L.n_out;
@@ -584,11 +610,7 @@ int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const 
                                grads + L.w_off, m->P_pad, K, stream);
       if (rc) return rc;
     }
-    if (L.kind == DYNB_LAYER_CONV3X3)   // rows are pixels: long columns, summed in row chunks
-      rc = launch_column_sums(L.dy, L.ld_out, L.n_out, m->row_scratch, grads + L.b_off, m->P_pad,
-                              segs[l], stream);
-    else
-      rc = launch_bias_grad(dt, L.dyT, L.capT, L.n_out, grads + L.b_off, m->P_pad, segs[l], stream);
+    rc = launch_bias_grad(dt, L.dyT, L.capT, L.n_out, grads + L.b_off, m->P_pad, segs[l], stream);
     if (rc) return rc;
     if (agg) {
       const int64_t nw = (int64_t)L.wg_rows * L.n_out;
