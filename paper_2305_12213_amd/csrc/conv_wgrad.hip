@@ -14,7 +14,8 @@
 // 32 pixels x one kernel row (3 taps): 3 x 4 KB of shifted input rows and 4 KB of dy, copied
 // global -> LDS asynchronously into a ring of 4 stage buffers.  Chunk results go to a scratch
 // area in register order and a second kernel adds the chunks of each worker in a fixed order
-// (deterministic, no atomics).
+// (deterministic, no atomics).  The bias gradient (column sums of dy) rides along as a tenth
+// "tap" whose input operand is all ones.
 #include <hip/hip_runtime.h>
 
 #include "dynb_internal.h"
@@ -33,7 +34,9 @@ constexpr int S = 4;                         // stage buffers
 constexpr int TILE_BYTES = 32 * 128;         // 32 pixels x 64 channels
 constexpr int STAGE_BYTES = 4 * TILE_BYTES;  // three shifted input tiles + the dy tile
 constexpr int PER = 4;                       // copies per wave and stage
-constexpr int TILE_FLOATS = 9 * 64 * 64;     // one chunk result (per 64 x 64 channel block)
+constexpr int SLOTS = 10;                    // nine taps and the column sums of dy
+constexpr int TILE_FLOATS = 4 * SLOTS * 16 * 64;   // one chunk result per 64 x 64 channel block:
+                                                   // [wave][slot][16 accumulator elements][lane]
 
 __device__ uint4 g_zeros[1];                 // what lanes outside the image or the chunk fetch
 
@@ -142,11 +145,18 @@ __global__ __launch_bounds__(256) void conv_wgrad_chunk_kernel(ConvWgradArgs p, 
     return __builtin_bit_cast(bf16x8, v);
   };
 
-  f32x16 acc[9];
+  f32x16 acc[9], colsum;
 #pragma unroll
   for (int t = 0; t < 9; ++t)
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) colsum[v] = 0.f;
+  // the waves of the first input-channel block that own input channels [0, 32) also sum dy over
+  // the pixels: an MFMA against ones (pixels outside the chunk hold zeros in the dy tile)
+  const bool sums_columns = cib == 0 && wci == 0;
+  const s16x8 ones_bits = {0x3f80, 0x3f80, 0x3f80, 0x3f80, 0x3f80, 0x3f80, 0x3f80, 0x3f80};
+  const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_bits);
 
   // ---- the stage pipeline: S - 1 stages in flight, one barrier per stage ----
   int issued = 0;                                // stages issued so far (its kernel row = issued % 3)
@@ -170,6 +180,10 @@ __global__ __launch_bounds__(256) void conv_wgrad_chunk_kernel(ConvWgradArgs p, 
       const uint32_t stage = lds0 + (uint32_t)((t % S) * STAGE_BYTES);
       const bf16x8 b0 = frag(stage + 3 * TILE_BYTES, foff_b, 0);
       const bf16x8 b1 = frag(stage + 3 * TILE_BYTES, foff_b, 1);
+      if (kh == 1 && sums_columns) {             // once per pixel block
+        colsum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b0, ones, colsum, 0, 0, 0);
+        colsum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b1, ones, colsum, 0, 0, 0);
+      }
 #pragma unroll
       for (int kw = 0; kw < 3; ++kw) {
         const bf16x8 a0 = frag(stage + kw * TILE_BYTES, foff_a, 0);
@@ -181,40 +195,54 @@ __global__ __launch_bounds__(256) void conv_wgrad_chunk_kernel(ConvWgradArgs p, 
     }
   }
 
-  // ---- chunk result, in register order: [wave][tap][v/4][lane] x 4 floats ----
+  // ---- chunk result, in register order: [wave][slot][v/4][lane] x 4 floats ----
   float* out = p.partial + ((int64_t)(chunk * gridDim.y + cib) * gridDim.z + cob) * TILE_FLOATS;
 #pragma unroll
   for (int t = 0; t < 9; ++t)
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const f32x4 o = {acc[t][4 * q], acc[t][4 * q + 1], acc[t][4 * q + 2], acc[t][4 * q + 3]};
-      *(f32x4*)&out[(((wave * 9 + t) * 4 + q) * 64 + lane) * 4] = o;
+      *(f32x4*)&out[(((wave * SLOTS + t) * 4 + q) * 64 + lane) * 4] = o;
     }
+  if (sums_columns) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const f32x4 o = {colsum[4 * q], colsum[4 * q + 1], colsum[4 * q + 2], colsum[4 * q + 3]};
+      *(f32x4*)&out[(((wave * SLOTS + 9) * 4 + q) * 64 + lane) * 4] = o;
+    }
+  }
 }
 
-// dW_k[tap][ci][co .. co+3] = the chunk results of worker k added in ascending chunk order.
+// dW_k[tap][ci][co .. co+3] = the chunk results of worker k added in ascending chunk order; the
+// items behind the weights are the bias gradients db_k[co .. co+3] (slot 9, input channel 0).
 // Accumulator element v of lane l belongs to output channel 8*(v/4) + 4*(l/32) + v%4 and input
 // channel l%32 of the wave's corner.
 __global__ __launch_bounds__(256) void conv_wgrad_reduce_kernel(const float* __restrict__ partial,
                                                                 int Cin, int Cout, int cibs, int cobs,
-                                                                float* __restrict__ grads,
+                                                                float* __restrict__ dW,
+                                                                float* __restrict__ db,
                                                                 int64_t group_stride, RowChunks ch) {
   const int k = blockIdx.y;
   const int quads = (Cout + 3) / 4;
-  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;    // (tap, ci, quad of co)
-  if (idx >= (int64_t)9 * Cin * quads) return;
-  const int quad = (int)(idx % quads);
-  const int ci = (int)((idx / quads) % Cin), tap = (int)(idx / ((int64_t)quads * Cin));
+  const int64_t n_weight = (int64_t)9 * Cin * quads;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;    // (tap, ci, quad of co) | quad
+  if (idx >= n_weight + quads) return;
+  const bool bias = idx >= n_weight;
+  const int64_t w = bias ? 0 : idx;
+  const int quad = bias ? (int)(idx - n_weight) : (int)(w % quads);
+  const int ci = bias ? 0 : (int)((w / quads) % Cin);
+  const int slot = bias ? 9 : (int)(w / ((int64_t)quads * Cin));
   const int co = quad * 4;
   const int cib = ci >> 6, cob = co >> 6, cil = ci & 63, col = co & 63;
   const int wave = (cil >> 5) + 2 * (col >> 5);
   const int c32 = col & 31;
   const int q = c32 >> 3, lane = (cil & 31) + 32 * ((c32 & 7) >> 2);
-  const int64_t within = ((int64_t)((wave * 9 + tap) * 4 + q) * 64 + lane) * 4;
+  const int64_t within = ((int64_t)((wave * SLOTS + slot) * 4 + q) * 64 + lane) * 4;
   f32x4 sum = {0.f, 0.f, 0.f, 0.f};
   for (int c = ch.first[k]; c < ch.first[k + 1]; ++c)
     sum += *(const f32x4*)&partial[((int64_t)(c * cibs + cib) * cobs + cob) * TILE_FLOATS + within];
-  float* dst = grads + (int64_t)k * group_stride + ((int64_t)tap * Cin + ci) * Cout + co;
+  float* dst = bias ? db + (int64_t)k * group_stride + co
+                    : dW + (int64_t)k * group_stride + ((int64_t)slot * Cin + ci) * Cout + co;
 #pragma unroll
   for (int e = 0; e < 4; ++e)
     if (co + e < Cout) dst[e] = sum[e];
@@ -247,8 +275,8 @@ int64_t conv_wgrad_scratch_floats(int64_t max_rows, int max_workers, int Cin, in
 
 int launch_conv_wgrad(const void* in, int64_t ldi, int Cin, int H, int W, const void* dy, int64_t ldd,
                       int Cout, int Ho, int Wo, int stride, int chunk_rows, float* scratch,
-                      int64_t scratch_floats, float* grads, int64_t group_stride, const Segs& s,
-                      double flops, double bytes, void* stream) {
+                      int64_t scratch_floats, float* dW, float* db, int64_t group_stride,
+                      const Segs& s, double flops, double bytes, void* stream) {
   if (Cin <= 0 || Cout <= 0) return DYNB_OK;
   const int cibs = (Cin + 63) / 64, cobs = (Cout + 63) / 64;
   if (ldi % 64 || ldd % 64 || ldi < 64 * cibs || ldd < 64 * cobs || chunk_rows < 32 || chunk_rows % 32 ||
@@ -264,9 +292,9 @@ int launch_conv_wgrad(const void* in, int64_t ldi, int Cin, int H, int W, const 
     hipLaunchKernelGGL(conv_wgrad_chunk_kernel, dim3(nch, cibs, cobs), dim3(256), 0,
                        (hipStream_t)stream, a, s, ch);
   }
-  const int64_t items = (int64_t)9 * Cin * ((Cout + 3) / 4);
+  const int64_t items = (int64_t)(9 * Cin + 1) * ((Cout + 3) / 4);
   hipLaunchKernelGGL(conv_wgrad_reduce_kernel, dim3((unsigned)((items + 255) / 256), s.K), dim3(256), 0,
-                     (hipStream_t)stream, scratch, Cin, Cout, cibs, cobs, grads, group_stride, ch);
+                     (hipStream_t)stream, scratch, Cin, Cout, cibs, cobs, dW, db, group_stride, ch);
   return hipGetLastError() == hipSuccess ? DYNB_OK : fail(DYNB_ERR_HIP, "conv_wgrad: launch failed");
 }
 

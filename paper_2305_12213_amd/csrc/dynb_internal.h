@@ -187,8 +187,6 @@ int launch_wgrad_reduce(const float* partial, int split, int64_t partial_stride,
 
 // ---- convolution helpers (bf16 storage) ----
 // out bf16 [9*C][ldo]: transposed patch matrix over the padded pixel positions of segments s
-int launch_im2col_t(const void* in, int64_t ldi, int C, int H, int W, int Ho, int Wo, int stride,
-                    void* out, int64_t ldo, const Segs& s, void* stream);
 int launch_gap_forward(const void* act, int64_t lda, int HW, int C, int samples, void* pooled,
                        int64_t ldp, void* stream);
 int launch_gap_backward(const void* dpooled, int64_t ldp, const void* act, int64_t lda, int HW,
@@ -205,15 +203,15 @@ struct RowChunks {
 RowChunks make_row_chunks(const Segs& s, int rows);
 
 // Per-worker weight gradient of a 3x3 convolution straight from the row-major activations
-// (bf16 in: [samples*H*W][ldi], dy: [samples*Ho*Wo][ldd]; grads[k * group_stride + (tap*Cin +
-// ci)*Cout + co], fp32).  chunk_rows = conv_wgrad_chunk_rows(largest row count of the model's
+// (bf16 in: [samples*H*W][ldi], dy: [samples*Ho*Wo][ldd]; dW[k * group_stride + (tap*Cin +
+// ci)*Cout + co] and the bias gradient db[k * group_stride + co], fp32).  chunk_rows = conv_wgrad_chunk_rows(largest row count of the model's
 // plan); scratch: conv_wgrad_scratch_floats() floats.
 int conv_wgrad_chunk_rows(int64_t max_rows);
 int64_t conv_wgrad_scratch_floats(int64_t max_rows, int max_workers, int Cin, int Cout);
 int launch_conv_wgrad(const void* in, int64_t ldi, int Cin, int H, int W, const void* dy, int64_t ldd,
                       int Cout, int Ho, int Wo, int stride, int chunk_rows, float* scratch,
-                      int64_t scratch_floats, float* grads, int64_t group_stride, const Segs& s,
-                      double flops, double bytes, void* stream);
+                      int64_t scratch_floats, float* dW, float* db, int64_t group_stride,
+                      const Segs& s, double flops, double bytes, void* stream);
 
 // Batch normalisation over each worker's own rows (bf16; x: T [rows][ldx], y: T [rows][ldy]):
 // writes mean / rstd [k][C] (kept for the backward pass).  `scratch`: row_scratch_floats() floats
@@ -229,10 +227,6 @@ int launch_bn_backward(const void* dy, int64_t ldd, const void* x, int64_t ldx, 
                        const float* gamma, const float* mean, const float* rstd, float* scratch,
                        float* dgamma, float* dbeta, int64_t group_stride, int need_dx,
                        int relu_below, void* dx, int64_t ldo, const Segs& s, void* stream);
-// out[k * group_stride + c] = sum of dy[row][c] over worker k's rows (bf16 dy, T [rows][ldd]):
-// the bias gradient of a layer whose rows are pixels; same scratch as above
-int launch_column_sums(const void* dy, int64_t ldd, int C, float* scratch, float* out,
-                       int64_t group_stride, const Segs& s, void* stream);
 // out = relu?(a + b) over `width` (padded, a multiple of 8) columns of `rows` rows
 int launch_add_forward(const void* a, int64_t lda, const void* b, int64_t ldb, int64_t width,
                        int64_t rows, int relu, void* out, int64_t ldo, void* stream);

@@ -1,6 +1,5 @@
 // Kernels around the implicit-GEMM convolutions (NHWC, 3x3, zero padding 1; bf16 storage):
-// the transposed patch matrix that feeds the per-worker weight-gradient GEMM, global average
-// pooling forward/backward, and the two 16-bit weight layouts of a convolution.
+// global average pooling forward/backward and the two 16-bit weight layouts of a convolution.
 #include <hip/hip_runtime.h>
 
 #include "device_rows.h"
@@ -8,79 +7,6 @@
 
 namespace dynb {
 namespace {
-
-
-__device__ inline void locate_padded(const Segs& s, int prow, int& k, int& r) {
-  k = 0;
-  while (k + 1 < s.K && prow >= s.poff[k + 1]) ++k;
-  r = prow - s.poff[k];
-}
-
-// out[(kh*3 + kw)*C + c][p] = in[(n, ho*stride + kh - 1, wo*stride + kw - 1)][c] for the output
-// pixel (n, ho, wo) that sits at padded position p (pixel-level segments `s`), zero for
-// padding positions and out-of-range taps.  A workgroup takes 64 positions x 64 channels and
-// walks the nine taps: the source rows are read as whole 128-byte lines (8 lanes x 16 bytes),
-// turned in LDS, and written as 128-byte runs of 64 positions per (tap, channel) row.
-__global__ __launch_bounds__(256) void im2col_t_kernel(const bf16* __restrict__ in, int64_t ldi,
-                                                       int C, int H, int W, int Ho, int Wo,
-                                                       int stride, bf16* __restrict__ out,
-                                                       int64_t ldo, Segs s) {
-  // 33 dwords per position: the turned reads of 8 lanes (8 positions apart) fall in 8 banks
-  __shared__ uint32_t tile[64][33];
-  const int P = s.poff[s.K];
-  const int p0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
-  const int lo = threadIdx.x & 7, hi = threadIdx.x >> 3;
-  // reading: this thread fetches channels [c0 + 8*lo, +8) of positions hi and hi + 32
-  int img[2], ho[2], wo[2];
-  bool live[2];
-#pragma unroll
-  for (int q = 0; q < 2; ++q) {
-    const int p = p0 + hi + 32 * q;
-    live[q] = false;
-    img[q] = ho[q] = wo[q] = 0;
-    if (p < P) {
-      int k, r;
-      locate_padded(s, p, k, r);
-      if (r < s.off[k + 1] - s.off[k]) {
-        const int m = s.off[k] + r;                // dense output pixel
-        img[q] = m / (Ho * Wo);
-        const int rem = m - img[q] * (Ho * Wo);
-        ho[q] = rem / Wo;
-        wo[q] = rem - ho[q] * Wo;
-        live[q] = true;
-      }
-    }
-  }
-  // writing: 8 positions [p0 + 8*lo, +8) of channels hi and hi + 32
-  const bool write_ok = p0 + 8 * lo < P;
-  for (int tap = 0; tap < 9; ++tap) {
-    const int kh = tap / 3, kw = tap - kh * 3;
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      uint4 v = make_uint4(0, 0, 0, 0);
-      const int y = ho[q] * stride + kh - 1, x = wo[q] * stride + kw - 1;
-      if (live[q] && y >= 0 && y < H && x >= 0 && x < W)
-        v = load8(in + ((int64_t)(img[q] * H + y) * W + x) * ldi + c0 + 8 * lo);
-      uint32_t* t = &tile[hi + 32 * q][4 * lo];
-      t[0] = v.x; t[1] = v.y; t[2] = v.z; t[3] = v.w;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      const int c = hi + 32 * q;
-      if (write_ok && c0 + c < C) {
-        uint32_t w[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {              // positions 8*lo + 2e and + 2e + 1, channel c
-          const uint32_t a = tile[8 * lo + 2 * e][c >> 1], b = tile[8 * lo + 2 * e + 1][c >> 1];
-          w[e] = (c & 1) ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
-        }
-        store8(out + (int64_t)(tap * C + c0 + c) * ldo + p0 + 8 * lo, make_uint4(w[0], w[1], w[2], w[3]));
-      }
-    }
-    __syncthreads();
-  }
-}
 
 // pooled[n][c] = mean over the HW pixels of act[(n, pixel)][c]   (fp32 sum in a fixed order,
 // bf16 store).  One workgroup per (sample, 64 channels); padding channels are written as zero.
@@ -164,19 +90,6 @@ inline int ok(const char* what) {
 }
 
 }  // namespace
-
-int launch_im2col_t(const void* in, int64_t ldi, int C, int H, int W, int Ho, int Wo, int stride,
-                    void* out, int64_t ldo, const Segs& s, void* stream) {
-  const int P = s.poff[s.K];
-  if (P == 0) return DYNB_OK;
-  if (ldi % 64 || ldo % 64 || ldo < P)
-    return fail(DYNB_ERR_BADARG, "im2col_t: pitches must be multiples of 64 and cover the positions");
-  Timed t(KC_CONV_AUX, stream, 0, 2.0 * 9 * C * (double)s.off[s.K] * 2);
-  dim3 grid((P + 63) / 64, (C + 63) / 64);
-  hipLaunchKernelGGL(im2col_t_kernel, grid, dim3(256), 0, (hipStream_t)stream, (const bf16*)in, ldi,
-                     C, H, W, Ho, Wo, stride, (bf16*)out, ldo, s);
-  return ok("im2col_t");
-}
 
 int launch_gap_forward(const void* act, int64_t lda, int HW, int C, int samples, void* pooled,
                        int64_t ldp, void* stream) {

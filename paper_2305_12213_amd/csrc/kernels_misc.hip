@@ -70,6 +70,20 @@ __global__ __launch_bounds__(256) void pack_rows_vec_kernel(const float* __restr
   }
 }
 
+// rows of at most 8 features (an RGB pixel): one lane per row, one 16-byte store; the columns
+// [D, 8) are written as zero, the rest of the padded row is never touched (it holds zeros)
+__global__ __launch_bounds__(256) void pack_rows_narrow_kernel(const float* __restrict__ x,
+                                                               int64_t rows, int D,
+                                                               __bf16* __restrict__ out, int64_t ld) {
+  typedef __bf16 vec8 __attribute__((ext_vector_type(8)));
+  const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (r >= rows) return;
+  vec8 v;
+#pragma unroll
+  for (int c = 0; c < 8; ++c) v[c] = c < D ? (__bf16)x[r * D + c] : (__bf16)0.f;
+  *(vec8*)(out + r * ld) = v;
+}
+
 // ---- transpose into the padded row space: out[c][p] = in[m(p)][c], 0 where p is padding ----
 // p runs over the padded positions; worker k's b_k rows sit at [poff_k, poff_k + b_k).
 // A 64 x 64 tile moves through LDS; global loads and stores are 16 bytes per lane, and eight
@@ -240,6 +254,11 @@ int launch_pack_rows(int dtype, const float* x, int rows, int D, void* out, int6
     if (blocks > 256 * 32) blocks = 256 * 32;
     DISPATCH_T(dtype, hipLaunchKernelGGL(pack_rows_vec_kernel<T>, dim3((unsigned)blocks), dim3(256), 0,
                                          (hipStream_t)stream, x, (int64_t)rows, D, (T*)out, ld));
+    return ok("pack_rows");
+  }
+  if (dtype == DYNB_BF16 && D <= 8 && (ld & 7) == 0 && !((uintptr_t)out & 15)) {
+    hipLaunchKernelGGL(pack_rows_narrow_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0,
+                       (hipStream_t)stream, x, (int64_t)rows, D, (__bf16*)out, ld);
     return ok("pack_rows");
   }
   dim3 grid((D + 255) / 256 > 8 ? 8 : (D + 255) / 256, rows);

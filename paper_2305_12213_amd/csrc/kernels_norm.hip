@@ -218,54 +218,6 @@ __global__ __launch_bounds__(256) void bn_merge_param_grad_kernel(const float* _
   }
 }
 
-// Chunk sums of the columns of dy (the bias gradient of a layer whose rows are pixels).
-__global__ __launch_bounds__(256) void column_sum_chunk_kernel(const bf16* __restrict__ dy, int64_t ldd,
-                                                               int C, float* __restrict__ part,
-                                                               Segs s, Chunks ch) {
-  __shared__ float red[4][64];
-  const int cg = threadIdx.x & 7, rl = threadIdx.x >> 3;
-  const int chunk = blockIdx.x, c0 = blockIdx.y * 64 + cg * 8;
-  int k, r0, n;
-  chunk_span(s, ch, chunk, k, r0, n);
-  const bf16* db = dy + (int64_t)r0 * ldd + c0;
-  float acc[8];
-#pragma unroll
-  for (int j = 0; j < 8; ++j) acc[j] = 0.f;
-#pragma unroll
-  for (int i = 0; i < PASSES; ++i) {
-    const int r = rl + 32 * i;
-    if (r < n) {
-      float d[8];
-      unpack8(load8(db + (int64_t)r * ldd), d);
-#pragma unroll
-      for (int j = 0; j < 8; ++j) acc[j] += d[j];
-    }
-  }
-  sum_over_rows(acc, red);
-  if (rl == 0) {
-#pragma unroll
-    for (int j = 0; j < 8; ++j)
-      if (c0 + j < C) part[(int64_t)chunk * C + c0 + j] = acc[j];
-  }
-}
-
-// out[k][c] = the chunk sums of worker k added in a fixed order; zeros for a worker without rows
-__global__ __launch_bounds__(256) void column_sum_merge_kernel(const float* __restrict__ part, int C,
-                                                               float* __restrict__ out,
-                                                               int64_t group_stride, Chunks ch) {
-  __shared__ float sp[4][64];
-  const int cl = threadIdx.x & 63, q = threadIdx.x >> 6;
-  const int c = blockIdx.x * 64 + cl, k = blockIdx.y;
-  const int first = ch.first[k], nc = ch.first[k + 1] - first;
-  float a = 0.f;
-  if (c < C)
-    for (int j = q; j < nc; j += 4) a += part[(int64_t)(first + j) * C + c];
-  sp[q][cl] = a;
-  __syncthreads();
-  if (q == 0 && c < C)
-    out[(int64_t)k * group_stride + c] = ((sp[0][cl] + sp[1][cl]) + sp[2][cl]) + sp[3][cl];
-}
-
 // dx = gamma * rstd * (dy - dbeta/n - xhat * dgamma/n), masked by the producer's ReLU (x > 0);
 // padding channels are written as zero
 __global__ __launch_bounds__(256) void bn_input_grad_kernel(
@@ -417,20 +369,6 @@ int launch_bn_backward(const void* dy, int64_t ldd, const void* x, int64_t ldx, 
                        (hipStream_t)stream, (const bf16*)dy, ldd, (const bf16*)x, ldx, C, gamma, mean,
                        rstd, dgamma, dbeta, group_stride, relu_below, (bf16*)dx, ldo, s, ch);
   return ok("bn_backward");
-}
-
-int launch_column_sums(const void* dy, int64_t ldd, int C, float* scratch, float* out,
-                       int64_t group_stride, const Segs& s, void* stream) {
-  if (C == 0) return DYNB_OK;
-  const Chunks ch = make_chunks(s);
-  const int nch = ch.first[s.K], cb = (C + 63) / 64;
-  Timed t(KC_BIAS_GRAD, stream, 0, (double)s.off[s.K] * C * 2);
-  if (nch > 0)
-    hipLaunchKernelGGL(column_sum_chunk_kernel, dim3(nch, cb), dim3(256), 0, (hipStream_t)stream,
-                       (const bf16*)dy, ldd, C, scratch, s, ch);
-  hipLaunchKernelGGL(column_sum_merge_kernel, dim3(cb, s.K), dim3(256), 0, (hipStream_t)stream,
-                     scratch, C, out, group_stride, ch);
-  return ok("column_sums");
 }
 
 int64_t row_scratch_floats(int64_t max_rows, int max_workers, int C) {

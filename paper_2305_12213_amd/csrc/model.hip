@@ -124,7 +124,7 @@ size_t carve(dynb_model* m, void* base, int max_batch, int max_workers) {
   }
   int64_t bn_floats = 0;
   for (Layer& L : m->layers)
-    if (L.kind == DYNB_LAYER_BN || L.kind == DYNB_LAYER_CONV3X3) {
+    if (L.kind == DYNB_LAYER_BN) {
       const int64_t need = row_scratch_floats((int64_t)max_batch * L.hw_out, max_workers, L.n_out);
       if (need > bn_floats) bn_floats = need;
     }
@@ -558,14 +558,11 @@ int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const 
     if (L.kind == DYNB_LAYER_CONV3X3) {
       rc = launch_conv_wgrad(in_act(l), L.ld_in, L.n_in, L.h_in, L.w_in, L.dy, L.ld_out, L.n_out,
                              L.h_out, L.w_out, L.stride, L.conv_chunk, m->partial, m->partial_floats,
-                             grads + L.w_off, m->P_pad, segs[l],
+                             grads + L.w_off, grads + L.b_off, m->P_pad, segs[l],
                              2.0 * B * L.hw_out * L.wg_rows * L.n_out,
                              (double)K * L.wg_rows * L.n_out * 4 +
                                  (double)B * (L.hw_in * L.n_in + L.hw_out * L.n_out) * es,
                              stream);
-      if (rc) return rc;
-      rc = launch_column_sums(L.dy, L.ld_out, L.n_out, m->row_scratch, grads + L.b_off, m->P_pad,
-                              segs[l], stream);
       if (rc) return rc;
       if (agg) {
         rc = add_small(L.w_off, (int64_t)L.wg_rows * L.n_out);
