@@ -74,7 +74,9 @@ enum { MODE_FWD = 0, MODE_DGRAD = 1, MODE_WGRAD = 2 };
 //   FWD   : i = batch row, j = output feature.  v = acc + bias[j], optional ReLU;
 //           C[i*ldc + j] = T(v) if C; Cf[i*ldcf + j] = v if Cf.
 //   DGRAD : i = batch row, j = input feature.  v = mask[i*ldmask + j] > 0 ? acc : 0 (mask
-//           optional); C[i*ldc + j] = T(v).
+//           optional); C[i*ldc + j] = T(v).  With `addend` (bf16 only: the gradient that reaches
+//           the same tensor over a residual branch) acc is first rounded to T and
+//           addend[i*ldadd + j] added, then the mask is applied.
 //   WGRAD : one group per worker g: operands start at column poff[g], depth
 //           poff[g+1]-poff[g]; i = output feature, j = input feature;
 //           Cf[g*group_stride + j*ldcf + i] = acc.
@@ -87,6 +89,7 @@ struct GemmArgs {
   void* C; int64_t ldc;
   float* Cf; int64_t ldcf;
   const void* mask; int64_t ldmask;
+  const void* addend; int64_t ldadd;   // DGRAD, bf16: see above
   int64_t group_stride;
   int groups_per_block;                // WGRAD, bf16 kernel: workers streamed by one workgroup
   // Implicit-GEMM gather of operand A for a 3x3 convolution with zero padding 1 (bf16 only).
@@ -218,9 +221,11 @@ int launch_conv_wgrad(const void* in, int64_t ldi, int Cin, int H, int W, const 
 // (the partial results of the row chunks), shared by forward and backward.
 constexpr int BN_CHUNK_ROWS = 256;
 int64_t row_scratch_floats(int64_t max_rows, int max_workers, int C);
+// With `skip` (a residual addition fused in): y = relu_sum?(T(normalised) + skip).
 int launch_bn_forward(const void* x, int64_t ldx, int C, const float* gamma, const float* beta,
-                      float eps, int relu, float* mean, float* rstd, float* scratch, void* y,
-                      int64_t ldy, const Segs& s, void* stream);
+                      float eps, int relu, float* mean, float* rstd, float* scratch,
+                      const void* skip, int64_t lds_, int relu_sum, void* y, int64_t ldy,
+                      const Segs& s, void* stream);
 // dgamma / dbeta[k * group_stride + c] (fp32, per worker) from dy (already masked by the layer's
 // own ReLU); with need_dx also dx (T [rows][ldo]), masked by x > 0 when relu_below
 int launch_bn_backward(const void* dy, int64_t ldd, const void* x, int64_t ldx, int C,

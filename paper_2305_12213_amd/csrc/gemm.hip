@@ -566,6 +566,11 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
           }
         }
         if (col_ok) {
+          if (MODE == MODE_DGRAD && p.addend) {
+            const bf16x8 ad = *(const bf16x8*)((const bf16*)p.addend + (int64_t)i * p.ldadd + jcol);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = (float)(bf16)v[e] + (float)ad[e];
+          }
           if (MODE == MODE_DGRAD && p.mask) {
             const bf16x8 mk = *(const bf16x8*)((const bf16*)p.mask + (int64_t)i * p.ldmask + jcol);
 #pragma unroll
@@ -588,6 +593,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
             const int j = jcol + e;
             if (j >= p.N) continue;
             float w = v[e];
+            if (MODE == MODE_DGRAD && p.addend)
+              w = (float)(bf16)w + (float)((const bf16*)p.addend)[(int64_t)i * p.ldadd + j];
             if (MODE == MODE_DGRAD && p.mask &&
                 !((float)((const bf16*)p.mask)[(int64_t)i * p.ldmask + j] > 0.f))
               w = 0.f;
@@ -743,6 +750,8 @@ int launch_gemm(int dtype, const GemmArgs& a, const Segs& s, void* stream) {
   const int gran = 16 / es;
   if ((a.lda % gran) || (a.ldb % gran) || ((uintptr_t)a.A & 15) || ((uintptr_t)a.B & 15))
     return fail(DYNB_ERR_BADARG, "gemm: operands must have 16-byte aligned rows");
+  if (a.addend && (dtype != DYNB_BF16 || a.mode != MODE_DGRAD))
+    return fail(DYNB_ERR_UNSUPPORTED, "gemm: an addend belongs to a bf16 input gradient");
   const int groups = a.mode == MODE_WGRAD ? s.K : 1;
   const KClass cls = a.mode == MODE_FWD ? KC_GEMM_FWD : a.mode == MODE_DGRAD ? KC_GEMM_DGRAD
                                                                               : KC_GEMM_WGRAD;

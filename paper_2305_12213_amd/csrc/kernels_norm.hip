@@ -107,14 +107,17 @@ __global__ __launch_bounds__(256) void bn_merge_stats_kernel(const float* __rest
   }
 }
 
-// y = relu?(gamma * ((x - mean_k) * rstd_k) + beta); padding channels are written as zero
+// y = relu?(gamma * ((x - mean_k) * rstd_k) + beta); padding channels are written as zero.
+// With `skip`, the residual addition behind the normalisation is applied in the same pass:
+// y = relu_sum?(bf16(normalised) + skip) -- rounded as if the normalised tensor had been stored.
 __global__ __launch_bounds__(256) void bn_apply_kernel(const bf16* __restrict__ x, int64_t ldx, int C,
                                                        const float* __restrict__ gamma,
                                                        const float* __restrict__ beta,
                                                        const float* __restrict__ mean,
                                                        const float* __restrict__ rstd, int relu,
-                                                       bf16* __restrict__ y, int64_t ldy, Segs s,
-                                                       Chunks ch) {
+                                                       const bf16* __restrict__ skip, int64_t lds_,
+                                                       int relu_sum, bf16* __restrict__ y, int64_t ldy,
+                                                       Segs s, Chunks ch) {
   const int cg = threadIdx.x & 7, rl = threadIdx.x >> 3;
   const int chunk = blockIdx.x, c0 = blockIdx.y * 64 + cg * 8;
   int k, r0, n;
@@ -141,6 +144,16 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const bf16* __restrict__ 
         float t = ga[j] * ((v[j] - mu[j]) * rs[j]) + be[j];
         if (relu) t = fmaxf(t, 0.f);
         v[j] = c0 + j < C ? t : 0.f;
+      }
+      if (skip) {
+        float u[8], w[8];
+        unpack8(pack8(v), u);                    // the normalised values as they would be stored
+        unpack8(load8(skip + (int64_t)(r0 + r) * lds_ + c0), w);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          v[j] = u[j] + w[j];
+          if (relu_sum) v[j] = fmaxf(v[j], 0.f);
+        }
       }
       store8(yb + (int64_t)r * ldy, pack8(v));
     }
@@ -329,22 +342,23 @@ Chunks make_chunks(const Segs& s) {
 }  // namespace
 
 int launch_bn_forward(const void* x, int64_t ldx, int C, const float* gamma, const float* beta,
-                      float eps, int relu, float* mean, float* rstd, float* scratch, void* y,
-                      int64_t ldy, const Segs& s, void* stream) {
+                      float eps, int relu, float* mean, float* rstd, float* scratch,
+                      const void* skip, int64_t lds_, int relu_sum, void* y, int64_t ldy,
+                      const Segs& s, void* stream) {
   const int rows = s.off[s.K];
   if (rows == 0 || C == 0) return DYNB_OK;
   const Chunks ch = make_chunks(s);
   const int nch = ch.first[s.K], cb = (C + 63) / 64;
   float* pmean = scratch;
   float* pm2 = scratch + (int64_t)nch * C;
-  Timed t(KC_NORM, stream, 0, (double)rows * C * 6);     // x twice, y once
+  Timed t(KC_NORM, stream, 0, (double)rows * C * (skip ? 8 : 6));     // x twice, y once (+ skip)
   hipLaunchKernelGGL(bn_chunk_stats_kernel, dim3(nch, cb), dim3(256), 0, (hipStream_t)stream,
                      (const bf16*)x, ldx, C, pmean, pm2, s, ch);
   hipLaunchKernelGGL(bn_merge_stats_kernel, dim3(cb, s.K), dim3(256), 0, (hipStream_t)stream, pmean,
                      pm2, C, eps, mean, rstd, s, ch);
   hipLaunchKernelGGL(bn_apply_kernel, dim3(nch, (unsigned)(ldy / 64)), dim3(256), 0,
                      (hipStream_t)stream, (const bf16*)x, ldx, C, gamma, beta, mean, rstd, relu,
-                     (bf16*)y, ldy, s, ch);
+                     (const bf16*)skip, lds_, relu_sum, (bf16*)y, ldy, s, ch);
   return ok("bn_forward");
 }
 

@@ -49,7 +49,13 @@ struct Layer {
   // receives the gradient of that branch in dy_skip and merges it into dy
   int skip_from = -1;
   bool skip_source = false;
-  void* dy_skip = nullptr;           // T [rows_out][ld_out]
+  void* dy_skip = nullptr;           // T [rows_out][ld_out]; not needed when skip_fused
+  // the layer above a skip source is a matrix product: its input-gradient kernel adds the
+  // residual branch's gradient while writing this layer's dy (no separate pass)
+  bool skip_fused = false;
+  // a normalisation without ReLU directly in front of a residual addition: both run in one
+  // kernel and the normalised tensor itself is never stored
+  bool add_fused = false;
 };
 
 struct dynb_model {
@@ -100,9 +106,9 @@ size_t carve(dynb_model* m, void* base, int max_batch, int max_workers) {
     Layer& L = m->layers[l];
     const bool last = l + 1 == m->layers.size();
     const int64_t rows_out = (int64_t)max_batch * L.hw_out;
-    if (!last) L.out = c.take((size_t)rows_out * L.ld_out * es);
+    if (!last && !L.add_fused) L.out = c.take((size_t)rows_out * L.ld_out * es);
     L.dy = c.take((size_t)rows_out * L.ld_out * es);
-    if (L.skip_source) L.dy_skip = c.take((size_t)rows_out * L.ld_out * es);
+    if (L.skip_source && !L.skip_fused) L.dy_skip = c.take((size_t)rows_out * L.ld_out * es);
     if (L.kind == DYNB_LAYER_BN) {
       L.bn_mean = (float*)c.take((size_t)max_workers * L.n_out * 4);
       L.bn_rstd = (float*)c.take((size_t)max_workers * L.n_out * 4);
@@ -272,6 +278,16 @@ extern "C" int dynb_model_create(const dynb_model_desc* d, dynb_model** out) {
   const Layer& Z = m->layers.back();
   if (Z.kind != DYNB_LAYER_DENSE || Z.n_out != d->n_classes || Z.hw_out != 1)
     return bad_model(m, DYNB_ERR_BADARG, "the last layer must be dense with n_classes outputs", d->n_layers - 1);
+  // what the layer graph allows to be fused (see Layer)
+  for (size_t l = 0; l + 1 < m->layers.size(); ++l) {
+    Layer& L = m->layers[l];
+    const Layer& Up = m->layers[l + 1];
+    if (L.skip_source && (Up.kind == DYNB_LAYER_DENSE || Up.kind == DYNB_LAYER_CONV3X3) &&
+        (int)l + 1 > m->first_param_layer)
+      L.skip_fused = true;
+    if (L.kind == DYNB_LAYER_BN && !L.relu && !L.skip_source && Up.kind == DYNB_LAYER_ADD)
+      L.add_fused = true;
+  }
   m->P = off;
   m->P_pad = round_up(off, 256);
   *out = m;
@@ -392,6 +408,11 @@ int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const 
   }
   auto in_act = [&](size_t l) -> const void* { return l == 0 ? m->act0 : m->layers[l - 1].out; };
 
+  // dyv[l]: where layer l's gradient is read from -- its own buffer, or (no copy) the buffer of
+  // the residual addition above it.  skip_grad[l]: the gradient that reaches a fused skip source
+  // over the residual branch; the input-gradient kernel of the layer above adds it.
+  std::vector<const void*> dyv(nL), skip_grad(nL, nullptr);
+  for (size_t l = 0; l < nL; ++l) dyv[l] = m->layers[l].dy;
   if (B > 0) {
     // ---- forward ----
     rc = launch_pack_rows(dt, x, B * m->in_h * m->in_w, m->in_c, m->act0, m->ld0, stream);
@@ -406,13 +427,22 @@ int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const 
         continue;
       }
       if (L.kind == DYNB_LAYER_BN) {
-        rc = launch_bn_forward(in_act(l), L.ld_in, L.n_out, m->params + L.w_off, m->params + L.b_off,
-                               L.eps, L.relu, L.bn_mean, L.bn_rstd, m->row_scratch, L.out, L.ld_out,
-                               segs[l], stream);
+        if (L.add_fused) {   // normalisation and the addition behind it in one pass
+          const Layer& Add = m->layers[l + 1];
+          const Layer& Src = m->layers[Add.skip_from];
+          rc = launch_bn_forward(in_act(l), L.ld_in, L.n_out, m->params + L.w_off, m->params + L.b_off,
+                                 L.eps, L.relu, L.bn_mean, L.bn_rstd, m->row_scratch, Src.out,
+                                 Src.ld_out, Add.relu, Add.out, Add.ld_out, segs[l], stream);
+        } else {
+          rc = launch_bn_forward(in_act(l), L.ld_in, L.n_out, m->params + L.w_off, m->params + L.b_off,
+                                 L.eps, L.relu, L.bn_mean, L.bn_rstd, m->row_scratch, nullptr, 0, 0,
+                                 L.out, L.ld_out, segs[l], stream);
+        }
         if (rc) return rc;
         continue;
       }
       if (L.kind == DYNB_LAYER_ADD) {
+        if (m->layers[l - 1].add_fused) continue;
         const Layer& Src = m->layers[L.skip_from];
         rc = launch_add_forward(in_act(l), L.ld_in, Src.out, Src.ld_out, L.ld_out, rows_out, L.relu,
                                 L.out, L.ld_out, stream);
@@ -456,22 +486,22 @@ int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const 
     // ---- backward: gradient wrt every layer's output, masked by that layer's ReLU ----
     for (size_t l = nL; l-- > 0;) {
       Layer& L = m->layers[l];
-      if (L.skip_source) {   // the gradient that arrived over the residual branch joins in
+      if (L.skip_source && !L.skip_fused) {   // the gradient of the residual branch joins in
         rc = launch_grad_route(L.dy_skip, L.ld_out, nullptr, 0, L.ld_out, (int64_t)B * L.hw_out, 0, 1,
                                L.dy, L.ld_out, stream);
         if (rc) return rc;
       }
       if (L.kind == DYNB_LAYER_DENSE) {
-        rc = launch_transpose(dt, L.dy, L.ld_out, L.n_out, L.dyT, L.capT, segs[l], stream);
+        rc = launch_transpose(dt, dyv[l], L.ld_out, L.n_out, L.dyT, L.capT, segs[l], stream);
         if (rc) return rc;
       }
       const bool below = (int)l > m->first_param_layer;   // does anything below need a gradient?
       if (L.kind == DYNB_LAYER_BN) {
         Layer* Lq = l > 0 ? &m->layers[l - 1] : nullptr;
-        rc = launch_bn_backward(L.dy, L.ld_out, in_act(l), L.ld_in, L.n_out, m->params + L.w_off,
+        rc = launch_bn_backward(dyv[l], L.ld_out, in_act(l), L.ld_in, L.n_out, m->params + L.w_off,
                                 L.bn_mean, L.bn_rstd, m->row_scratch, grads + L.w_off,
-                                grads + L.b_off, m->P_pad, below, Lq ? Lq->relu : 0, Lq ? Lq->dy : nullptr, Lq ? Lq->ld_out : 0,
-                                segs[l], stream);
+                                grads + L.b_off, m->P_pad, below, Lq ? Lq->relu : 0,
+                                Lq ? Lq->dy : nullptr, Lq ? Lq->ld_out : 0, segs[l], stream);
         if (rc) return rc;
         continue;
       }
@@ -480,16 +510,24 @@ int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const 
       const int rows_in = B * L.hw_in;
       if (L.kind == DYNB_LAYER_ADD) {                 // the same gradient goes down both branches
         Layer& Src = m->layers[L.skip_from];
-        rc = launch_grad_route(L.dy, L.ld_out, Lp.out, Lp.ld_out, L.ld_out, rows_in, Lp.relu, 0, Lp.dy,
-                               Lp.ld_out, stream);
-        if (rc) return rc;
-        rc = launch_grad_route(L.dy, L.ld_out, Src.out, Src.ld_out, L.ld_out, rows_in, Src.relu, 0,
-                               Src.dy_skip, Src.ld_out, stream);
-        if (rc) return rc;
+        if (!Lp.relu && !Lp.skip_source) {
+          dyv[l - 1] = dyv[l];                        // unchanged: read it where it is
+        } else {
+          rc = launch_grad_route(dyv[l], L.ld_out, Lp.out, Lp.ld_out, L.ld_out, rows_in, Lp.relu, 0,
+                                 Lp.dy, Lp.ld_out, stream);
+          if (rc) return rc;
+        }
+        if (Src.skip_fused) {
+          skip_grad[L.skip_from] = dyv[l];
+        } else {
+          rc = launch_grad_route(dyv[l], L.ld_out, Src.out, Src.ld_out, L.ld_out, rows_in, Src.relu, 0,
+                                 Src.dy_skip, Src.ld_out, stream);
+          if (rc) return rc;
+        }
         continue;
       }
       if (L.kind == DYNB_LAYER_GAP) {
-        rc = launch_gap_backward(L.dy, L.ld_out, Lp.out, Lp.ld_out, L.hw_in, L.n_in, B, Lp.relu,
+        rc = launch_gap_backward(dyv[l], L.ld_out, Lp.out, Lp.ld_out, L.hw_in, L.n_in, B, Lp.relu,
                                  Lp.dy, Lp.ld_out, stream);
         if (rc) return rc;
         continue;
@@ -500,14 +538,15 @@ int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const 
       g.N = L.n_in;
       g.C = Lp.dy; g.ldc = Lp.ld_out;
       if (Lp.relu) { g.mask = Lp.out; g.ldmask = Lp.ld_out; }
+      if (Lp.skip_source && Lp.skip_fused) { g.addend = skip_grad[l - 1]; g.ldadd = Lp.ld_out; }
       if (L.kind == DYNB_LAYER_DENSE) {
-        g.A = L.dy; g.lda = L.ld_out;
+        g.A = dyv[l]; g.lda = L.ld_out;
         g.B = L.Wn; g.ldb = L.ld_out;
         g.K = (int)L.ld_out;
         g.alg_flops = 2.0 * rows_in * L.n_in * L.n_out;
         g.alg_bytes = ((double)rows_in * (L.n_in + L.n_out) + (double)L.n_in * L.n_out) * es;
       } else {
-        g.A = L.dy; g.lda = L.ld_out;
+        g.A = dyv[l]; g.lda = L.ld_out;
         g.B = L.Wn; g.ldb = L.kd;
         g.K = L.kd;
         g.conv = 2; g.src_h = L.h_out; g.src_w = L.w_out; g.row_h = L.h_in; g.row_w = L.w_in;
@@ -556,7 +595,7 @@ int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const 
     }
     if (!L.has_params) continue;
     if (L.kind == DYNB_LAYER_CONV3X3) {
-      rc = launch_conv_wgrad(in_act(l), L.ld_in, L.n_in, L.h_in, L.w_in, L.dy, L.ld_out, L.n_out,
+      rc = launch_conv_wgrad(in_act(l), L.ld_in, L.n_in, L.h_in, L.w_in, dyv[l], L.ld_out, L.n_out,
                              L.h_out, L.w_out, L.stride, L.conv_chunk, m->partial, m->partial_floats,
                              grads + L.w_off, grads + L.b_off, m->P_pad, segs[l],
                              2.0 * B * L.hw_out * L.wg_rows * L.n_out,
