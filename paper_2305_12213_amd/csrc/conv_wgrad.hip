@@ -18,6 +18,9 @@
 // "tap" whose input operand is all ones.
 #include <hip/hip_runtime.h>
 
+#include <climits>
+#include <mutex>
+
 #include "dynb_internal.h"
 
 namespace dynb {
@@ -69,10 +72,13 @@ __device__ inline void chunk_span(const Segs& s, const RowChunks& ch, int chunk,
 }
 
 struct ConvWgradArgs {
-  const bf16* in; int64_t ldi;       // [samples * H * W][ldi]
-  const bf16* dy; int64_t ldd;       // [samples * Ho * Wo][ldd]
+  const bf16* in; int ldi;           // [samples * H * W][ldi]
+  const bf16* dy; int ldd;           // [samples * Ho * Wo][ldd]
   int H, W, Ho, Wo, stride;
   float* partial;                    // [chunk][cin block][cout block][TILE_FLOATS]
+  const void* zeros;                 // 16 bytes of zeros in device memory (address of g_zeros: a
+                                     // kernel argument stays in scalar registers, the symbol's
+                                     // address would be re-loaded around every copy)
 };
 
 __global__ __launch_bounds__(256) void conv_wgrad_chunk_kernel(ConvWgradArgs p, Segs segs, RowChunks ch) {
@@ -107,17 +113,17 @@ __global__ __launch_bounds__(256) void conv_wgrad_chunk_kernel(ConvWgradArgs p, 
     const int sy = oy * p.stride + kh - 1;
     const bool row_ok = valid && sy >= 0 && sy < p.H;
     const int csy = sy < 0 ? 0 : (sy >= p.H ? p.H - 1 : sy);
-    const int64_t line = valid ? (int64_t)(img * p.H + csy) * p.W : 0;
+    const int line = valid ? (img * p.H + csy) * p.W : 0;      // (pixel indices fit 31 bits)
 #pragma unroll
     for (int kw = 0; kw < 3; ++kw) {
       const int sx = ox * p.stride + kw - 1;
       const int csx = sx < 0 ? 0 : (sx >= p.W ? p.W - 1 : sx);
-      const bf16* a = in_c + (line + csx) * p.ldi;
-      const void* src = (row_ok && sx >= 0 && sx < p.W) ? (const void*)a : (const void*)g_zeros;
+      const bf16* a = in_c + (int64_t)(line + csx) * p.ldi;
+      const void* src = (row_ok && sx >= 0 && sx < p.W) ? (const void*)a : p.zeros;
       async_copy_1k(src, base + kw * TILE_BYTES);
     }
-    const bf16* d = dy_c + (valid ? (int64_t)row * p.ldd : 0);
-    const void* src = valid ? (const void*)d : (const void*)g_zeros;
+    const bf16* d = dy_c + (int64_t)(valid ? row : 0) * p.ldd;
+    const void* src = valid ? (const void*)d : p.zeros;
     async_copy_1k(src, base + 3 * TILE_BYTES);
   };
   auto next_block = [&]() {                      // this lane's pixel, 32 pixels on
@@ -248,6 +254,21 @@ __global__ __launch_bounds__(256) void conv_wgrad_reduce_kernel(const float* __r
     if (co + e < Cout) dst[e] = sum[e];
 }
 
+// address of g_zeros on the current device (looked up once per device)
+const void* zeros_on_device() {
+  static std::mutex mu;
+  static const void* known[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+  std::lock_guard<std::mutex> lk(mu);
+  if (!known[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_zeros)) != hipSuccess) return nullptr;
+    known[dev] = p;
+  }
+  return known[dev];
+}
+
 }  // namespace
 
 RowChunks make_row_chunks(const Segs& s, int rows) {
@@ -282,13 +303,18 @@ int launch_conv_wgrad(const void* in, int64_t ldi, int Cin, int H, int W, const 
   if (ldi % 64 || ldd % 64 || ldi < 64 * cibs || ldd < 64 * cobs || chunk_rows < 32 || chunk_rows % 32 ||
       (((uintptr_t)in | (uintptr_t)dy | (uintptr_t)scratch) & 15))
     return fail(DYNB_ERR_BADARG, "conv_wgrad: pitches must cover whole 64-channel blocks, 16-byte aligned");
+  if (ldi > INT_MAX || ldd > INT_MAX || (int64_t)s.off[s.K] * stride * stride > INT_MAX / 2)
+    return fail(DYNB_ERR_UNSUPPORTED, "conv_wgrad: tensor too large for 32-bit pixel indices");
+  const void* zeros = zeros_on_device();
+  if (!zeros) return fail(DYNB_ERR_HIP, "conv_wgrad: no address for the zero granule");
   const RowChunks ch = make_row_chunks(s, chunk_rows);
   const int nch = ch.first[s.K];
   if ((int64_t)nch * cibs * cobs * TILE_FLOATS > scratch_floats)
     return fail(DYNB_ERR_BADARG, "conv_wgrad: scratch area too small");
   Timed t(KC_GEMM_WGRAD, stream, flops, bytes);
   if (nch > 0) {
-    ConvWgradArgs a = {(const bf16*)in, ldi, (const bf16*)dy, ldd, H, W, Ho, Wo, stride, scratch};
+    ConvWgradArgs a = {(const bf16*)in, (int)ldi, (const bf16*)dy, (int)ldd, H, W, Ho, Wo, stride,
+                       scratch, zeros};
     hipLaunchKernelGGL(conv_wgrad_chunk_kernel, dim3(nch, cibs, cobs), dim3(256), 0,
                        (hipStream_t)stream, a, s, ch);
   }

@@ -259,10 +259,11 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
           sy = gy[u] * p.stride + kh - 1;
           sx = gx[u] * p.stride + kw - 1;
         } else {
-          const int ty = gy[u] + 1 - kh, tx = gx[u] + 1 - kw;
-          sy = ty / p.stride;
-          sx = tx / p.stride;
-          ok = ok && ty >= 0 && tx >= 0 && sy * p.stride == ty && sx * p.stride == tx;
+          // (stride is 1 or 2: a shift instead of a division in the hot loop)
+          const int ty = gy[u] + 1 - kh, tx = gx[u] + 1 - kw, sh = p.stride - 1;
+          sy = ty >> sh;
+          sx = tx >> sh;
+          ok = ok && ty >= 0 && tx >= 0 && (sy << sh) == ty && (sx << sh) == tx;
         }
         ok = ok && sy >= 0 && sy < p.src_h && sx >= 0 && sx < p.src_w;
         const int64_t pix = (int64_t)offA[u] + sy * p.src_w + sx;
@@ -757,7 +758,7 @@ int launch_gemm(int dtype, const GemmArgs& a, const Segs& s, void* stream) {
                                                                               : KC_GEMM_WGRAD;
   Timed t(cls, stream, a.alg_flops, a.alg_bytes);
   if (a.conv) {
-    if (dtype != DYNB_BF16 || a.mode == MODE_WGRAD || (a.cp & 7) || a.stride < 1)
+    if (dtype != DYNB_BF16 || a.mode == MODE_WGRAD || (a.cp & 7) || (a.stride != 1 && a.stride != 2))
       return fail(DYNB_ERR_UNSUPPORTED, "gemm: gathered operand needs bf16, forward/input-gradient mode");
     launch_bf16_gather(a, s, (hipStream_t)stream);
   } else if (dtype == DYNB_BF16 && a.agg) {
