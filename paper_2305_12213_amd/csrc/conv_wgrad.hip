@@ -219,34 +219,55 @@ __global__ __launch_bounds__(256) void conv_wgrad_chunk_kernel(ConvWgradArgs p, 
   }
 }
 
-// dW_k[tap][ci][co .. co+3] = the chunk results of worker k added in ascending chunk order; the
-// items behind the weights are the bias gradients db_k[co .. co+3] (slot 9, input channel 0).
-// Accumulator element v of lane l belongs to output channel 8*(v/4) + 4*(l/32) + v%4 and input
-// channel l%32 of the wave's corner.
+// dW_k[tap][ci][co .. co+3] = the chunk results of worker k added in a fixed order; the items
+// behind the weights are the bias gradients db_k[co .. co+3] (slot 9, input channel 0).
+// 256 threads = 32 items x 8 chunk-lanes: lane q adds chunks q, q+8, ... (four independent
+// partial sums, so that the loads overlap), then the lanes are added in ascending order.
+// Neighbouring threads take neighbouring input channels, which lie 16 bytes apart in a chunk
+// result.  Accumulator element v of lane l belongs to output channel 8*(v/4) + 4*(l/32) + v%4
+// and input channel l%32 of the wave's corner.
 __global__ __launch_bounds__(256) void conv_wgrad_reduce_kernel(const float* __restrict__ partial,
                                                                 int Cin, int Cout, int cibs, int cobs,
                                                                 float* __restrict__ dW,
                                                                 float* __restrict__ db,
                                                                 int64_t group_stride, RowChunks ch) {
+  __shared__ f32x4 red[8][32];
+  const int il = threadIdx.x & 31, q = threadIdx.x >> 5;
   const int k = blockIdx.y;
   const int quads = (Cout + 3) / 4;
-  const int64_t n_weight = (int64_t)9 * Cin * quads;
-  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;    // (tap, ci, quad of co) | quad
-  if (idx >= n_weight + quads) return;
+  const int64_t n_weight = (int64_t)9 * quads * Cin;
+  int64_t idx = (int64_t)blockIdx.x * 32 + il;   // ((tap, quad of co), ci) | quad
+  const bool live = idx < n_weight + quads;
+  if (!live) idx = 0;
   const bool bias = idx >= n_weight;
-  const int64_t w = bias ? 0 : idx;
-  const int quad = bias ? (int)(idx - n_weight) : (int)(w % quads);
-  const int ci = bias ? 0 : (int)((w / quads) % Cin);
-  const int slot = bias ? 9 : (int)(w / ((int64_t)quads * Cin));
+  const int ci = bias ? 0 : (int)(idx % Cin);
+  const int64_t tq = bias ? 0 : idx / Cin;
+  const int quad = bias ? (int)(idx - n_weight) : (int)(tq % quads);
+  const int slot = bias ? 9 : (int)(tq / quads);
   const int co = quad * 4;
   const int cib = ci >> 6, cob = co >> 6, cil = ci & 63, col = co & 63;
   const int wave = (cil >> 5) + 2 * (col >> 5);
   const int c32 = col & 31;
-  const int q = c32 >> 3, lane = (cil & 31) + 32 * ((c32 & 7) >> 2);
-  const int64_t within = ((int64_t)((wave * SLOTS + slot) * 4 + q) * 64 + lane) * 4;
-  f32x4 sum = {0.f, 0.f, 0.f, 0.f};
-  for (int c = ch.first[k]; c < ch.first[k + 1]; ++c)
-    sum += *(const f32x4*)&partial[((int64_t)(c * cibs + cib) * cobs + cob) * TILE_FLOATS + within];
+  const int lane = (cil & 31) + 32 * ((c32 & 7) >> 2);
+  const int64_t within = ((int64_t)((wave * SLOTS + slot) * 4 + (c32 >> 3)) * 64 + lane) * 4;
+  const int64_t stride = (int64_t)cibs * cobs * TILE_FLOATS;
+  const float* src = partial + ((int64_t)cib * cobs + cob) * TILE_FLOATS + within;
+  const int last = ch.first[k + 1];
+  f32x4 a0 = {0.f, 0.f, 0.f, 0.f}, a1 = a0, a2 = a0, a3 = a0;
+  int c = ch.first[k] + q;
+  for (; c + 24 < last; c += 32) {
+    a0 += *(const f32x4*)(src + c * stride);
+    a1 += *(const f32x4*)(src + (c + 8) * stride);
+    a2 += *(const f32x4*)(src + (c + 16) * stride);
+    a3 += *(const f32x4*)(src + (c + 24) * stride);
+  }
+  for (; c < last; c += 8) a0 += *(const f32x4*)(src + c * stride);
+  red[q][il] = (a0 + a1) + (a2 + a3);
+  __syncthreads();
+  if (q != 0 || !live) return;
+  f32x4 sum = red[0][il];
+#pragma unroll
+  for (int i = 1; i < 8; ++i) sum += red[i][il];
   float* dst = bias ? db + (int64_t)k * group_stride + co
                     : dW + (int64_t)k * group_stride + ((int64_t)slot * Cin + ci) * Cout + co;
 #pragma unroll
@@ -319,7 +340,7 @@ int launch_conv_wgrad(const void* in, int64_t ldi, int Cin, int H, int W, const 
                        (hipStream_t)stream, a, s, ch);
   }
   const int64_t items = (int64_t)(9 * Cin + 1) * ((Cout + 3) / 4);
-  hipLaunchKernelGGL(conv_wgrad_reduce_kernel, dim3((unsigned)((items + 255) / 256), s.K), dim3(256), 0,
+  hipLaunchKernelGGL(conv_wgrad_reduce_kernel, dim3((unsigned)((items + 31) / 32), s.K), dim3(256), 0,
                      (hipStream_t)stream, scratch, Cin, Cout, cibs, cobs, dW, db, group_stride, ch);
   return hipGetLastError() == hipSuccess ? DYNB_OK : fail(DYNB_ERR_HIP, "conv_wgrad: launch failed");
 }

@@ -72,36 +72,52 @@ __global__ __launch_bounds__(256) void bn_chunk_stats_kernel(const bf16* __restr
   }
 }
 
-// (n, mu, m2) <- (n, mu, m2) merged with (nb, mb, m2b): the pairwise update of Chan et al.
-__device__ inline void merge_moments(float& n, float& mu, float& m2, float nb, float mb, float m2b) {
-  if (nb <= 0.f) return;
-  const float tot = n + nb, d = mb - mu;
-  mu += d * (nb / tot);
-  m2 += m2b + d * d * (n * nb / tot);
-  n = tot;
+// Sum over the chunks of one worker, for 64 channels at a time: 1024 threads = 64 channels x 16
+// chunk-lanes; lane q adds the terms of chunks q, q+16, ... (four independent partial sums, so
+// that the loads overlap), the 16 lanes are then added in ascending order.  term(j) = value of
+// chunk j for this thread's channel.  Every thread of the channel gets the total.
+template <typename F>
+__device__ inline float sum_over_chunks(int nc, int q, int cl, float (*red)[64], F term) {
+  float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+  int j = q;
+  for (; j + 48 < nc; j += 64) {
+    a0 += term(j); a1 += term(j + 16); a2 += term(j + 32); a3 += term(j + 48);
+  }
+  for (; j < nc; j += 16) a0 += term(j);
+  __syncthreads();
+  red[q][cl] = (a0 + a1) + (a2 + a3);
+  __syncthreads();
+  float t = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) t += red[i][cl];
+  return t;
 }
 
-// mean[k][c], rstd[k][c] from the chunk moments of worker k, merged in a fixed order
-// (4 lanes per channel take every 4th chunk, then the lanes are merged 0..3).
-__global__ __launch_bounds__(256) void bn_merge_stats_kernel(const float* __restrict__ pmean,
-                                                             const float* __restrict__ pm2, int C,
-                                                             float eps, float* __restrict__ mean,
-                                                             float* __restrict__ rstd, Segs s, Chunks ch) {
-  __shared__ float sn[4][64], sm[4][64], sq[4][64];
+// mean[k][c], rstd[k][c] from the chunk moments of worker k: the mean is the weighted sum of
+// the chunk means, the sum of squares follows from the parallel-axis relation
+//   M2 = sum_j (M2_j + n_j (mean_j - mean)^2)
+// -- two plain sums in a fixed order.
+__global__ __launch_bounds__(1024) void bn_merge_stats_kernel(const float* __restrict__ pmean,
+                                                              const float* __restrict__ pm2, int C,
+                                                              float eps, float* __restrict__ mean,
+                                                              float* __restrict__ rstd, Segs s, Chunks ch) {
+  __shared__ float red[16][64];
   const int cl = threadIdx.x & 63, q = threadIdx.x >> 6;
   const int c = blockIdx.x * 64 + cl, k = blockIdx.y;
   const int rows = s.off[k + 1] - s.off[k];
   if (rows <= 0) return;                      // (uniform over the workgroup)
   const int first = ch.first[k], nc = ch.first[k + 1] - first;
-  float n = 0.f, mu = 0.f, m2 = 0.f;
-  if (c < C)
-    for (int j = q; j < nc; j += 4)
-      merge_moments(n, mu, m2, (float)min(CHUNK_ROWS, rows - j * CHUNK_ROWS),
-                    pmean[(int64_t)(first + j) * C + c], pm2[(int64_t)(first + j) * C + c]);
-  sn[q][cl] = n; sm[q][cl] = mu; sq[q][cl] = m2;
-  __syncthreads();
+  const int cc = c < C ? c : C - 1;           // lanes past the last channel repeat it, unused
+  const float n = (float)rows;
+  auto rows_of = [&](int j) { return (float)min(CHUNK_ROWS, rows - j * CHUNK_ROWS); };
+  const float mu = sum_over_chunks(nc, q, cl, red, [&](int j) {
+                     return rows_of(j) * pmean[(int64_t)(first + j) * C + cc];
+                   }) / n;
+  const float m2 = sum_over_chunks(nc, q, cl, red, [&](int j) {
+    const float d = pmean[(int64_t)(first + j) * C + cc] - mu;
+    return pm2[(int64_t)(first + j) * C + cc] + rows_of(j) * d * d;
+  });
   if (q == 0 && c < C) {
-    for (int j = 1; j < 4; ++j) merge_moments(n, mu, m2, sn[j][cl], sm[j][cl], sq[j][cl]);
     mean[(int64_t)k * C + c] = mu;
     rstd[(int64_t)k * C + c] = 1.f / sqrtf(m2 / n + eps);
   }
@@ -208,26 +224,21 @@ __global__ __launch_bounds__(256) void bn_chunk_param_grad_kernel(
 
 // dgamma[k][c], dbeta[k][c] = the chunk sums of worker k added in a fixed order, written into
 // worker k's gradient vector; a worker without rows gets zeros.
-__global__ __launch_bounds__(256) void bn_merge_param_grad_kernel(const float* __restrict__ pdg,
-                                                                  const float* __restrict__ pdb, int C,
-                                                                  float* __restrict__ dgamma,
-                                                                  float* __restrict__ dbeta,
-                                                                  int64_t group_stride, Chunks ch) {
-  __shared__ float sg[4][64], sb[4][64];
+__global__ __launch_bounds__(1024) void bn_merge_param_grad_kernel(const float* __restrict__ pdg,
+                                                                   const float* __restrict__ pdb, int C,
+                                                                   float* __restrict__ dgamma,
+                                                                   float* __restrict__ dbeta,
+                                                                   int64_t group_stride, Chunks ch) {
+  __shared__ float red[16][64];
   const int cl = threadIdx.x & 63, q = threadIdx.x >> 6;
   const int c = blockIdx.x * 64 + cl, k = blockIdx.y;
   const int first = ch.first[k], nc = ch.first[k + 1] - first;
-  float g = 0.f, b = 0.f;
-  if (c < C)
-    for (int j = q; j < nc; j += 4) {
-      g += pdg[(int64_t)(first + j) * C + c];
-      b += pdb[(int64_t)(first + j) * C + c];
-    }
-  sg[q][cl] = g; sb[q][cl] = b;
-  __syncthreads();
+  const int cc = c < C ? c : C - 1;
+  const float g = sum_over_chunks(nc, q, cl, red, [&](int j) { return pdg[(int64_t)(first + j) * C + cc]; });
+  const float b = sum_over_chunks(nc, q, cl, red, [&](int j) { return pdb[(int64_t)(first + j) * C + cc]; });
   if (q == 0 && c < C) {
-    dgamma[(int64_t)k * group_stride + c] = ((sg[0][cl] + sg[1][cl]) + sg[2][cl]) + sg[3][cl];
-    dbeta[(int64_t)k * group_stride + c] = ((sb[0][cl] + sb[1][cl]) + sb[2][cl]) + sb[3][cl];
+    dgamma[(int64_t)k * group_stride + c] = g;
+    dbeta[(int64_t)k * group_stride + c] = b;
   }
 }
 
@@ -354,7 +365,7 @@ int launch_bn_forward(const void* x, int64_t ldx, int C, const float* gamma, con
   Timed t(KC_NORM, stream, 0, (double)rows * C * (skip ? 8 : 6));     // x twice, y once (+ skip)
   hipLaunchKernelGGL(bn_chunk_stats_kernel, dim3(nch, cb), dim3(256), 0, (hipStream_t)stream,
                      (const bf16*)x, ldx, C, pmean, pm2, s, ch);
-  hipLaunchKernelGGL(bn_merge_stats_kernel, dim3(cb, s.K), dim3(256), 0, (hipStream_t)stream, pmean,
+  hipLaunchKernelGGL(bn_merge_stats_kernel, dim3(cb, s.K), dim3(1024), 0, (hipStream_t)stream, pmean,
                      pm2, C, eps, mean, rstd, s, ch);
   hipLaunchKernelGGL(bn_apply_kernel, dim3(nch, (unsigned)(ldy / 64)), dim3(256), 0,
                      (hipStream_t)stream, (const bf16*)x, ldx, C, gamma, beta, mean, rstd, relu,
@@ -376,7 +387,7 @@ int launch_bn_backward(const void* dy, int64_t ldd, const void* x, int64_t ldx, 
   if (nch > 0)
     hipLaunchKernelGGL(bn_chunk_param_grad_kernel, dim3(nch, cb), dim3(256), 0, (hipStream_t)stream,
                        (const bf16*)dy, ldd, (const bf16*)x, ldx, C, mean, rstd, pdg, pdb, s, ch);
-  hipLaunchKernelGGL(bn_merge_param_grad_kernel, dim3(cb, s.K), dim3(256), 0, (hipStream_t)stream, pdg,
+  hipLaunchKernelGGL(bn_merge_param_grad_kernel, dim3(cb, s.K), dim3(1024), 0, (hipStream_t)stream, pdg,
                      pdb, C, dgamma, dbeta, group_stride, ch);
   if (need_dx && nch > 0)
     hipLaunchKernelGGL(bn_input_grad_kernel, dim3(nch, (unsigned)(ldo / 64)), dim3(256), 0,
