@@ -100,6 +100,10 @@ struct GemmArgs {
   // (x + 1 - kw)/stride) when both divisions are exact.  Out-of-range taps read zero.
   // A points at the source tensor [n * src_h * src_w][lda]; cp is a multiple of 8.
   int conv, src_h, src_w, row_h, row_w, stride, cp;
+  // set by launch_gemm: log2(cp) when the cheap addressing applies (cp a power of two >= 32,
+  // so that a 32-deep stage lies within one tap; the source pixel of a tap is the row's own
+  // pixel plus an offset that is the same for all rows; source tensor below 2 GiB), else -1
+  int gather_log2cp;
   double alg_flops, alg_bytes;         // algorithmic work of the launch (timing aid only)
   // WGRAD, bf16 kernel: split every worker's reduction into `split` chunks of `chunk` columns
   // (a multiple of 64).  Chunk c of worker g writes its tile to partial + (g*split + c) *
@@ -207,8 +211,9 @@ RowChunks make_row_chunks(const Segs& s, int rows);
 
 // Per-worker weight gradient of a 3x3 convolution straight from the row-major activations
 // (bf16 in: [samples*H*W][ldi], dy: [samples*Ho*Wo][ldd]; dW[k * group_stride + (tap*Cin +
-// ci)*Cout + co] and the bias gradient db[k * group_stride + co], fp32).  chunk_rows = conv_wgrad_chunk_rows(largest row count of the model's
-// plan); scratch: conv_wgrad_scratch_floats() floats.
+// ci)*Cout + co] and the bias gradient db[k * group_stride + co], fp32).  chunk_rows =
+// conv_wgrad_chunk_rows(largest row count of the model's plan); scratch:
+// conv_wgrad_scratch_floats() floats.
 int conv_wgrad_chunk_rows(int64_t max_rows);
 int64_t conv_wgrad_scratch_floats(int64_t max_rows, int max_workers, int Cin, int Cout);
 int launch_conv_wgrad(const void* in, int64_t ldi, int Cin, int H, int W, const void* dy, int64_t ldd,

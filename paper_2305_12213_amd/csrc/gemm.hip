@@ -209,6 +209,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
   const char* Bb = (const char*)p.B;
   uint32_t offA[LA], offB[LB];
   int gy[GATHER ? LA : 1], gx[GATHER ? LA : 1];   // gather: the row's pixel coordinates
+  // gather, cheap addressing: byte offset of (the row's own source pixel, this lane's granule)
+  // and one validity bit per tap; a stage then adds one wave-uniform offset per tap
+  uint32_t goff[GATHER ? LA : 1], gok[GATHER ? LA : 1];
+  const bool gfast = GATHER && p.gather_log2cp >= 0;
 #pragma unroll
   for (int u = 0; u < LA; ++u) {
     int i = i0 + (wave + NW * u) * 16 + lrow;
@@ -219,6 +223,15 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
       gy[u] = rem / p.row_w;
       gx[u] = rem - gy[u] * p.row_w;
       offA[u] = (uint32_t)(n * p.src_h * p.src_w);   // first source pixel of the sample
+      const int fwd = p.conv == 1;
+      const int py = fwd ? gy[u] * p.stride : gy[u], px = fwd ? gx[u] * p.stride : gx[u];
+      goff[u] = (uint32_t)(((int64_t)(offA[u] + py * p.src_w + px) * p.lda + lgran * 8) * 2);
+      gok[u] = 0;
+      for (int tap = 0; tap < 9; ++tap) {           // (forward: +tap offset, input gradient: -)
+        const int dy_ = tap / 3 - 1, dx_ = tap % 3 - 1;
+        const int sy = fwd ? py + dy_ : py - dy_, sx = fwd ? px + dx_ : px - dx_;
+        if (sy >= 0 && sy < p.src_h && sx >= 0 && sx < p.src_w) gok[u] |= 1u << tap;
+      }
     } else {
       offA[u] = (uint32_t)(((int64_t)i * p.lda + lgran * 8) * 2);
     }
@@ -241,7 +254,19 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
     }
     int kh = 0, kw = 0, ch = 0;
     bool tap_ok = false;
-    if (GATHER) {
+    if (gfast) {
+      // the whole stage lies in tap k0 >> log2(cp): one signed byte offset for every row
+      const int tap = k0 >> p.gather_log2cp, kc = k0 & (p.cp - 1);
+      const int th = (tap * 11) >> 5, tw = tap - 3 * th;          // tap / 3, tap % 3 (tap <= 9)
+      const int dpix = (th - 1) * p.src_w + (tw - 1);
+      const uint32_t dbyte = (uint32_t)(((p.conv == 1 ? dpix : -dpix) * (int)p.lda + kc) * 2);
+#pragma unroll
+      for (int u = 0; u < LA; ++u) {
+        const void* src = (gok[u] >> tap) & 1u ? (const void*)(Ab + (uint32_t)(goff[u] + dbyte))
+                                               : (const void*)g_zero_granule;
+        async_copy_1k(src, ldsA + (uint32_t)((buf * BM * GPR + (wave + NW * u) * 64) * 16));
+      }
+    } else if (GATHER) {
       const int k = k0 + lgran * 8;
       const int tap = k / p.cp;
       ch = k - tap * p.cp;
@@ -251,6 +276,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
     }
 #pragma unroll
     for (int u = 0; u < LA; ++u) {
+      if (gfast) break;                              // (copied above)
       const void* src;
       if (GATHER) {
         int sy, sx;
@@ -713,7 +739,14 @@ void launch_bf16_gather_as(GemmArgs a, const Segs& s, hipStream_t st) {
     hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, MODE_DGRAD, true, S>), grid, block, 0, st, a, s);
 }
 
-void launch_bf16_gather(const GemmArgs& a, const Segs& s, hipStream_t st) {
+void launch_bf16_gather(GemmArgs a, const Segs& s, hipStream_t st) {
+  a.gather_log2cp = -1;
+  const int64_t src_bytes = ((int64_t)((a.M + a.row_h * a.row_w - 1) / (a.row_h * a.row_w)) * a.src_h *
+                             a.src_w + 1) * a.lda * 2;
+  if (a.cp >= 32 && (a.cp & (a.cp - 1)) == 0 && !(a.conv == 2 && a.stride != 1) &&
+      src_bytes < ((int64_t)1 << 31))
+    for (int l = 5; l < 31; ++l)
+      if ((1 << l) == a.cp) a.gather_log2cp = l;
   if (a.N <= 64)
     launch_bf16_gather_as<256, 64, 4, 1, 4>(a, s, st);
   else
