@@ -96,6 +96,21 @@ def test_cnn_odd_image_size_and_wide_channels():
     check_worker_gradients(spec, params, x, y, [5, 6], label="cnn odd")
 
 
+@pytest.mark.parametrize("channels", [(72, 136, 40), (128, 64, 32)])
+def test_cnn_channel_blocks_and_row_chunks(channels):
+    # more than 64 input and output channels (several 64-channel blocks, the last one ragged),
+    # channel counts that are and are not powers of two, a stride-2 layer, and workers whose
+    # pixel rows span several chunks of the weight-gradient reduction with a ragged last chunk
+    c1, c2, c3 = channels
+    spec = {"dtype": "bf16", "input": (8, 8, 3), "classes": 5,
+            "layers": [synth.conv3x3(3, c1, 1), synth.conv3x3(c1, c2, 1), synth.conv3x3(c2, c3, 2),
+                       synth.gap(), synth.dense(c3, 5, relu=False)]}
+    params = synth.init_params(spec, "he", 51)
+    b = [9, 1, 0, 5]
+    x, y = synth.make_batch(spec, "normal", sum(b), 52, 0)
+    check_worker_gradients(spec, params, x, y, b, label="cnn blocks %s" % (channels,))
+
+
 def test_sixty_four_workers():
     # the largest worker count the interface takes, most workers tiny, some idle
     for dtype in ("f32", "bf16"):
