@@ -94,7 +94,10 @@ __global__ __launch_bounds__(256) void transpose_kernel(const T* __restrict__ in
                                                         Segs s) {
   constexpr int G = 16 / sizeof(T);          // elements per 16-byte granule
   constexpr int GC = 64 / G;                 // granules per tile row
-  __shared__ T tile[64][64 + 2 * G];
+  // row pitch of 33 (bf16) / 65 (fp32) dwords: the turned reads below walk down a column, and
+  // rows that are 8 apart must not fall into the same LDS bank
+  constexpr int PITCH = 64 + 4 / sizeof(T);
+  __shared__ T tile[64][PITCH];
   const int p0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
   const int P = s.poff[s.K];
   typedef T vecT __attribute__((ext_vector_type(G)));
