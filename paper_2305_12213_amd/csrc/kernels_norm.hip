@@ -362,7 +362,8 @@ int launch_bn_forward(const void* x, int64_t ldx, int C, const float* gamma, con
   const int nch = ch.first[s.K], cb = (C + 63) / 64;
   float* pmean = scratch;
   float* pm2 = scratch + (int64_t)nch * C;
-  Timed t(KC_NORM, stream, 0, (double)rows * C * (skip ? 8 : 6));     // x twice, y once (+ skip)
+  // algorithmic bytes: x read and y written once (+ the skip tensor); the statistics pass reads x again
+  Timed t(KC_NORM, stream, 0, (double)rows * C * (skip ? 6 : 4));
   hipLaunchKernelGGL(bn_chunk_stats_kernel, dim3(nch, cb), dim3(256), 0, (hipStream_t)stream,
                      (const bf16*)x, ldx, C, pmean, pm2, s, ch);
   hipLaunchKernelGGL(bn_merge_stats_kernel, dim3(cb, s.K), dim3(1024), 0, (hipStream_t)stream, pmean,
@@ -383,7 +384,8 @@ int launch_bn_backward(const void* dy, int64_t ldd, const void* x, int64_t ldx, 
   const int nch = ch.first[s.K], cb = (C + 63) / 64;
   float* pdg = scratch;
   float* pdb = scratch + (int64_t)nch * C;
-  Timed t(KC_NORM, stream, 0, (double)rows * C * (need_dx ? 10 : 4));   // dy, x twice; dx once
+  // algorithmic bytes: dy and x read once, dx written once (the kernels read dy and x twice)
+  Timed t(KC_NORM, stream, 0, (double)rows * C * (need_dx ? 6 : 4));
   if (nch > 0)
     hipLaunchKernelGGL(bn_chunk_param_grad_kernel, dim3(nch, cb), dim3(256), 0, (hipStream_t)stream,
                        (const bf16*)dy, ldd, (const bf16*)x, ldx, C, mean, rstd, pdg, pdb, s, ch);
