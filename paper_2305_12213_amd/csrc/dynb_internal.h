@@ -201,6 +201,11 @@ int launch_gap_backward(const void* dpooled, int64_t ldp, const void* act, int64
 int launch_conv_weight_cast(const float* W, int Cin, int Cout, int cin_p, int cout_p, void* Wf,
                             int kf, void* Wd, int kd, void* stream);
 
+// Forward / input gradient of a 3x3 convolution from one halo tile in LDS (conv_direct.hip):
+// takes the same description as the gathered-operand GEMM where conv_direct_applies() says so.
+bool conv_direct_applies(int dtype, const GemmArgs& a);
+int launch_conv_direct(const GemmArgs& a, void* stream);
+
 // The rows of every worker cut into chunks of `rows` rows: first[k] = index of worker k's first
 // chunk, first[K] = number of chunks (chunk c of worker k starts at off[k] + (c - first[k]) * rows).
 struct RowChunks {

@@ -793,6 +793,7 @@ int launch_gemm(int dtype, const GemmArgs& a, const Segs& s, void* stream) {
   if (a.conv) {
     if (dtype != DYNB_BF16 || a.mode == MODE_WGRAD || (a.cp & 7) || (a.stride != 1 && a.stride != 2))
       return fail(DYNB_ERR_UNSUPPORTED, "gemm: gathered operand needs bf16, forward/input-gradient mode");
+    if (conv_direct_applies(dtype, a)) return launch_conv_direct(a, stream);
     launch_bf16_gather(a, s, (hipStream_t)stream);
   } else if (dtype == DYNB_BF16 && a.agg) {
     launch_bf16_wgrad_agg(a, s, (hipStream_t)stream);

@@ -111,6 +111,21 @@ def test_cnn_channel_blocks_and_row_chunks(channels):
     check_worker_gradients(spec, params, x, y, b, label="cnn blocks %s" % (channels,))
 
 
+def test_cnn_on_32_wide_images_several_channel_blocks():
+    # 32 x 32 images select the halo-tile convolution kernel for forward and input gradient
+    # (stride 1, whole 64-channel blocks: 64 and 128 channels per tap), the stem (3 channels) and
+    # the strided layer stay on the gathered-operand kernel
+    spec = {"dtype": "bf16", "input": (32, 32, 3), "classes": 5,
+            "layers": [synth.conv3x3(3, 64, 1), synth.conv3x3(64, 128, 1), synth.conv3x3(128, 72, 1),
+                       synth.conv3x3(72, 16, 2), synth.gap(), synth.dense(16, 5, relu=False)]}
+    params = synth.init_params(spec, "he", 61)
+    rng = np.random.default_rng(3)
+    params = [(W, (rng.standard_normal(bb.shape) * 0.1).astype(np.float32)) for W, bb in params]
+    b = [2, 0, 1]
+    x, y = synth.make_batch(spec, "uniform", sum(b), 62, 0)
+    check_worker_gradients(spec, params, x, y, b, label="cnn 32 wide")
+
+
 def test_sixty_four_workers():
     # the largest worker count the interface takes, most workers tiny, some idle
     for dtype in ("f32", "bf16"):
