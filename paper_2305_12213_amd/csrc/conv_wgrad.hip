@@ -219,6 +219,152 @@ __global__ __launch_bounds__(256) void conv_wgrad_chunk_kernel(ConvWgradArgs p, 
   }
 }
 
+// The same for stride 1 on images exactly 32 pixels wide, where a 32-pixel block is one image
+// row: a stage is one output row, and instead of nine shifted copies it stages the three
+// input rows y-1, y, y+1 once, each with one pixel of (zero) border on both sides, and the three
+// horizontal taps read them at a pixel offset.  5.2 KB per row and stage move into LDS instead
+// of 12 KB, which is what bounds the general kernel.  Stage: 3 x 40 pixel slots (5 KB each),
+// the dy row (4 KB) and 1 KB of padding = 20 copies, 5 per wave; ring of 4 stages.
+constexpr int ROW_TILE = 40 * 128;               // an input row with border, 40 pixel slots
+constexpr int ROW_STAGE = 3 * ROW_TILE + TILE_BYTES + 1024;
+constexpr int ROW_PER = 5;                       // copies per wave and stage
+
+__device__ inline void wait_row_copies(int stages) {
+  switch (stages) {
+    case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+    case 1: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(ROW_PER) : "memory"); break;
+    default: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * ROW_PER) : "memory"); break;
+  }
+}
+
+__global__ __launch_bounds__(256) void conv_wgrad_rows_kernel(ConvWgradArgs p, Segs segs, RowChunks ch) {
+  __shared__ uint4 ring[S * ROW_STAGE / 16];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int chunk = blockIdx.x, cib = blockIdx.y, cob = blockIdx.z;
+  int k, r0, n;
+  chunk_span(segs, ch, chunk, k, r0, n);         // r0 and n are multiples of 32: whole image rows
+  const int T = n / 32;                          // stages = output rows
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)&ring[0];
+
+  // ---- global -> LDS.  Copy c = wave + 4u (u < 5) of a stage: c < 15: input row kh = c / 5,
+  // pixel slots [8o, 8o+8), o = c % 5 (slot hx holds source pixel x = hx - 1); 15 <= c < 19:
+  // pixels [8(c-15), +8) of the dy row; c = 19: padding.  This lane moves slot lane/8 of the
+  // eight, granule lane%8; halves of slots 2,3,6,7,... are swapped as in the kernel above.
+  const int gq = (lane & 7) ^ (((lane >> 4) & 1) << 2);
+  int64_t src_off[ROW_PER];                      // element offset relative to the stage's row, or -1
+  int src_kind[ROW_PER];                         // 0..2: input row kh, 3: dy, 4: zeros
+#pragma unroll
+  for (int u = 0; u < ROW_PER; ++u) {
+    const int c = wave + 4 * u;
+    src_kind[u] = 4;
+    src_off[u] = 0;
+    if (c < 15) {
+      const int x = 8 * (c % 5) + (lane >> 3) - 1;
+      if (x >= 0 && x < 32) {
+        src_kind[u] = c / 5;
+        src_off[u] = (int64_t)x * p.ldi + cib * 64 + gq * 8;
+      }
+    } else if (c < 19) {
+      src_kind[u] = 3;
+      src_off[u] = (int64_t)(8 * (c - 15) + (lane >> 3)) * p.ldd + cob * 64 + gq * 8;
+    }
+  }
+  int orow = r0 / 32;                            // output row (image * H + y) of the next stage to issue
+  auto issue = [&](int t) {
+    const uint32_t base = lds0 + (uint32_t)((t % S) * ROW_STAGE);
+    const int img = orow / p.H, oy = orow - img * p.H;
+#pragma unroll
+    for (int u = 0; u < ROW_PER; ++u) {
+      const int c = wave + 4 * u;
+      const void* src = p.zeros;
+      if (src_kind[u] < 3) {
+        const int sy = oy + src_kind[u] - 1;
+        const int csy = sy < 0 ? 0 : (sy >= p.H ? p.H - 1 : sy);
+        const bf16* a = p.in + (int64_t)(img * p.H + csy) * 32 * p.ldi + src_off[u];
+        if (sy >= 0 && sy < p.H) src = a;
+      } else if (src_kind[u] == 3) {
+        src = p.dy + (int64_t)orow * 32 * p.ldd + src_off[u];
+      }
+      const uint32_t dst = c < 15 ? (uint32_t)((c / 5) * ROW_TILE + (c % 5) * 1024)
+                                  : (uint32_t)(3 * ROW_TILE + (c - 15) * 1024);
+      async_copy_1k(src, base + dst);
+    }
+    ++orow;
+  };
+
+  // ---- LDS -> MFMA operands (see the kernel above); input rows are read at slot x + kw
+  const int wci = wave & 1, wco = wave >> 1;
+  const int g = lane >> 4, r = lane & 15;
+  const uint32_t fcol = (uint32_t)((16 * (g & 1) + 4 * (r & 3)) * 2);
+  uint32_t foff_a[3];
+#pragma unroll
+  for (int kw = 0; kw < 3; ++kw) {
+    const int hx = 8 * (g >> 1) + (r >> 2) + kw;
+    foff_a[kw] = (uint32_t)(hx * 128 + ((wci ^ ((hx >> 1) & 1)) * 64)) + fcol;
+  }
+  const int fpix = 8 * (g >> 1) + (r >> 2);
+  const uint32_t foff_b = (uint32_t)(fpix * 128 + ((wco ^ ((r >> 3) & 1)) * 64)) + fcol;
+  auto frag = [&](uint32_t tile, uint32_t foff, int kk) {
+    const uint32_t a = tile + foff + (uint32_t)(kk * 16 * 128);
+    const s16x4 lo = read_tr(a), hi = read_tr(a + 4 * 128);
+    const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8, v);
+  };
+
+  f32x16 acc[9], colsum;
+#pragma unroll
+  for (int t = 0; t < 9; ++t)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) colsum[v] = 0.f;
+  const bool sums_columns = cib == 0 && wci == 0;
+  const s16x8 ones_bits = {0x3f80, 0x3f80, 0x3f80, 0x3f80, 0x3f80, 0x3f80, 0x3f80, 0x3f80};
+  const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_bits);
+
+  int issued = 0;
+#pragma unroll
+  for (int f = 0; f < S - 1; ++f)
+    if (issued < T) { issue(issued); ++issued; }
+  for (int t = 0; t < T; ++t) {
+    wait_row_copies(issued - t - 1);             // stage t of this wave has landed
+    __syncthreads();                             // ... of all waves; stage t-1 is no longer read
+    if (issued < T) { issue(issued); ++issued; }
+    const uint32_t stage = lds0 + (uint32_t)((t % S) * ROW_STAGE);
+    const bf16x8 b0 = frag(stage + 3 * ROW_TILE, foff_b, 0);
+    const bf16x8 b1 = frag(stage + 3 * ROW_TILE, foff_b, 1);
+    if (sums_columns) {
+      colsum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b0, ones, colsum, 0, 0, 0);
+      colsum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b1, ones, colsum, 0, 0, 0);
+    }
+#pragma unroll
+    for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+      for (int kw = 0; kw < 3; ++kw) {
+        const bf16x8 a0 = frag(stage + kh * ROW_TILE, foff_a[kw], 0);
+        const bf16x8 a1 = frag(stage + kh * ROW_TILE, foff_a[kw], 1);
+        acc[kh * 3 + kw] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b0, a0, acc[kh * 3 + kw], 0, 0, 0);
+        acc[kh * 3 + kw] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b1, a1, acc[kh * 3 + kw], 0, 0, 0);
+      }
+  }
+
+  float* out = p.partial + ((int64_t)(chunk * gridDim.y + cib) * gridDim.z + cob) * TILE_FLOATS;
+#pragma unroll
+  for (int t = 0; t < 9; ++t)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const f32x4 o = {acc[t][4 * q], acc[t][4 * q + 1], acc[t][4 * q + 2], acc[t][4 * q + 3]};
+      *(f32x4*)&out[(((wave * SLOTS + t) * 4 + q) * 64 + lane) * 4] = o;
+    }
+  if (sums_columns) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const f32x4 o = {colsum[4 * q], colsum[4 * q + 1], colsum[4 * q + 2], colsum[4 * q + 3]};
+      *(f32x4*)&out[(((wave * SLOTS + 9) * 4 + q) * 64 + lane) * 4] = o;
+    }
+  }
+}
+
 // dW_k[tap][ci][co .. co+3] = the chunk results of worker k added in a fixed order; the items
 // behind the weights are the bias gradients db_k[co .. co+3] (slot 9, input channel 0).
 // 256 threads = 32 items x 8 chunk-lanes: lane q adds chunks q, q+8, ... (four independent
@@ -336,8 +482,15 @@ int launch_conv_wgrad(const void* in, int64_t ldi, int Cin, int H, int W, const 
   if (nch > 0) {
     ConvWgradArgs a = {(const bf16*)in, (int)ldi, (const bf16*)dy, (int)ldd, H, W, Ho, Wo, stride,
                        scratch, zeros};
-    hipLaunchKernelGGL(conv_wgrad_chunk_kernel, dim3(nch, cibs, cobs), dim3(256), 0,
-                       (hipStream_t)stream, a, s, ch);
+    // whole image rows per chunk and per worker: the row-staged kernel applies
+    bool by_rows = stride == 1 && W == 32 && Wo == 32 && H == Ho && chunk_rows % 32 == 0;
+    for (int k = 0; k <= s.K && by_rows; ++k) by_rows = s.off[k] % 32 == 0;
+    if (by_rows)
+      hipLaunchKernelGGL(conv_wgrad_rows_kernel, dim3(nch, cibs, cobs), dim3(256), 0,
+                         (hipStream_t)stream, a, s, ch);
+    else
+      hipLaunchKernelGGL(conv_wgrad_chunk_kernel, dim3(nch, cibs, cobs), dim3(256), 0,
+                         (hipStream_t)stream, a, s, ch);
   }
   const int64_t items = (int64_t)(9 * Cin + 1) * ((Cout + 3) / 4);
   hipLaunchKernelGGL(conv_wgrad_reduce_kernel, dim3((unsigned)((items + 31) / 32), s.K), dim3(256), 0,
