@@ -111,19 +111,23 @@ def test_cnn_channel_blocks_and_row_chunks(channels):
     check_worker_gradients(spec, params, x, y, b, label="cnn blocks %s" % (channels,))
 
 
-def test_cnn_on_32_wide_images_several_channel_blocks():
-    # 32 x 32 images select the halo-tile convolution kernel for forward and input gradient
-    # (stride 1, whole 64-channel blocks: 64 and 128 channels per tap), the stem (3 channels) and
-    # the strided layer stay on the gathered-operand kernel
-    spec = {"dtype": "bf16", "input": (32, 32, 3), "classes": 5,
-            "layers": [synth.conv3x3(3, 64, 1), synth.conv3x3(64, 128, 1), synth.conv3x3(128, 72, 1),
-                       synth.conv3x3(72, 16, 2), synth.gap(), synth.dense(16, 5, relu=False)]}
+@pytest.mark.parametrize("image,channels", [((32, 32, 3), (64, 128, 72)), ((8, 32, 3), (64, 20, 64))])
+def test_cnn_on_32_wide_images(image, channels):
+    # 32-wide images select the halo-tile convolution kernel for forward and input gradient and
+    # the row-staged weight gradient (stride 1; whole 64-channel blocks per tap: 64 and 128
+    # channels; output channel counts that fill a block, leave 8, or are no multiple of 8; an
+    # image one tile high); the stem (3 channels), layers behind a ragged channel count and the
+    # strided layer stay on the gathered-operand kernel
+    c1, c2, c3 = channels
+    spec = {"dtype": "bf16", "input": image, "classes": 5,
+            "layers": [synth.conv3x3(3, c1, 1), synth.conv3x3(c1, c2, 1), synth.conv3x3(c2, c3, 1),
+                       synth.conv3x3(c3, 16, 2), synth.gap(), synth.dense(16, 5, relu=False)]}
     params = synth.init_params(spec, "he", 61)
     rng = np.random.default_rng(3)
     params = [(W, (rng.standard_normal(bb.shape) * 0.1).astype(np.float32)) for W, bb in params]
     b = [2, 0, 1]
     x, y = synth.make_batch(spec, "uniform", sum(b), 62, 0)
-    check_worker_gradients(spec, params, x, y, b, label="cnn 32 wide")
+    check_worker_gradients(spec, params, x, y, b, label="cnn 32 wide %s" % (channels,))
 
 
 def test_sixty_four_workers():
