@@ -42,7 +42,7 @@ def worst_pair_relerr(got_list, ref_list):
     return worst
 
 
-class GpuRun:
+class DeviceRun:
     def __init__(self, spec, params_list, max_batch, max_workers):
         import torch
         self.torch = torch

@@ -6,7 +6,7 @@ import pytest
 
 from oracle import network as on
 from paper_2305_12213_amd import binding, synth
-from gpu_harness import GpuRun, relerr, worst_relerr
+from gpu_harness import DeviceRun, relerr, worst_relerr
 
 pytestmark = pytest.mark.gpu
 
@@ -67,8 +67,8 @@ def test_model_update_and_fused_aggregate_update(name, make_spec, opt):
     K, G = 5, 40
     b = [13, 0, 7, 19, 1]
     p0 = synth.init_params(spec, "he", 31)
-    sep = GpuRun(spec, p0, G, K)          # weighted_aggregate, then model_update
-    fus = GpuRun(spec, p0, G, K)          # model_aggregate_update
+    sep = DeviceRun(spec, p0, G, K)          # weighted_aggregate, then model_update
+    fus = DeviceRun(spec, p0, G, K)          # model_aggregate_update
     P, Pp = sep.P, sep.Pp
     rng = np.random.default_rng(77)
     st = {r: [torch.zeros(Pp, device="cuda"), torch.zeros(Pp, device="cuda")] for r in (sep, fus)}
@@ -112,7 +112,7 @@ def test_model_update_and_fused_aggregate_update(name, make_spec, opt):
 def test_update_argument_checks():
     import torch
     spec = synth.mlp_spec([16, 8, 4], "f32")
-    run = GpuRun(spec, synth.init_params(spec, "he", 1), 8, 2)
+    run = DeviceRun(spec, synth.init_params(spec, "he", 1), 8, 2)
     g = torch.zeros(run.Pp, device="cuda"); s = torch.zeros(run.Pp, device="cuda")
     with pytest.raises(binding.DynbError):
         binding.model_update(run.model, g, binding.make_optimizer("momentum", lr=0.1))      # no state
@@ -138,7 +138,7 @@ def test_forward_backward_aggregate_equals_the_two_call_form():
         G, K = sum(b), len(b)
         p0 = synth.init_params(spec, "he", 11)
         x, y = synth.make_batch(spec, "normal", G, 11, 0)
-        two = GpuRun(spec, p0, G, K); one = GpuRun(spec, p0, G, K)
+        two = DeviceRun(spec, p0, G, K); one = DeviceRun(spec, p0, G, K)
         xd = torch.from_numpy(np.ascontiguousarray(x, np.float32)).cuda()
         yd = torch.from_numpy(np.ascontiguousarray(y, np.int32)).cuda()
         two.forward_backward(xd, yd, b); two.aggregate(b)

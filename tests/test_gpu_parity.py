@@ -17,7 +17,7 @@ import pytest
 from oracle import controller as oc
 from oracle import network as on
 from paper_2305_12213_amd import binding, synth
-from gpu_harness import GpuRun, relerr, worker_grads_as_lists, worst_pair_relerr, worst_relerr
+from gpu_harness import DeviceRun, relerr, worker_grads_as_lists, worst_pair_relerr, worst_relerr
 from relu_ties import resolved_worker_references
 
 pytestmark = pytest.mark.gpu
@@ -27,7 +27,7 @@ TOL_EMULATED = 8e-3
 
 
 def check_worker_gradients(spec, params, x, y, b, run=None, label=""):
-    run = run or GpuRun(spec, params, max(1, sum(b)), len(b))
+    run = run or DeviceRun(spec, params, max(1, sum(b)), len(b))
     g = run.forward_backward(x, y, b).cpu().numpy()
     bf = spec["dtype"] == "bf16"
     got = worker_grads_as_lists(spec, g, run.P)
@@ -161,7 +161,7 @@ def test_same_handle_serves_changing_batch_splits():
     # batch sizes change every step; nothing is rebuilt per size and stale padding is harmless
     spec = synth.mlp_spec([128, 96, 10], "bf16")
     params = synth.init_params(spec, "he", 3)
-    run = GpuRun(spec, params, 300, 6)
+    run = DeviceRun(spec, params, 300, 6)
     for step, b in enumerate(([50] * 6, [1, 9, 100, 120, 3, 67], [300], [0, 299, 1], [7, 7, 7, 7])):
         x, y = synth.make_batch(spec, "uniform", sum(b), 5, step)
         check_worker_gradients(spec, params, x, y, b, run=run, label=str(b))
@@ -176,7 +176,7 @@ def test_bf16_gemms_are_exact_on_exactly_representable_inputs():
     x = rng.integers(-3, 4, (40, 64)).astype(np.float32)
     y = rng.integers(0, 10, 40).astype(np.int32)
     b = [16, 8, 16]
-    run = GpuRun(spec, params, 40, 3)
+    run = DeviceRun(spec, params, 40, 3)
     g = run.forward_backward(x, y, b).cpu().numpy()
     _, ref = on.worker_gradients(spec, params, x, y, b, emulate_bf16=True)
     # logits are exact, so dlogits differ only by fp32 softmax rounding before the bf16 store
@@ -230,7 +230,7 @@ def test_split_invariance_on_the_gpu():
     spec = synth.mlp_spec([96, 80, 10], "f32")
     params = synth.init_params(spec, "he", 8)
     x, y = synth.make_batch(spec, "normal", 120, 8, 0)
-    run = GpuRun(spec, params, 120, 8)
+    run = DeviceRun(spec, params, 120, 8)
     run.forward_backward(x, y, [120]); whole = run.aggregate([120]).cpu().numpy().copy()
     for b in ([60, 60], [1, 119], [17, 0, 3, 100], [15] * 8):
         run.forward_backward(x, y, b)
@@ -257,7 +257,7 @@ def run_workload(ci, steps):
     G, K = cfg["global_batch"], cfg["K"]
     ref_p = synth.init_params(spec, cfg["init"], seed)
     ref_v = on.zeros_like_params(ref_p)
-    run = GpuRun(spec, ref_p, G, K)
+    run = DeviceRun(spec, ref_p, G, K)
     b_gpu = list(cfg["b0"]); b_ref = list(cfg["b0"])
     worst_g = worst_agg = worst_p = 0.0
     amb = flips = 0
@@ -317,7 +317,7 @@ def test_workload0_free_running_trajectories_agree():
     cfg = synth.config(0)
     spec, seed = cfg["spec"], synth.BASE_SEED
     p = synth.init_params(spec, cfg["init"], seed)
-    run = GpuRun(spec, p, 64, 2)
+    run = DeviceRun(spec, p, 64, 2)
     ref = p
     b = list(cfg["b0"])
     for step in range(cfg["steps"]):
@@ -365,7 +365,7 @@ def test_workload4_wide_mlp_full_size_step(capsys):
     assert b == b_ref
     assert min(b) <= 8 and max(b) > 1000                   # the ragged split, 5 ... 1265
     x, y = synth.make_batch(spec, cfg["x_dist"], G, seed, 0)
-    run = GpuRun(spec, p0, G, K)
+    run = DeviceRun(spec, p0, G, K)
     g = run.forward_backward_aggregate(x, y, b)          # the calls the benchmark times
     out = run.out.cpu().numpy()
     run.update(cfg["lr"])

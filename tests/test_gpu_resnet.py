@@ -6,7 +6,7 @@ import pytest
 
 from oracle import network as on
 from paper_2305_12213_amd import binding, synth
-from gpu_harness import GpuRun, relerr, worker_grads_as_lists, worst_pair_relerr, worst_relerr
+from gpu_harness import DeviceRun, relerr, worker_grads_as_lists, worst_pair_relerr, worst_relerr
 from relu_ties import resolved_worker_references
 
 pytestmark = pytest.mark.gpu
@@ -44,7 +44,7 @@ def layer_errors(got, ref):
 
 
 def check(spec, params, x, y, b, label):
-    run = GpuRun(spec, params, max(1, sum(b)), len(b))
+    run = DeviceRun(spec, params, max(1, sum(b)), len(b))
     g = run.forward_backward_aggregate(x, y, b).cpu().numpy()
     got = worker_grads_as_lists(spec, g, run.P)
     refs, losses, n_amb, n_flip = resolved_worker_references(spec, params, x, y, b, got, True)
@@ -97,7 +97,7 @@ def test_training_steps_with_momentum_follow_the_checker():
     ref_p = perturbed(spec, 34)
     ref_v = on.zeros_like_params(ref_p)
     b = [5, 11]
-    run = GpuRun(spec, ref_p, 16, 2)
+    run = DeviceRun(spec, ref_p, 16, 2)
     for step in range(3):
         x, y = synth.make_batch(spec, "uniform", 16, 34, step)
         run.set_params(ref_p); run.set_velocity(ref_v)
@@ -150,7 +150,7 @@ def workload_size_case(spec, seed, capsys, label):
     x, y = synth.make_batch(spec, "uniform", sum(b), seed, 0)
     with capsys.disabled():
         print("\n  residual workload (%s): GPU pass" % label, flush=True)
-    run = GpuRun(spec, params, sum(b), len(b))
+    run = DeviceRun(spec, params, sum(b), len(b))
     g = run.forward_backward_aggregate(x, y, b).cpu().numpy()
     got = worker_grads_as_lists(spec, g, run.P)
     got_losses = run.losses(len(b))
