@@ -16,7 +16,9 @@ Everything is float64 numpy, written as the textbook definition:
 
 Pins (tests/test_oracle_network.py): central finite differences, a pure
 Python loop convolution, closed forms for softmax regression, the delta-image
-convolution, and the split-invariance of the weighted average.
+convolution, and the split-invariance of the weighted average; the
+asynchronous variant by the closed-form solution of its delay recurrence on
+a quadratic and by its reduction to plain SGD with one worker.
 
 `emulate_bf16=True` additionally rounds to bfloat16 (round-to-nearest-even)
 the quantities a bf16 implementation stores in 16 bits: the weights (not the
@@ -331,6 +333,24 @@ def sgd_update(params, g, lr):
     """x <- x - eta * g."""
     return [(np.asarray(W, np.float64) - lr * gW, np.asarray(b, np.float64) - lr * gb)
             for (W, b), (gW, gb) in zip(params, g)]
+
+
+def asynchronous_updates(gradient_of, params, order, lr):
+    """Asynchronous-parallel training as the paper describes it in words (Section "Distributed
+    Training": workers push gradients and pull parameters without waiting for one another; no
+    update rule is printed).  Reading: the workers arrive in the sequence `order`; an arriving
+    worker k delivers the gradient it computed at the parameters it pulled at its previous
+    arrival (the start parameters the first time) -- stale by however many other arrivals lay
+    in between --, the server applies it at once, x <- x - eta * g_k, and the worker pulls the
+    new parameters.  `gradient_of(k, params)` is worker k's gradient in the shape of `params`.
+    Returns the final parameters."""
+    pulled = {}
+    cur = [(np.asarray(W, np.float64), np.asarray(b, np.float64)) for W, b in params]
+    for k in order:
+        g = gradient_of(k, pulled.get(k, params))
+        cur = sgd_update(cur, g, lr)
+        pulled[k] = cur
+    return cur
 
 
 def momentum_update(params, velocity, g, lr, mu):

@@ -413,3 +413,52 @@ def test_residual_add_sends_the_same_gradient_down_both_branches():
     np.testing.assert_allclose(g0[0][0], gp[0][0], rtol=1e-12, atol=1e-14)
     np.testing.assert_allclose(g0[2][0], gp[1][0], rtol=1e-12, atol=1e-14)
     assert np.max(np.abs(g[0][0] - gp[0][0])) > 1e-6      # with the branch it differs
+
+
+# --------------------------------------------------------------------------
+# asynchronous (stale-gradient) variant
+# --------------------------------------------------------------------------
+def test_asynchronous_updates_follow_the_delay_recurrence_on_a_quadratic():
+    # f(w) = a w^2 / 2 for both workers, arrivals alternate 0,1,0,1,...: every gradient but the
+    # first two is one update stale, w_{t+1} = w_t - c w_{t-1} with c = eta a, whose solution is
+    # A r1^t + B r2^t with r = (1 +- sqrt(1 - 4c)) / 2 (textbook linear recurrence)
+    a, eta, w0 = 2.0, 0.1, 3.0
+    c = eta * a
+    grad = lambda k, p: [(a * p[0][0], 0.0 * p[0][1])]
+    steps = 12
+    got = on.asynchronous_updates(grad, [(np.array([w0]), np.array([0.0]))], [t % 2 for t in range(steps)], eta)
+    # arrivals: t=0 worker 0 at w0 -> w1 = w0 - c w0; t=1 worker 1 at w0 (never pulled) -> w2 = w1 - c w0;
+    # from then on the arriving worker pulled two arrivals ago: w_{t+1} = w_t - c w_{t-1}
+    w1 = w0 - c * w0
+    r1, r2 = (1 + np.sqrt(1 - 4 * c)) / 2, (1 - np.sqrt(1 - 4 * c)) / 2
+    B = (w1 - w0 * r1) / (r2 - r1)
+    A = w0 - B
+    assert got[0][0][0] == pytest.approx(A * r1 ** steps + B * r2 ** steps, rel=1e-12)
+
+
+def test_asynchronous_updates_with_one_worker_are_plain_sgd():
+    spec = synth.mlp_spec([6, 5, 3], "f32")
+    params = synth.init_params(spec, "he", 4)
+    x, y = synth.make_batch(spec, "normal", 7, 4, 0)
+    grad = lambda k, p: on.loss_and_gradient(spec, p, x, y)[1]
+    got = on.asynchronous_updates(grad, params, [0, 0, 0], 0.05)
+    want = params
+    for _ in range(3):
+        want = on.sgd_update(want, on.loss_and_gradient(spec, want, x, y)[1], 0.05)
+    for (gW, gb), (wW, wb) in zip(got, want):
+        assert np.array_equal(gW, wW) and np.array_equal(gb, wb)
+
+
+def test_asynchronous_updates_use_stale_parameters():
+    # two workers, worker 1 arrives after two updates by worker 0: its gradient must be the one
+    # at the START parameters, not at the current ones (a dropped snapshot would pass the other two)
+    a, eta = 1.5, 0.2
+    seen = []
+    def grad(k, p):
+        seen.append((k, float(p[0][0][0])))
+        return [(a * p[0][0], 0.0 * p[0][1])]
+    on.asynchronous_updates(grad, [(np.array([1.0]), np.array([0.0]))], [0, 0, 1, 1], eta)
+    assert seen[0] == (0, 1.0)
+    assert seen[1][1] == pytest.approx(1.0 - eta * a)          # worker 0 pulled after its update
+    assert seen[2] == (1, 1.0)                                  # worker 1 still holds the start
+    assert seen[3][0] == 1 and seen[3][1] != 1.0                # and has pulled since
