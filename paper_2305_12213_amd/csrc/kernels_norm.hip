@@ -141,11 +141,15 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const bf16* __restrict__ 
   float mu[8], rs[8], ga[8], be[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
+    // (clamped index, then a select: all loads are issued at once, no branch per channel)
     const bool live = c0 + j < C;
-    mu[j] = live ? mean[(int64_t)k * C + c0 + j] : 0.f;
-    rs[j] = live ? rstd[(int64_t)k * C + c0 + j] : 0.f;
-    ga[j] = live ? gamma[c0 + j] : 0.f;
-    be[j] = live ? beta[c0 + j] : 0.f;
+    const int cj = live ? c0 + j : C - 1;
+    const float m_ = mean[(int64_t)k * C + cj], r_ = rstd[(int64_t)k * C + cj];
+    const float g_ = gamma[cj], b_ = beta[cj];
+    mu[j] = live ? m_ : 0.f;
+    rs[j] = live ? r_ : 0.f;
+    ga[j] = live ? g_ : 0.f;
+    be[j] = live ? b_ : 0.f;
   }
   const bf16* xb = x + (int64_t)r0 * ldx + c0;
   bf16* yb = y + (int64_t)r0 * ldy + c0;
@@ -190,8 +194,10 @@ __global__ __launch_bounds__(256) void bn_chunk_param_grad_kernel(
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     const bool live = c0 + j < C;
-    mu[j] = live ? mean[(int64_t)k * C + c0 + j] : 0.f;
-    rs[j] = live ? rstd[(int64_t)k * C + c0 + j] : 0.f;
+    const int cj = live ? c0 + j : C - 1;
+    const float m_ = mean[(int64_t)k * C + cj], r_ = rstd[(int64_t)k * C + cj];
+    mu[j] = live ? m_ : 0.f;
+    rs[j] = live ? r_ : 0.f;
     ag[j] = 0.f; ab[j] = 0.f;
   }
   const bf16* xb = x + (int64_t)r0 * ldx + c0;
@@ -258,11 +264,14 @@ __global__ __launch_bounds__(256) void bn_input_grad_kernel(
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     const bool live = c0 + j < C;
-    mu[j] = live ? mean[(int64_t)k * C + c0 + j] : 0.f;
-    rs[j] = live ? rstd[(int64_t)k * C + c0 + j] : 0.f;
-    gr[j] = live ? gamma[c0 + j] * rs[j] : 0.f;
-    mg[j] = live ? dgamma[(int64_t)k * group_stride + c0 + j] / rows : 0.f;
-    mb[j] = live ? dbeta[(int64_t)k * group_stride + c0 + j] / rows : 0.f;
+    const int cj = live ? c0 + j : C - 1;
+    const float m_ = mean[(int64_t)k * C + cj], r_ = rstd[(int64_t)k * C + cj], g_ = gamma[cj];
+    const float dg_ = dgamma[(int64_t)k * group_stride + cj], db_ = dbeta[(int64_t)k * group_stride + cj];
+    mu[j] = live ? m_ : 0.f;
+    rs[j] = live ? r_ : 0.f;
+    gr[j] = live ? g_ * r_ : 0.f;
+    mg[j] = live ? dg_ / rows : 0.f;
+    mb[j] = live ? db_ / rows : 0.f;
   }
   const bf16* xb = x + (int64_t)r0 * ldx + c0;
   const bf16* db = dy + (int64_t)r0 * ldd + c0;
