@@ -116,6 +116,15 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(ConvDirectArgs p) {
     return *(const bf16x8*)((const char*)&wring[st][0] + addr);
   };
 
+  // bias of this lane's 8 output channels in the epilogue (fetched here: its latency hides
+  // behind the main loop; clamped index and a select instead of a branch per channel)
+  float bv[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int j = j0 + (lane & 7) * 8 + e;
+    const float t = p.bias ? p.bias[j < p.N ? j : p.N - 1] : 0.f;
+    bv[e] = j < p.N ? t : 0.f;
+  }
   f32x16 acc[2][2];
 #pragma unroll
   for (int a = 0; a < 2; ++a)
@@ -165,12 +174,6 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(ConvDirectArgs p) {
   const int rrow = lane >> 3, rcol = (lane & 7) * 8;
   const int jcol = j0 + rcol;
   const bool col_ok = jcol + 7 < p.N;
-  float bv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  if (p.bias) {
-#pragma unroll
-    for (int e = 0; e < 8; ++e)
-      if (jcol + e < p.N) bv[e] = p.bias[jcol + e];
-  }
   const int64_t row0 = (int64_t)(img * p.H + y0 + 2 * wave) * 32;   // first pixel of the wave's strip
   // the mask and addend rows of the whole strip are fetched up front (one round trip to
   // memory instead of eight)
