@@ -333,19 +333,28 @@ __global__ __launch_bounds__(256) void conv_wgrad_rows_kernel(ConvWgradArgs p, S
     const uint32_t stage = lds0 + (uint32_t)((t % S) * ROW_STAGE);
     const bf16x8 b0 = frag(stage + 3 * ROW_TILE, foff_b, 0);
     const bf16x8 b1 = frag(stage + 3 * ROW_TILE, foff_b, 1);
-    if (sums_columns) {
-      colsum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b0, ones, colsum, 0, 0, 0);
-      colsum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b1, ones, colsum, 0, 0, 0);
-    }
+    // the operands of tap n+1 are fetched before the MFMAs of tap n (two register sets), so
+    // that the LDS latency hides behind them; the column sums run in every wave (no branch in
+    // the loop), only the waves that own them write them out
+    bf16x8 a0[2], a1[2];
+    a0[0] = frag(stage, foff_a[0], 0);
+    a1[0] = frag(stage, foff_a[0], 1);
 #pragma unroll
-    for (int kh = 0; kh < 3; ++kh)
-#pragma unroll
-      for (int kw = 0; kw < 3; ++kw) {
-        const bf16x8 a0 = frag(stage + kh * ROW_TILE, foff_a[kw], 0);
-        const bf16x8 a1 = frag(stage + kh * ROW_TILE, foff_a[kw], 1);
-        acc[kh * 3 + kw] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b0, a0, acc[kh * 3 + kw], 0, 0, 0);
-        acc[kh * 3 + kw] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b1, a1, acc[kh * 3 + kw], 0, 0, 0);
+    for (int tap = 0; tap < 9; ++tap) {
+      if (tap + 1 < 9) {
+        const int nh = (tap + 1) / 3, nw = (tap + 1) - 3 * nh;
+        a0[(tap + 1) & 1] = frag(stage + nh * ROW_TILE, foff_a[nw], 0);
+        a1[(tap + 1) & 1] = frag(stage + nh * ROW_TILE, foff_a[nw], 1);
       }
+      __builtin_amdgcn_sched_barrier(0);         // (keeps the fetches in front of the MFMAs)
+      if (tap == 4) {
+        colsum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b0, ones, colsum, 0, 0, 0);
+        colsum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b1, ones, colsum, 0, 0, 0);
+      }
+      acc[tap] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b0, a0[tap & 1], acc[tap], 0, 0, 0);
+      acc[tap] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b1, a1[tap & 1], acc[tap], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
   }
 
   float* out = p.partial + ((int64_t)(chunk * gridDim.y + cib) * gridDim.z + cob) * TILE_FLOATS;
