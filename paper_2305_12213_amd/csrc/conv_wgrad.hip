@@ -250,46 +250,46 @@ __global__ __launch_bounds__(256) void conv_wgrad_rows_kernel(ConvWgradArgs p, S
   // pixel slots [8o, 8o+8), o = c % 5 (slot hx holds source pixel x = hx - 1); 15 <= c < 19:
   // pixels [8(c-15), +8) of the dy row; c = 19: padding.  This lane moves slot lane/8 of the
   // eight, granule lane%8; halves of slots 2,3,6,7,... are swapped as in the kernel above.
+  // Rows are contiguous in memory across images, so every copy keeps a running pointer that
+  // moves on by one row per stage; whether a neighbouring row lies inside the image is the same
+  // for the whole wave.  (Cycle counters showed the address arithmetic of this step, done from
+  // scratch with 64-bit products, taking longer than the MFMAs of a stage.)
   const int gq = (lane & 7) ^ (((lane >> 4) & 1) << 2);
-  int64_t src_off[ROW_PER];                      // element offset relative to the stage's row, or -1
-  int src_kind[ROW_PER];                         // 0..2: input row kh, 3: dy, 4: zeros
+  const char* ptr[ROW_PER];                      // this lane's source in the stage's row, or nullptr
+  int kind[ROW_PER];                             // 0..2: input row kh, 3: dy, 4: zeros
+  const int o0 = r0 / 32;                        // first output row (image * H + y)
 #pragma unroll
   for (int u = 0; u < ROW_PER; ++u) {
     const int c = wave + 4 * u;
-    src_kind[u] = 4;
-    src_off[u] = 0;
+    kind[u] = 4;
+    ptr[u] = nullptr;
     if (c < 15) {
       const int x = 8 * (c % 5) + (lane >> 3) - 1;
       if (x >= 0 && x < 32) {
-        src_kind[u] = c / 5;
-        src_off[u] = (int64_t)x * p.ldi + cib * 64 + gq * 8;
+        kind[u] = c / 5;
+        ptr[u] = (const char*)(p.in + ((int64_t)(o0 + c / 5 - 1) * 32 + x) * p.ldi + cib * 64 + gq * 8);
       }
     } else if (c < 19) {
-      src_kind[u] = 3;
-      src_off[u] = (int64_t)(8 * (c - 15) + (lane >> 3)) * p.ldd + cob * 64 + gq * 8;
+      kind[u] = 3;
+      ptr[u] = (const char*)(p.dy + ((int64_t)o0 * 32 + 8 * (c - 15) + (lane >> 3)) * p.ldd + cob * 64 + gq * 8);
     }
   }
-  int orow = r0 / 32;                            // output row (image * H + y) of the next stage to issue
+  const int64_t in_step = (int64_t)32 * p.ldi * 2, dy_step = (int64_t)32 * p.ldd * 2;   // bytes per row
+  int iy = o0 % p.H;                             // image row of the next stage to issue
   auto issue = [&](int t) {
     const uint32_t base = lds0 + (uint32_t)((t % S) * ROW_STAGE);
-    const int img = orow / p.H, oy = orow - img * p.H;
+    const bool above = iy > 0, below = iy < p.H - 1;   // rows y-1 / y+1 exist
 #pragma unroll
     for (int u = 0; u < ROW_PER; ++u) {
       const int c = wave + 4 * u;
-      const void* src = p.zeros;
-      if (src_kind[u] < 3) {
-        const int sy = oy + src_kind[u] - 1;
-        const int csy = sy < 0 ? 0 : (sy >= p.H ? p.H - 1 : sy);
-        const bf16* a = p.in + (int64_t)(img * p.H + csy) * 32 * p.ldi + src_off[u];
-        if (sy >= 0 && sy < p.H) src = a;
-      } else if (src_kind[u] == 3) {
-        src = p.dy + (int64_t)orow * 32 * p.ldd + src_off[u];
-      }
+      const bool row_ok = kind[u] == 0 ? above : (kind[u] == 2 ? below : true);
+      const void* src = (ptr[u] != nullptr && row_ok) ? (const void*)ptr[u] : p.zeros;
       const uint32_t dst = c < 15 ? (uint32_t)((c / 5) * ROW_TILE + (c % 5) * 1024)
                                   : (uint32_t)(3 * ROW_TILE + (c - 15) * 1024);
       async_copy_1k(src, base + dst);
+      if (ptr[u] != nullptr) ptr[u] += kind[u] == 3 ? dy_step : in_step;
     }
-    ++orow;
+    if (++iy == p.H) iy = 0;
   };
 
   // ---- LDS -> MFMA operands (see the kernel above); input rows are read at slot x + kw
