@@ -14,9 +14,8 @@
 // tracked with vmcnt by hand, as in gemm.hip.
 #include <hip/hip_runtime.h>
 
-#include <mutex>
-
 #include "dynb_internal.h"
+#include "lds_async.h"
 
 namespace dynb {
 namespace {
@@ -30,14 +29,6 @@ constexpr int HALO_W = 34, HALO_H = 10, HALO_PIX = HALO_W * HALO_H;   // 340 pix
 constexpr int HALO_COPIES = 44;             // 1 KB each (8 pixels): 11 per wave, 352 pixel slots
 constexpr int WSTAGES = 3;                  // ring of weight stages (one tap x 64 channels: 8 KB)
 constexpr int EP = 64 + 4;                  // epilogue patch row pitch in floats
-
-__device__ uint4 g_zero16[1];
-
-__device__ inline void async_copy_1k(const void* src, uint32_t lds_base) {
-  const uint32_t base = __builtin_amdgcn_readfirstlane(lds_base);
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(base), "v"(src)
-               : "memory", "m0");
-}
 
 struct ConvDirectArgs {
   const bf16* src; int lds;          // [images * H * 32][lds]
@@ -241,20 +232,6 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(ConvDirectArgs p) {
   }
 }
 
-const void* zeros_on_device() {
-  static std::mutex mu;
-  static const void* known[64] = {};
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
-  std::lock_guard<std::mutex> lk(mu);
-  if (!known[dev]) {
-    void* q = nullptr;
-    if (hipGetSymbolAddress(&q, HIP_SYMBOL(g_zero16)) != hipSuccess) return nullptr;
-    known[dev] = q;
-  }
-  return known[dev];
-}
-
 }  // namespace
 
 // Does the halo-tile kernel cover this convolution?  (stride 1, images 32 wide and a multiple
@@ -269,7 +246,7 @@ bool conv_direct_applies(int dtype, const GemmArgs& a) {
 }
 
 int launch_conv_direct(const GemmArgs& a, void* stream) {
-  const void* zeros = zeros_on_device();
+  const void* zeros = device_zero_granule();
   if (!zeros) return fail(DYNB_ERR_HIP, "conv_direct: no address for the zero granule");
   ConvDirectArgs p = {};
   p.src = (const bf16*)a.A; p.lds = (int)a.lda;

@@ -22,6 +22,7 @@
 #include <mutex>
 
 #include "dynb_internal.h"
+#include "lds_async.h"
 
 namespace dynb {
 namespace {
@@ -42,13 +43,6 @@ constexpr int TILE_FLOATS = 4 * SLOTS * 16 * 64;   // one chunk result per 64 x 
                                                    // [wave][slot][16 accumulator elements][lane]
 
 __device__ uint4 g_zeros[1];                 // what lanes outside the image or the chunk fetch
-
-// 64 lanes x 16 bytes, global -> LDS: lane l lands at lds_base + 16 * l (lds_base wave-uniform)
-__device__ inline void async_copy_1k(const void* src, uint32_t lds_base) {
-  const uint32_t base = __builtin_amdgcn_readfirstlane(lds_base);
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(base), "v"(src)
-               : "memory", "m0");
-}
 
 __device__ inline void wait_copies(int stages) {   // at most `stages` stages of this wave pending
   switch (stages) {
@@ -430,8 +424,10 @@ __global__ __launch_bounds__(256) void conv_wgrad_reduce_kernel(const float* __r
     if (co + e < Cout) dst[e] = sum[e];
 }
 
+}  // namespace
+
 // address of g_zeros on the current device (looked up once per device)
-const void* zeros_on_device() {
+const void* device_zero_granule() {
   static std::mutex mu;
   static const void* known[64] = {};
   int dev = 0;
@@ -444,8 +440,6 @@ const void* zeros_on_device() {
   }
   return known[dev];
 }
-
-}  // namespace
 
 RowChunks make_row_chunks(const Segs& s, int rows) {
   RowChunks ch;
@@ -481,7 +475,7 @@ int launch_conv_wgrad(const void* in, int64_t ldi, int Cin, int H, int W, const 
     return fail(DYNB_ERR_BADARG, "conv_wgrad: pitches must cover whole 64-channel blocks, 16-byte aligned");
   if (ldi > INT_MAX || ldd > INT_MAX || (int64_t)s.off[s.K] * stride * stride > INT_MAX / 2)
     return fail(DYNB_ERR_UNSUPPORTED, "conv_wgrad: tensor too large for 32-bit pixel indices");
-  const void* zeros = zeros_on_device();
+  const void* zeros = device_zero_granule();
   if (!zeros) return fail(DYNB_ERR_HIP, "conv_wgrad: no address for the zero granule");
   const RowChunks ch = make_row_chunks(s, chunk_rows);
   const int nch = ch.first[s.K];
