@@ -79,7 +79,7 @@ enum { MODE_FWD = 0, MODE_DGRAD = 1, MODE_WGRAD = 2 };
 //           addend[i*ldadd + j] added, then the mask is applied.
 //   WGRAD : one group per worker g: operands start at column poff[g], depth
 //           poff[g+1]-poff[g]; i = output feature, j = input feature;
-//           Cf[g*group_stride + j*ldcf + i] = acc.
+//           Cf[g*group_stride + j*ldcf + i] = acc.  (`rowmajor`: see the field.)
 struct GemmArgs {
   const void* A; int64_t lda; int M;   // rows of A  (i)
   const void* B; int64_t ldb; int N;   // rows of B  (j)
@@ -92,6 +92,9 @@ struct GemmArgs {
   const void* addend; int64_t ldadd;   // DGRAD, bf16: see above
   int64_t group_stride;
   int groups_per_block;                // WGRAD, bf16 kernel: workers streamed by one workgroup
+  // WGRAD, bf16 only: A and B are the ROW-MAJOR tensors, A = dy [batch rows][lda], B = the layer
+  // input [batch rows][ldb]; worker g owns rows [off[g], off[g+1]) (no padded transposed copies)
+  int rowmajor;
   // Implicit-GEMM gather of operand A for a 3x3 convolution with zero padding 1 (bf16 only).
   // conv == 0: A is a plain matrix.  conv == 1 (forward): row i is output pixel (n, y, x) of a
   // row_h x row_w grid and reduction index k = (kh*3 + kw)*cp + c reads channel c of source
@@ -141,6 +144,10 @@ int launch_softmax_xent(int dtype, const float* logits, int64_t ldz, const int32
                         void* dz, int64_t ldd, int ld_cols, float* rowloss, const Segs& s,
                         void* stream);
 // grads[g*group_stride + n] = sum over worker g's rows of dyT[n][row]
+// ... and from the row-major gradient dy [rows][ld] (bf16; ld a multiple of 64, zeros in the
+// padding columns)
+int launch_bias_grad_rows(const void* dy, int64_t ld, int N, float* grads, int64_t group_stride,
+                          const Segs& s, void* stream);
 int launch_bias_grad(int dtype, const void* dyT, int64_t ld, int N, float* grads,
                      int64_t group_stride, const Segs& s, void* stream);
 // loss[g] = mean of rowloss over worker g's rows; grads[g][P..P_pad) = 0

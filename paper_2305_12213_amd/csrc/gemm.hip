@@ -135,9 +135,16 @@ struct PatchArea<0> {
 // S = number of LDS stage buffers (ring).
 // AGG (weight gradient only): the workgroup also accumulates sum_g lam[g] * tile_g in registers
 // and writes it to p.agg; it then owns all workers of its tile and walks them in ascending order.
-template <int BM, int BN, int WM, int WN, int MODE, bool GATHER, int S, bool AGG = false>
+// RM (weight gradient only): the operands are the row-major tensors themselves, A = dy
+// [rows][lda] and B = the layer input [rows][ldb], the reduction runs over their ROWS (worker g
+// owns rows [off[g], off[g+1])), and a stage holds 32 rows x BM (BN) features as they lie in
+// memory; MFMA operands are fetched with the LDS transpose read (see conv_wgrad.hip for its
+// lane layout).  No transposed copies of the activations are needed.
+template <int BM, int BN, int WM, int WN, int MODE, bool GATHER, int S, bool AGG = false, bool RM = false>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Segs segs) {
   static_assert(!AGG || MODE == MODE_WGRAD, "aggregation belongs to the weight gradient");
+  static_assert(!RM || (MODE == MODE_WGRAD && !GATHER && (BM == 256 || BM == 128) && (BN == 256 || BN == 128)),
+                "row-major operands: weight gradient, 128 or 256 features per tile side");
   constexpr int NW = WM * WN;
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
   constexpr int LA = BM / 16 / NW, LB = BN / 16 / NW;   // 16-row blocks per wave and stage
@@ -165,12 +172,14 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
 
   auto col0_of = [&](int g) {   // first reduction column of a group
     if (MODE != MODE_WGRAD) return 0;
-    return split > 1 ? segs.poff[g / split] + (g % split) * p.chunk : segs.poff[g];
+    const int* first = RM ? segs.off : segs.poff;
+    return split > 1 ? first[g / split] + (g % split) * p.chunk : first[g];
   };
   auto depth_of = [&](int g) {
     if (MODE != MODE_WGRAD) return p.K;
-    if (split == 1) return segs.poff[g + 1] - segs.poff[g];
-    const int w = g / split, left = segs.poff[w + 1] - segs.poff[w] - (g % split) * p.chunk;
+    const int* first = RM ? segs.off : segs.poff;
+    if (split == 1) return first[g + 1] - first[g];
+    const int w = g / split, left = first[w + 1] - first[w] - (g % split) * p.chunk;
     return left < 0 ? 0 : (left < p.chunk ? left : p.chunk);
   };
   auto tile_base = [&](int g) -> float* {   // where a group's tile goes
@@ -244,8 +253,49 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
   }
   const uint32_t ldsA = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)&sA[0][0];
   const uint32_t ldsB = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)&sB[0][0];
+  // RM: a copy moves 512/BM (512/BN) whole reduction rows of BM (BN) features; this lane's
+  // row within the stage and its byte offset from the stage's first row (~0u: past the row
+  // pitch, zeros).  Granule g of reduction row k sits at slot g ^ ((k & 3) << 2): the
+  // transpose reads of 4 neighbouring rows and of the two 16-feature halves of a 32-feature
+  // block then fall into 8 different 32-byte bank ranges.
+  int rkA[RM ? LA : 1], rkB[RM ? LB : 1];
+  uint32_t roA[RM ? LA : 1], roB[RM ? LB : 1];
+  if constexpr (RM) {
+    constexpr int GA = BM / 8, GB = BN / 8;      // granules per reduction row
+#pragma unroll
+    for (int u = 0; u < LA; ++u) {
+      const int k = (wave + NW * u) * (64 / GA) + lane / GA;
+      const int f = i0 + (((lane % GA) ^ ((k & 3) << 2)) * 8);
+      rkA[u] = k;
+      roA[u] = f < p.lda ? (uint32_t)(((int64_t)k * p.lda + f) * 2) : ~0u;
+    }
+#pragma unroll
+    for (int u = 0; u < LB; ++u) {
+      const int k = (wave + NW * u) * (64 / GB) + lane / GB;
+      const int f = j0 + (((lane % GB) ^ ((k & 3) << 2)) * 8);
+      rkB[u] = k;
+      roB[u] = f < p.ldb ? (uint32_t)(((int64_t)k * p.ldb + f) * 2) : ~0u;
+    }
+  }
   auto issue = [&](int buf, const StageCursor& c) {
     const int k0 = c.kt * BK;
+    if constexpr (RM) {
+      const uint32_t rowA = (uint32_t)((int64_t)(c.col0 + k0) * p.lda * 2);
+      const uint32_t rowB = (uint32_t)((int64_t)(c.col0 + k0) * p.ldb * 2);
+#pragma unroll
+      for (int u = 0; u < LA; ++u) {
+        const void* src = (k0 + rkA[u] < c.depth && roA[u] != ~0u) ? (const void*)(Ab + rowA + roA[u])
+                                                                   : (const void*)g_zero_granule;
+        async_copy_1k(src, ldsA + (uint32_t)((buf * BM * GPR + (wave + NW * u) * 64) * 16));
+      }
+#pragma unroll
+      for (int u = 0; u < LB; ++u) {
+        const void* src = (k0 + rkB[u] < c.depth && roB[u] != ~0u) ? (const void*)(Bb + rowB + roB[u])
+                                                                   : (const void*)g_zero_granule;
+        async_copy_1k(src, ldsB + (uint32_t)((buf * BN * GPR + (wave + NW * u) * 64) * 16));
+      }
+      return;
+    }
     bool live = true;
     uint32_t kbyte = (uint32_t)k0 * 2;
     if (MODE == MODE_WGRAD) {
@@ -311,7 +361,40 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
   const int frow_b = (wn * (BN / WN) + (lane & 31)) * GPR;
   const int fsw = ((lane & 31) >> 1) & 3, fhi = lane >> 5;
   bf16x8 fa[2][TM], fb[2][TN];   // two register sets, alternating per k-step
+  // RM: 16 lanes fetch 4 reduction rows x 16 features with two transpose reads (lane r supplies
+  // the address of features 4(r%4).. of row r/4 and receives feature r of the 4 rows)
+  const int tg = lane >> 4, tr = lane & 15;
+  auto tr_off = [&](int feat0, int pitch) {      // this lane's byte offset for the block at feat0
+    const int f = feat0 + 16 * (tg & 1) + 4 * (tr & 3);
+    return (uint32_t)((8 * (tg >> 1) + (tr >> 2)) * pitch + (((f >> 3) ^ ((tr >> 2) << 2)) * 16) + (f & 7) * 2);
+  };
+  uint32_t trA[RM ? TM : 1], trB[RM ? TN : 1];
+  if constexpr (RM) {
+#pragma unroll
+    for (int a = 0; a < TM; ++a) trA[a] = tr_off(wm * (BM / WM) + a * 32, BM * 2);
+#pragma unroll
+    for (int b = 0; b < TN; ++b) trB[b] = tr_off(wn * (BN / WN) + b * 32, BN * 2);
+  }
+  auto tr_frag = [&](uint32_t addr, int pitch) {
+    typedef short s16x4 __attribute__((ext_vector_type(4)));
+    typedef short s16x8 __attribute__((ext_vector_type(8)));
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) s16x4*)(uintptr_t)addr);
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) s16x4*)(uintptr_t)(addr + 4 * pitch));
+    const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8, v);
+  };
   auto lfrag = [&](const uint4* sa, const uint4* sb, int kk, int set) {
+    if constexpr (RM) {
+      const uint32_t la = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)sa;
+      const uint32_t lb = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)sb;
+#pragma unroll
+      for (int a = 0; a < TM; ++a) fa[set][a] = tr_frag(la + trA[a] + (uint32_t)(kk * 16 * BM * 2), BM * 2);
+#pragma unroll
+      for (int b = 0; b < TN; ++b) fb[set][b] = tr_frag(lb + trB[b] + (uint32_t)(kk * 16 * BN * 2), BN * 2);
+      return;
+    }
     const int g = (kk * 2 + fhi) ^ fsw;
 #pragma unroll
     for (int a = 0; a < TM; ++a) fa[set][a] = *(const bf16x8*)&sa[frow_a + a * 32 * GPR + g];
@@ -714,14 +797,31 @@ void launch_bf16(GemmArgs a, const Segs& s, hipStream_t st) {
   }
 }
 
+// Weight gradients straight from the row-major activations (RM): the same three tile shapes.
+template <int BM, int BN, int S>
+void launch_bf16_wgrad_rm(GemmArgs a, const Segs& s, hipStream_t st) {
+  const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
+  const int n_groups = s.K * (a.split > 1 ? a.split : 1);
+  int chunks = (256 + tiles - 1) / tiles;
+  if (chunks > n_groups) chunks = n_groups;
+  a.groups_per_block = (n_groups + chunks - 1) / chunks;
+  const int gy = (n_groups + a.groups_per_block - 1) / a.groups_per_block;
+  hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, 2, 2, MODE_WGRAD, false, S, false, true>), dim3(tiles, gy, 1),
+                     dim3(256), 0, st, a, s);
+}
+
 // Weight gradient with the weighted aggregation folded in: 256 x 128 tiles leave room for a
 // second set of accumulators; every workgroup takes all workers of its tile.
 constexpr int AGG_BM = 256, AGG_BN = 128;
 void launch_bf16_wgrad_agg(GemmArgs a, const Segs& s, hipStream_t st) {
   const int tiles = ((a.M + AGG_BM - 1) / AGG_BM) * ((a.N + AGG_BN - 1) / AGG_BN);
   a.groups_per_block = s.K;
-  hipLaunchKernelGGL((gemm_bf16_kernel<AGG_BM, AGG_BN, 2, 2, MODE_WGRAD, false, 5, true>), dim3(tiles),
-                     dim3(256), 0, st, a, s);
+  if (a.rowmajor)
+    hipLaunchKernelGGL((gemm_bf16_kernel<AGG_BM, AGG_BN, 2, 2, MODE_WGRAD, false, 5, true, true>), dim3(tiles),
+                       dim3(256), 0, st, a, s);
+  else
+    hipLaunchKernelGGL((gemm_bf16_kernel<AGG_BM, AGG_BN, 2, 2, MODE_WGRAD, false, 5, true>), dim3(tiles),
+                       dim3(256), 0, st, a, s);
 }
 
 // implicit-GEMM convolution (operand A gathered).  The reduction is short (9 x channels), so a
@@ -786,6 +886,8 @@ int launch_gemm(int dtype, const GemmArgs& a, const Segs& s, void* stream) {
     return fail(DYNB_ERR_BADARG, "gemm: operands must have 16-byte aligned rows");
   if (a.addend && (dtype != DYNB_BF16 || a.mode != MODE_DGRAD))
     return fail(DYNB_ERR_UNSUPPORTED, "gemm: an addend belongs to a bf16 input gradient");
+  if (a.rowmajor && dtype != DYNB_BF16)
+    return fail(DYNB_ERR_UNSUPPORTED, "gemm: row-major weight-gradient operands are a bf16 path");
   const int groups = a.mode == MODE_WGRAD ? s.K : 1;
   const KClass cls = a.mode == MODE_FWD ? KC_GEMM_FWD : a.mode == MODE_DGRAD ? KC_GEMM_DGRAD
                                                                               : KC_GEMM_WGRAD;
@@ -801,7 +903,13 @@ int launch_gemm(int dtype, const GemmArgs& a, const Segs& s, void* stream) {
     // large tiles have the best LDS-traffic-to-MFMA ratio; small problems need more, smaller
     // tiles to occupy 256 compute units
     const int64_t big = (int64_t)((a.M + 255) / 256) * ((a.N + 255) / 256);
-    if (big >= 192)
+    if (a.rowmajor) {
+      if (a.mode != MODE_WGRAD) return fail(DYNB_ERR_BADARG, "gemm: row-major operands belong to the weight gradient");
+      if (big >= 192)
+        launch_bf16_wgrad_rm<256, 256, 4>(a, s, (hipStream_t)stream);
+      else
+        launch_bf16_wgrad_rm<128, 128, 8>(a, s, (hipStream_t)stream);
+    } else if (big >= 192)
       launch_bf16<256, 256, 2, 2, 5, 4>(a, s, (hipStream_t)stream);   // 160 KB / 128 + 18 KB of LDS
     else
       launch_bf16<128, 128, 2, 2, 8, 8>(a, s, (hipStream_t)stream);

@@ -3,6 +3,7 @@
 // 16-bit weight copies.
 #include <hip/hip_runtime.h>
 
+#include "device_rows.h"
 #include "dynb_internal.h"
 
 namespace dynb {
@@ -292,6 +293,43 @@ int launch_softmax_xent(int dtype, const float* logits, int64_t ldz, const int32
                                        (hipStream_t)stream, logits, ldz, y, C, (T*)dz, ldd,
                                        ld_cols, rowloss, s));
   return ok("softmax_xent");
+}
+
+// The same from the row-major gradient dy [rows][ld] (bf16): one workgroup per (64 features,
+// worker); 8 lanes cover the 128 bytes of a row, 32 row-lanes walk the worker's rows, the
+// partial sums meet in a fixed order.
+__global__ __launch_bounds__(256) void bias_grad_rows_kernel(const bf16* __restrict__ dy, int64_t ld,
+                                                             int N, float* __restrict__ grads,
+                                                             int64_t group_stride, Segs s) {
+  __shared__ float red[4][64];
+  const int cg = threadIdx.x & 7, rl = threadIdx.x >> 3;
+  const int c0 = blockIdx.x * 64 + cg * 8, k = blockIdx.y;
+  const int r0 = s.off[k], n = s.off[k + 1] - r0;
+  float acc[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+  for (int r = rl; r < n; r += 32) {
+    float v[8];
+    unpack8(load8(dy + (int64_t)(r0 + r) * ld + c0), v);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] += v[j];
+  }
+  sum_over_rows(acc, red);
+  if (rl == 0) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (c0 + j < N) grads[(int64_t)k * group_stride + c0 + j] = acc[j];
+  }
+}
+
+int launch_bias_grad_rows(const void* dy, int64_t ld, int N, float* grads, int64_t group_stride,
+                          const Segs& s, void* stream) {
+  if (N == 0) return DYNB_OK;
+  if (ld % 64 || ld < N) return fail(DYNB_ERR_BADARG, "bias_grad_rows: the row pitch must cover whole 64-feature blocks");
+  Timed t(KC_BIAS_GRAD, stream, 0, (double)s.off[s.K] * N * 2);
+  hipLaunchKernelGGL(bias_grad_rows_kernel, dim3((unsigned)(ld / 64), s.K), dim3(256), 0,
+                     (hipStream_t)stream, (const bf16*)dy, ld, N, grads, group_stride, s);
+  return ok("bias_grad_rows");
 }
 
 int launch_bias_grad(int dtype, const void* dyT, int64_t ld, int N, float* grads,

@@ -114,7 +114,8 @@ size_t carve(dynb_model* m, void* base, int max_batch, int max_workers) {
       L.bn_rstd = (float*)c.take((size_t)max_workers * L.n_out * 4);
     }
     if (L.has_params) {
-      if (L.kind == DYNB_LAYER_DENSE) {   // (a convolution's weight gradient reads the row-major tensors)
+      if (L.kind == DYNB_LAYER_DENSE && m->dtype != DYNB_BF16) {   // (bf16 weight gradients read the
+                                                                   // row-major tensors themselves)
         L.capT = padded_cap(max_batch, L.hw_out, max_workers);
         L.inT = c.take((size_t)L.wg_rows * L.capT * es);
         L.dyT = c.take((size_t)L.n_out * L.capT * es);
@@ -458,8 +459,10 @@ int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const 
       if (last) { g.Cf = m->logits; g.ldcf = L.ld_out; }
       else { g.C = L.out; g.ldc = L.ld_out; }
       if (L.kind == DYNB_LAYER_DENSE) {
-        rc = launch_transpose(dt, in_act(l), L.ld_in, L.n_in, L.inT, L.capT, segs[l], stream);
-        if (rc) return rc;
+        if (dt != DYNB_BF16) {
+          rc = launch_transpose(dt, in_act(l), L.ld_in, L.n_in, L.inT, L.capT, segs[l], stream);
+          if (rc) return rc;
+        }
         g.A = in_act(l); g.lda = L.ld_in;
         g.B = L.Wt; g.ldb = L.ld_in;
         g.K = (int)L.ld_in;
@@ -491,7 +494,7 @@ int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const 
                                L.dy, L.ld_out, stream);
         if (rc) return rc;
       }
-      if (L.kind == DYNB_LAYER_DENSE) {
+      if (L.kind == DYNB_LAYER_DENSE && dt != DYNB_BF16) {
         rc = launch_transpose(dt, dyv[l], L.ld_out, L.n_out, L.dyT, L.capT, segs[l], stream);
         if (rc) return rc;
       }
@@ -612,15 +615,22 @@ int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const 
     }
     GemmArgs g = {};
     g.mode = MODE_WGRAD;
-    g.A = L.dyT; g.lda = L.capT; g.M = L.n_out;
-    g.B = L.inT; g.ldb = L.capT; g.N = L.wg_rows;
+    if (dt == DYNB_BF16) {   // the row-major tensors themselves, reduced over each worker's rows
+      g.A = dyv[l]; g.lda = L.ld_out;
+      g.B = in_act(l); g.ldb = L.ld_in;
+      g.rowmajor = 1;
+    } else {
+      g.A = L.dyT; g.lda = L.capT;
+      g.B = L.inT; g.ldb = L.capT;
+    }
+    g.M = L.n_out; g.N = L.wg_rows;
     g.Cf = grads + L.w_off; g.ldcf = L.n_out;
     g.group_stride = m->P_pad;
     g.alg_flops = 2.0 * B * L.hw_out * L.wg_rows * L.n_out;
     g.alg_bytes = (double)K * L.wg_rows * L.n_out * 4 + (double)B * L.hw_out * (L.wg_rows + L.n_out) * es;
     int deepest = 0;
     for (int k = 0; k < K; ++k) {
-      const int d = segs[l].poff[k + 1] - segs[l].poff[k];
+      const int d = dt == DYNB_BF16 ? segs[l].off[k + 1] - segs[l].off[k] : segs[l].poff[k + 1] - segs[l].poff[k];
       deepest = d > deepest ? d : deepest;
     }
     int split = (deepest + 255) / 256;               // chunks of at least eight 32-deep stages
@@ -646,7 +656,10 @@ int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const 
                                grads + L.w_off, m->P_pad, K, stream);
       if (rc) return rc;
     }
-    rc = launch_bias_grad(dt, L.dyT, L.capT, L.n_out, grads + L.b_off, m->P_pad, segs[l], stream);
+    if (dt == DYNB_BF16)
+      rc = launch_bias_grad_rows(dyv[l], L.ld_out, L.n_out, grads + L.b_off, m->P_pad, segs[l], stream);
+    else
+      rc = launch_bias_grad(dt, L.dyT, L.capT, L.n_out, grads + L.b_off, m->P_pad, segs[l], stream);
     if (rc) return rc;
     if (agg) {
       const int64_t nw = (int64_t)L.wg_rows * L.n_out;
