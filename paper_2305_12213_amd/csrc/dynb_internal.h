@@ -77,9 +77,11 @@ enum { MODE_FWD = 0, MODE_DGRAD = 1, MODE_WGRAD = 2 };
 //           optional); C[i*ldc + j] = T(v).  With `addend` (bf16 only: the gradient that reaches
 //           the same tensor over a residual branch) acc is first rounded to T and
 //           addend[i*ldadd + j] added, then the mask is applied.
-//   WGRAD : one group per worker g: operands start at column poff[g], depth
-//           poff[g+1]-poff[g]; i = output feature, j = input feature;
-//           Cf[g*group_stride + j*ldcf + i] = acc.  (`rowmajor`: see the field.)
+//   WGRAD : one group per worker g; i = output feature, j = input feature;
+//           Cf[g*group_stride + j*ldcf + i] = acc.  fp32: A = dy^T, B = input^T (features x
+//           padded rows), operands start at column poff[g], depth poff[g+1]-poff[g].  bf16:
+//           A = dy and B = the input as they are, ROW-MAJOR [batch rows][lda / ldb]; worker g
+//           owns rows [off[g], off[g+1]) (no transposed copies).
 struct GemmArgs {
   const void* A; int64_t lda; int M;   // rows of A  (i)
   const void* B; int64_t ldb; int N;   // rows of B  (j)
@@ -92,9 +94,6 @@ struct GemmArgs {
   const void* addend; int64_t ldadd;   // DGRAD, bf16: see above
   int64_t group_stride;
   int groups_per_block;                // WGRAD, bf16 kernel: workers streamed by one workgroup
-  // WGRAD, bf16 only: A and B are the ROW-MAJOR tensors, A = dy [batch rows][lda], B = the layer
-  // input [batch rows][ldb]; worker g owns rows [off[g], off[g+1]) (no padded transposed copies)
-  int rowmajor;
   // Implicit-GEMM gather of operand A for a 3x3 convolution with zero padding 1 (bf16 only).
   // conv == 0: A is a plain matrix.  conv == 1 (forward): row i is output pixel (n, y, x) of a
   // row_h x row_w grid and reduction index k = (kh*3 + kw)*cp + c reads channel c of source

@@ -76,7 +76,8 @@ __device__ inline void tile_of_block(int pid, int tiles_i, int tiles_j, int& ti,
   tj = r / rows;
 }
 
-// 16 bytes of zeros: lanes whose reduction column lies past a worker's depth fetch this
+// 16 bytes of zeros: lanes whose reduction row lies past a worker's rows (weight gradient), or
+// whose tap lies outside the image (gathered operand), fetch this
 // instead of a neighbour's data (an LDS-direct load cannot be predicated to zero).
 __device__ uint4 g_zero_granule[1];
 
@@ -135,16 +136,17 @@ struct PatchArea<0> {
 // S = number of LDS stage buffers (ring).
 // AGG (weight gradient only): the workgroup also accumulates sum_g lam[g] * tile_g in registers
 // and writes it to p.agg; it then owns all workers of its tile and walks them in ascending order.
-// RM (weight gradient only): the operands are the row-major tensors themselves, A = dy
+// Weight gradient (RM below): the operands are the row-major tensors themselves, A = dy
 // [rows][lda] and B = the layer input [rows][ldb], the reduction runs over their ROWS (worker g
 // owns rows [off[g], off[g+1])), and a stage holds 32 rows x BM (BN) features as they lie in
 // memory; MFMA operands are fetched with the LDS transpose read (see conv_wgrad.hip for its
 // lane layout).  No transposed copies of the activations are needed.
-template <int BM, int BN, int WM, int WN, int MODE, bool GATHER, int S, bool AGG = false, bool RM = false>
+template <int BM, int BN, int WM, int WN, int MODE, bool GATHER, int S, bool AGG = false>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Segs segs) {
+  constexpr bool RM = MODE == MODE_WGRAD;
   static_assert(!AGG || MODE == MODE_WGRAD, "aggregation belongs to the weight gradient");
-  static_assert(!RM || (MODE == MODE_WGRAD && !GATHER && (BM == 256 || BM == 128) && (BN == 256 || BN == 128)),
-                "row-major operands: weight gradient, 128 or 256 features per tile side");
+  static_assert(!RM || (!GATHER && (BM == 256 || BM == 128) && (BN == 256 || BN == 128)),
+                "weight gradient: plain operands, 128 or 256 features per tile side");
   constexpr int NW = WM * WN;
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
   constexpr int LA = BM / 16 / NW, LB = BN / 16 / NW;   // 16-row blocks per wave and stage
@@ -170,16 +172,14 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave % WM, wn = wave / WM;
 
-  auto col0_of = [&](int g) {   // first reduction column of a group
+  auto col0_of = [&](int g) {   // first reduction row of a group (weight gradient)
     if (MODE != MODE_WGRAD) return 0;
-    const int* first = RM ? segs.off : segs.poff;
-    return split > 1 ? first[g / split] + (g % split) * p.chunk : first[g];
+    return split > 1 ? segs.off[g / split] + (g % split) * p.chunk : segs.off[g];
   };
   auto depth_of = [&](int g) {
     if (MODE != MODE_WGRAD) return p.K;
-    const int* first = RM ? segs.off : segs.poff;
-    if (split == 1) return first[g + 1] - first[g];
-    const int w = g / split, left = first[w + 1] - first[w] - (g % split) * p.chunk;
+    if (split == 1) return segs.off[g + 1] - segs.off[g];
+    const int w = g / split, left = segs.off[w + 1] - segs.off[w] - (g % split) * p.chunk;
     return left < 0 ? 0 : (left < p.chunk ? left : p.chunk);
   };
   auto tile_base = [&](int g) -> float* {   // where a group's tile goes
@@ -211,8 +211,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
   // global -> LDS, asynchronously and without registers: one instruction moves 16 rows x 64
   // bytes; lane l lands at LDS slot l of the block, i.e. row l/4, physical granule l%4, which
   // holds logical granule (l%4) ^ ((row/2) & 3) (conflict-free 16-byte fragment reads).  Rows
-  // past the matrix edge are clamped (their products are never stored).  Reduction columns
-  // past a worker's depth fetch zeros.
+  // past the matrix edge are clamped (their products are never stored).  (Forward and input
+  // gradient; the weight gradient's row-major stages are laid out further down.)
   const int lrow = lane >> 2, lgran = (lane & 3) ^ ((lane >> 3) & 3);
   const char* Ab = (const char*)p.A;
   const char* Bb = (const char*)p.B;
@@ -296,12 +296,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
       }
       return;
     }
-    bool live = true;
-    uint32_t kbyte = (uint32_t)k0 * 2;
-    if (MODE == MODE_WGRAD) {
-      live = k0 + lgran * 8 < c.depth;
-      kbyte += (uint32_t)c.col0 * 2;
-    }
+    const uint32_t kbyte = (uint32_t)k0 * 2;
     int kh = 0, kw = 0, ch = 0;
     bool tap_ok = false;
     if (gfast) {
@@ -345,13 +340,13 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
         const int64_t pix = (int64_t)offA[u] + sy * p.src_w + sx;
         src = ok ? (const void*)(Ab + (pix * p.lda + ch) * 2) : (const void*)g_zero_granule;
       } else {
-        src = live ? (const void*)(Ab + offA[u] + kbyte) : (const void*)g_zero_granule;
+        src = (const void*)(Ab + offA[u] + kbyte);
       }
       async_copy_1k(src, ldsA + (uint32_t)((buf * BM * GPR + (wave + NW * u) * 64) * 16));
     }
 #pragma unroll
     for (int u = 0; u < LB; ++u) {
-      const void* src = live ? (const void*)(Bb + offB[u] + kbyte) : (const void*)g_zero_granule;
+      const void* src = (const void*)(Bb + offB[u] + kbyte);
       async_copy_1k(src, ldsB + (uint32_t)((buf * BN * GPR + (wave + NW * u) * 64) * 16));
     }
   };
@@ -797,31 +792,14 @@ void launch_bf16(GemmArgs a, const Segs& s, hipStream_t st) {
   }
 }
 
-// Weight gradients straight from the row-major activations (RM): the same three tile shapes.
-template <int BM, int BN, int S>
-void launch_bf16_wgrad_rm(GemmArgs a, const Segs& s, hipStream_t st) {
-  const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
-  const int n_groups = s.K * (a.split > 1 ? a.split : 1);
-  int chunks = (256 + tiles - 1) / tiles;
-  if (chunks > n_groups) chunks = n_groups;
-  a.groups_per_block = (n_groups + chunks - 1) / chunks;
-  const int gy = (n_groups + a.groups_per_block - 1) / a.groups_per_block;
-  hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, 2, 2, MODE_WGRAD, false, S, false, true>), dim3(tiles, gy, 1),
-                     dim3(256), 0, st, a, s);
-}
-
 // Weight gradient with the weighted aggregation folded in: 256 x 128 tiles leave room for a
 // second set of accumulators; every workgroup takes all workers of its tile.
 constexpr int AGG_BM = 256, AGG_BN = 128;
 void launch_bf16_wgrad_agg(GemmArgs a, const Segs& s, hipStream_t st) {
   const int tiles = ((a.M + AGG_BM - 1) / AGG_BM) * ((a.N + AGG_BN - 1) / AGG_BN);
   a.groups_per_block = s.K;
-  if (a.rowmajor)
-    hipLaunchKernelGGL((gemm_bf16_kernel<AGG_BM, AGG_BN, 2, 2, MODE_WGRAD, false, 5, true, true>), dim3(tiles),
-                       dim3(256), 0, st, a, s);
-  else
-    hipLaunchKernelGGL((gemm_bf16_kernel<AGG_BM, AGG_BN, 2, 2, MODE_WGRAD, false, 5, true>), dim3(tiles),
-                       dim3(256), 0, st, a, s);
+  hipLaunchKernelGGL((gemm_bf16_kernel<AGG_BM, AGG_BN, 2, 2, MODE_WGRAD, false, 5, true>), dim3(tiles),
+                     dim3(256), 0, st, a, s);
 }
 
 // implicit-GEMM convolution (operand A gathered).  The reduction is short (9 x channels), so a
@@ -886,8 +864,6 @@ int launch_gemm(int dtype, const GemmArgs& a, const Segs& s, void* stream) {
     return fail(DYNB_ERR_BADARG, "gemm: operands must have 16-byte aligned rows");
   if (a.addend && (dtype != DYNB_BF16 || a.mode != MODE_DGRAD))
     return fail(DYNB_ERR_UNSUPPORTED, "gemm: an addend belongs to a bf16 input gradient");
-  if (a.rowmajor && dtype != DYNB_BF16)
-    return fail(DYNB_ERR_UNSUPPORTED, "gemm: row-major weight-gradient operands are a bf16 path");
   const int groups = a.mode == MODE_WGRAD ? s.K : 1;
   const KClass cls = a.mode == MODE_FWD ? KC_GEMM_FWD : a.mode == MODE_DGRAD ? KC_GEMM_DGRAD
                                                                               : KC_GEMM_WGRAD;
@@ -903,13 +879,7 @@ int launch_gemm(int dtype, const GemmArgs& a, const Segs& s, void* stream) {
     // large tiles have the best LDS-traffic-to-MFMA ratio; small problems need more, smaller
     // tiles to occupy 256 compute units
     const int64_t big = (int64_t)((a.M + 255) / 256) * ((a.N + 255) / 256);
-    if (a.rowmajor) {
-      if (a.mode != MODE_WGRAD) return fail(DYNB_ERR_BADARG, "gemm: row-major operands belong to the weight gradient");
-      if (big >= 192)
-        launch_bf16_wgrad_rm<256, 256, 4>(a, s, (hipStream_t)stream);
-      else
-        launch_bf16_wgrad_rm<128, 128, 8>(a, s, (hipStream_t)stream);
-    } else if (big >= 192)
+    if (big >= 192)
       launch_bf16<256, 256, 2, 2, 5, 4>(a, s, (hipStream_t)stream);   // 160 KB / 128 + 18 KB of LDS
     else
       launch_bf16<128, 128, 2, 2, 8, 8>(a, s, (hipStream_t)stream);

@@ -618,7 +618,6 @@ int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const 
     if (dt == DYNB_BF16) {   // the row-major tensors themselves, reduced over each worker's rows
       g.A = dyv[l]; g.lda = L.ld_out;
       g.B = in_act(l); g.ldb = L.ld_in;
-      g.rowmajor = 1;
     } else {
       g.A = L.dyT; g.lda = L.capT;
       g.B = L.inT; g.ldb = L.capT;
