@@ -94,6 +94,10 @@ struct GemmArgs {
   const void* addend; int64_t ldadd;   // DGRAD, bf16: see above
   int64_t group_stride;
   int groups_per_block;                // WGRAD, bf16 kernel: workers streamed by one workgroup
+  // WGRAD, bf16, unsplit, optional: also write the bias gradient bias_grad[g*group_stride + i] =
+  // sum over worker g's rows of A[row][i] (formed in the same kernel as one more column of the
+  // product; its weighted aggregate is left to the pass over the small tensors)
+  float* bias_grad;
   // Implicit-GEMM gather of operand A for a 3x3 convolution with zero padding 1 (bf16 only).
   // conv == 0: A is a plain matrix.  conv == 1 (forward): row i is output pixel (n, y, x) of a
   // row_h x row_w grid and reduction index k = (kh*3 + kw)*cp + c reads channel c of source

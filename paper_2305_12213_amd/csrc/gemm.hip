@@ -416,6 +416,30 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
         for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
   };
   clear_acc();
+  // Weight gradient, optional: the bias gradient db_g[i] = sum over worker g's rows of dy[.][i]
+  // rides along as one more column of the product -- the waves that own the tile column j0 = 0
+  // multiply their dy fragments with ones.  Every column of rsum holds the same sums; lanes 0 and
+  // 32 (column 0) write them out.
+  const bool sums_rows = RM && p.bias_grad != nullptr && j0 == 0 && wn == 0;
+  typedef short s16x8 __attribute__((ext_vector_type(8)));
+  const s16x8 ones_bits = {0x3f80, 0x3f80, 0x3f80, 0x3f80, 0x3f80, 0x3f80, 0x3f80, 0x3f80};
+  const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_bits);
+  f32x16 rsum[TM];   // (unused and optimised away outside the weight gradient)
+#pragma unroll
+  for (int a = 0; a < TM; ++a)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) rsum[a][v] = 0.f;
+  // writes src (or zeros) as the bias gradient at `dst` (this tile's rows), from column 0
+  auto store_row_sums = [&](float* dst, const f32x16 (&src)[TM], bool zeros) {
+    if ((lane & 31) != 0) return;
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int i = i0 + wm * (BM / WM) + a * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v & 3);
+        if (i < p.M) dst[i] = zeros ? 0.f : src[a][v];
+      }
+  };
   auto mma = [&](int set) {
 #pragma unroll
     for (int a = 0; a < TM; ++a)
@@ -428,6 +452,13 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
           acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][a], fb[set][b], acc[a][b], 0, 0, 0);
         else
           acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][b], fa[set][a], acc[a][b], 0, 0, 0);
+    if constexpr (RM) {
+      if (sums_rows) {             // (uniform per wave) the bias gradient: dy against ones
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+          rsum[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][a], ones, rsum[a], 0, 0, 0);
+      }
+    }
   };
 
   // Accumulator element v of lane l sits at (8*(v/4) + 4*(l/32) + v%4, l%32) of its 32x32 tile,
@@ -517,6 +548,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
 
   // A worker without rows contributes a zero tile (not unrolled: it is rare and tiny).
   auto store_zero = [&](int g) {
+    if constexpr (RM) {
+      if (sums_rows) store_row_sums(p.bias_grad + (int64_t)g * p.group_stride, rsum, true);
+    }
     float* Cg = tile_base(g);
     const bool vec_ok = (p.ldcf & 3) == 0 && (((uintptr_t)Cg) & 15) == 0;
     const int rr = lane >> 3, rc = (lane & 7) * 4;
@@ -607,6 +641,15 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
       }
       store_tile(tile_base(gid(g)), acc);
       clear_acc();
+      if constexpr (RM) {
+        if (sums_rows) {
+          store_row_sums(p.bias_grad + (int64_t)gid(g) * p.group_stride, rsum, false);
+#pragma unroll
+          for (int a = 0; a < TM; ++a)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) rsum[a][v] = 0.f;
+        }
+      }
       for (stored = g + 1; stored < (later ? ng.g : g_hi); ++stored) store_zero(gid(stored));
     }
     cc = ng;
@@ -862,6 +905,8 @@ int launch_gemm(int dtype, const GemmArgs& a, const Segs& s, void* stream) {
   const int gran = 16 / es;
   if ((a.lda % gran) || (a.ldb % gran) || ((uintptr_t)a.A & 15) || ((uintptr_t)a.B & 15))
     return fail(DYNB_ERR_BADARG, "gemm: operands must have 16-byte aligned rows");
+  if (a.bias_grad && (dtype != DYNB_BF16 || a.mode != MODE_WGRAD || a.split > 1))
+    return fail(DYNB_ERR_UNSUPPORTED, "gemm: the bias gradient rides along with an unsplit bf16 weight gradient only");
   if (a.addend && (dtype != DYNB_BF16 || a.mode != MODE_DGRAD))
     return fail(DYNB_ERR_UNSUPPORTED, "gemm: an addend belongs to a bf16 input gradient");
   const int groups = a.mode == MODE_WGRAD ? s.K : 1;

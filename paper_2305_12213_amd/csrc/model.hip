@@ -648,6 +648,9 @@ int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const 
       g.agg = agg + L.w_off;
       for (int k = 0; k < K; ++k) g.lam[k] = lam.w[k];
     }
+    // bf16, unsplit: the bias gradient is formed by the same kernel
+    const bool bias_inside = dt == DYNB_BF16 && split <= 1;
+    if (bias_inside) g.bias_grad = grads + L.b_off;
     rc = launch_gemm(dt, g, segs[l], stream);
     if (rc) return rc;
     if (split > 1) {
@@ -655,7 +658,9 @@ int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const 
                                grads + L.w_off, m->P_pad, K, stream);
       if (rc) return rc;
     }
-    if (dt == DYNB_BF16)
+    if (bias_inside)
+      rc = DYNB_OK;
+    else if (dt == DYNB_BF16)
       rc = launch_bias_grad_rows(dyv[l], L.ld_out, L.n_out, grads + L.b_off, m->P_pad, segs[l], stream);
     else
       rc = launch_bias_grad(dt, L.dyT, L.capT, L.n_out, grads + L.b_off, m->P_pad, segs[l], stream);
