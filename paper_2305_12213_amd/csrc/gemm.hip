@@ -6,6 +6,8 @@
 // is compiled per size.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "dynb_internal.h"
 
 namespace dynb {
@@ -492,12 +494,13 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
 #pragma unroll
       for (int t = 0; t < 4; ++t) o[t] = *(const f32x4*)&patch[(rr + 8 * t) * SPITCH + rc];
     };
-    if (interior) {
-      // Software pipeline over the sub-tiles.  LDS operations of one wave execute in order, so
-      // sub-tile n+1 may be written to the patch as soon as the reads of sub-tile n are
-      // *issued*; its read-back is issued before the global stores of sub-tile n, which
-      // therefore wait only for data requested a whole sub-tile earlier.  Without this the
-      // tile store is a chain of exposed LDS latencies (one per store instruction).
+    // Software pipeline over the sub-tiles.  LDS operations of one wave execute in order, so
+    // sub-tile n+1 may be written to the patch as soon as the reads of sub-tile n are *issued*;
+    // its read-back is issued before the global stores of sub-tile n, which therefore wait only
+    // for data requested a whole sub-tile earlier.  Without this the tile store is a chain of
+    // exposed LDS latencies (one per store instruction).  `checked`: a tile on the matrix edge,
+    // one predicate per store.
+    auto pipelined = [&](auto checked) {
       f32x4 o[2][4];
       put(0, 0);
       __builtin_amdgcn_wave_barrier();
@@ -514,10 +517,28 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
         __builtin_amdgcn_sched_barrier(0);
         float* d = base + (int64_t)(4 * b) * row8 + a * 32;
 #pragma unroll
-        for (int t = 0; t < 4; ++t) __builtin_nontemporal_store(o[n & 1][t], (f32x4*)(d + t * row8));
+        for (int t = 0; t < 4; ++t) {
+          if constexpr (decltype(checked)::value) {
+            if (ib0 + a * 32 + 3 < p.M && jb0 + b * 32 + 8 * t < p.N)
+              __builtin_nontemporal_store(o[n & 1][t], (f32x4*)(d + t * row8));
+          } else {
+            __builtin_nontemporal_store(o[n & 1][t], (f32x4*)(d + t * row8));
+          }
+        }
         __builtin_amdgcn_sched_barrier(0);
       }
+    };
+    if (interior) {
+      pipelined(std::false_type{});
       return;
+    }
+    // (not in the 256 x 128 aggregating kernel, which measurably slows down with the extra code;
+    // its edge tiles take the plain loop below)
+    if constexpr (!(AGG && BM == 256)) {
+      if (vec_ok && (p.M & 3) == 0) {   // a lane's four floats are inside or outside together
+        pipelined(std::true_type{});
+        return;
+      }
     }
 #pragma unroll
     for (int b = 0; b < TN; ++b)
@@ -836,13 +857,20 @@ void launch_bf16(GemmArgs a, const Segs& s, hipStream_t st) {
 }
 
 // Weight gradient with the weighted aggregation folded in: 256 x 128 tiles leave room for a
-// second set of accumulators; every workgroup takes all workers of its tile.
-constexpr int AGG_BM = 256, AGG_BN = 128;
+// second set of accumulators; every workgroup takes all workers of its tile.  A matrix with too
+// few such tiles for the 256 compute units takes 128 x 128 tiles.
+constexpr int AGG_BM = 256, AGG_BN = 128, AGG_SMALL = 128;
+int64_t tiles_of(const GemmArgs& a, int bm, int bn) {
+  return (int64_t)((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn);
+}
 void launch_bf16_wgrad_agg(GemmArgs a, const Segs& s, hipStream_t st) {
-  const int tiles = ((a.M + AGG_BM - 1) / AGG_BM) * ((a.N + AGG_BN - 1) / AGG_BN);
   a.groups_per_block = s.K;
-  hipLaunchKernelGGL((gemm_bf16_kernel<AGG_BM, AGG_BN, 2, 2, MODE_WGRAD, false, 5, true>), dim3(tiles),
-                     dim3(256), 0, st, a, s);
+  if (tiles_of(a, AGG_BM, AGG_BN) >= 256)
+    hipLaunchKernelGGL((gemm_bf16_kernel<AGG_BM, AGG_BN, 2, 2, MODE_WGRAD, false, 5, true>),
+                       dim3((unsigned)tiles_of(a, AGG_BM, AGG_BN)), dim3(256), 0, st, a, s);
+  else
+    hipLaunchKernelGGL((gemm_bf16_kernel<AGG_SMALL, AGG_SMALL, 2, 2, MODE_WGRAD, false, 8, true>),
+                       dim3((unsigned)tiles_of(a, AGG_SMALL, AGG_SMALL)), dim3(256), 0, st, a, s);
 }
 
 // implicit-GEMM convolution (operand A gathered).  The reduction is short (9 x channels), so a
@@ -892,9 +920,8 @@ void launch_f32(const GemmArgs& a, const Segs& s, int groups, hipStream_t st) {
 
 bool gemm_fuses_aggregate(int dtype, const GemmArgs& a, const Segs& s) {
   // enough tiles to occupy the compute units without splitting the workers over workgroups
-  const int64_t tiles = (int64_t)((a.M + AGG_BM - 1) / AGG_BM) * ((a.N + AGG_BN - 1) / AGG_BN);
-  return dtype == DYNB_BF16 && a.mode == MODE_WGRAD && !a.conv && a.split <= 1 && tiles >= 256 &&
-         s.K <= DYNB_MAX_WORKERS;
+  return dtype == DYNB_BF16 && a.mode == MODE_WGRAD && !a.conv && a.split <= 1 &&
+         tiles_of(a, AGG_SMALL, AGG_SMALL) >= 256 && s.K <= DYNB_MAX_WORKERS;
 }
 
 int launch_gemm(int dtype, const GemmArgs& a, const Segs& s, void* stream) {

@@ -127,13 +127,15 @@ def test_update_argument_checks():
 
 
 def test_forward_backward_aggregate_equals_the_two_call_form():
-    # small models (aggregate by a pass over the written gradients) and one whose weight
-    # gradients are large enough for the in-kernel sum (>= 256 tiles of 256 x 128)
+    # small models (aggregate by a pass over the written gradients), one whose weight gradients
+    # are large enough for the in-kernel sum on 256 x 128 tiles (>= 256 of them), and one that
+    # takes the in-kernel sum on 128 x 128 tiles (264 of them, edge tiles in both directions)
     import torch
     cases = [(synth.mlp_spec([96, 80, 12], "f32"), [13, 0, 7, 19, 1]),
              (synth.mlp_spec([200, 136, 10], "bf16"), [5, 60, 0, 31]),
              (SPECS[3][1](), [3, 9, 0, 4]),
-             (synth.mlp_spec([2500, 4200, 16], "bf16"), [700, 1, 0, 257, 66])]
+             (synth.mlp_spec([2500, 4200, 16], "bf16"), [700, 1, 0, 257, 66]),
+             (synth.mlp_spec([4100, 1000, 16], "bf16"), [300, 2, 0, 129, 40])]
     for spec, b in cases:
         G, K = sum(b), len(b)
         p0 = synth.init_params(spec, "he", 11)
