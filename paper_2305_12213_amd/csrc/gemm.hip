@@ -94,6 +94,14 @@ __device__ inline void async_copy_1k(const void* src, uint32_t lds_base) {
                : "memory", "m0");
 }
 
+// Staged operand tiles (forward / input gradient): rows of 64 bytes = four 16-byte granules;
+// logical granule g of row r sits at physical granule g ^ swizzle_of_row(r).  The LDS has 64
+// banks of 4 bytes, so a 16-byte fragment read serves 16 lanes per clock and four consecutive
+// rows fill the 256 bytes of one pass over the banks: rows r, r+4, r+8, r+12 need four different
+// swizzles (bits 2 and 3 of the row, swapped so that rows r and r+4 differ in the upper bit --
+// conflict-free also if the hardware pairs lanes l and l+32, which read granules g and g^1).
+__device__ inline int swizzle_of_row(int r) { return (((r >> 2) & 1) << 1) | ((r >> 3) & 1); }
+
 // Position in the stream of 32-deep stages that one workgroup walks: stage `kt` of group `g`.
 // FWD/DGRAD have one group; WGRAD has one group per worker, and a workgroup runs through its
 // workers back to back so that the load pipeline never drains between them.
@@ -212,10 +220,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
 
   // global -> LDS, asynchronously and without registers: one instruction moves 16 rows x 64
   // bytes; lane l lands at LDS slot l of the block, i.e. row l/4, physical granule l%4, which
-  // holds logical granule (l%4) ^ ((row/2) & 3) (conflict-free 16-byte fragment reads).  Rows
+  // holds logical granule (l%4) ^ swizzle_of_row(row) (conflict-free 16-byte fragment reads).  Rows
   // past the matrix edge are clamped (their products are never stored).  (Forward and input
   // gradient; the weight gradient's row-major stages are laid out further down.)
-  const int lrow = lane >> 2, lgran = (lane & 3) ^ ((lane >> 3) & 3);
+  const int lrow = lane >> 2, lgran = (lane & 3) ^ swizzle_of_row(lrow);
   const char* Ab = (const char*)p.A;
   const char* Bb = (const char*)p.B;
   uint32_t offA[LA], offB[LB];
@@ -356,7 +364,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
   // LDS -> MFMA fragments: lane reads row (lane & 31) of a 32-row block, granule 2*kk + lane/32
   const int frow_a = (wm * (BM / WM) + (lane & 31)) * GPR;
   const int frow_b = (wn * (BN / WN) + (lane & 31)) * GPR;
-  const int fsw = ((lane & 31) >> 1) & 3, fhi = lane >> 5;
+  const int fsw = swizzle_of_row(lane & 31), fhi = lane >> 5;
   bf16x8 fa[2][TM], fb[2][TN];   // two register sets, alternating per k-step
   // RM: 16 lanes fetch 4 reduction rows x 16 features with two transpose reads (lane r supplies
   // the address of features 4(r%4).. of row r/4 and receives feature r of the 4 rows)
