@@ -9,8 +9,9 @@
 // operand from that tile at a pixel offset.  Only the weights are streamed per tap (8 KB).
 //
 // LDS rows are 128 bytes (64 channels of a pixel, or of a weight row); the 16-byte granule g of
-// row r sits at slot g ^ (r & 7), so that the 16-byte operand reads of 8 neighbouring rows
-// cover all banks.  Copies are asynchronous (global -> LDS without registers), completion is
+// row r sits at slot g ^ slot_swizzle(r).  A 16-byte operand read serves 16 lanes = 16
+// neighbouring rows per clock (64 banks of 4 bytes, two rows per pass over the banks): the
+// eight rows of equal parity among them need eight different swizzles.  Copies are asynchronous (global -> LDS without registers), completion is
 // tracked with vmcnt by hand, as in gemm.hip.
 #include <hip/hip_runtime.h>
 
@@ -29,6 +30,10 @@ constexpr int HALO_W = 34, HALO_H = 10, HALO_PIX = HALO_W * HALO_H;   // 340 pix
 constexpr int HALO_COPIES = 44;             // 1 KB each (8 pixels): 11 per wave, 352 pixel slots
 constexpr int WSTAGES = 3;                  // ring of weight stages (one tap x 64 channels: 8 KB)
 constexpr int EP = 64 + 4;                  // epilogue patch row pitch in floats
+
+// bits 1..3 of the row, rotated (rows r and r+8 differ in the lowest bit, rows 2 apart in the
+// upper two: also conflict-free if lanes l and l+32, which read granules g and g^1, are paired)
+__device__ inline int slot_swizzle(int r) { return (((r >> 1) & 3) << 1) | ((r >> 3) & 1); }
 
 struct ConvDirectArgs {
   const bf16* src; int lds;          // [images * H * 32][lds]
@@ -55,14 +60,14 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(ConvDirectArgs p) {
   const uint32_t lds_w = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)&wring[0][0];
 
   // ---- copy plans.  Halo copy c = wave + 4u moves halo pixels [8c, 8c+8): this lane pixel
-  // 8c + lane/8, LDS slot lane%8, i.e. logical granule (lane%8) ^ (pixel & 7).
+  // 8c + lane/8, LDS slot lane%8, i.e. logical granule (lane%8) ^ slot_swizzle(pixel).
   uint32_t hoff[11];                 // byte offset of the lane's granule in src, ~0u: zeros
 #pragma unroll
   for (int u = 0; u < 11; ++u) {
     const int pi = (wave + 4 * u) * 8 + (lane >> 3);
     const int hr = pi / HALO_W, hx = pi - hr * HALO_W;
     const int sy = y0 + hr - 1, sx = hx - 1;
-    const int lg = (lane & 7) ^ (pi & 7);
+    const int lg = (lane & 7) ^ slot_swizzle(pi);
     const bool ok = pi < HALO_PIX && sy >= 0 && sy < p.H && sx >= 0 && sx < 32;
     hoff[u] = ok ? (uint32_t)((((img * p.H + sy) * 32 + sx) * p.lds + lg * 8) * 2) : ~0u;
   }
@@ -70,9 +75,10 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(ConvDirectArgs p) {
   uint32_t woff[2];
 #pragma unroll
   for (int u = 0; u < 2; ++u) {
-    int j = j0 + (wave + 4 * u) * 8 + (lane >> 3);
+    const int row = (wave + 4 * u) * 8 + (lane >> 3);
+    int j = j0 + row;
     j = j < p.N ? j : p.N - 1;       // rows past the last channel repeat it (never stored)
-    const int lg = (lane & 7) ^ ((lane >> 3) & 7);
+    const int lg = (lane & 7) ^ slot_swizzle(row);
     woff[u] = (uint32_t)((j * p.ldw + lg * 8) * 2);
   }
   const char* srcb = (const char*)p.src;
@@ -96,10 +102,10 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(ConvDirectArgs p) {
   // A: lane reads pixel (row, x = lane%32) shifted by the tap, granule 2kk + lane/32.
   // B: lane reads weight row b*32 + lane%32.
   const int x = lane & 31, hi = lane >> 5;
-  const uint32_t brow0 = (uint32_t)(x * 128), bsw = (uint32_t)(x & 7);
+  const uint32_t brow0 = (uint32_t)(x * 128), bsw = (uint32_t)slot_swizzle(x);
   auto a_frag = [&](int a, int dy_, int dx_, int kk) {
     const int pi = (2 * wave + a + dy_) * HALO_W + x + dx_;
-    const uint32_t addr = (uint32_t)(pi * 128) + (uint32_t)(((2 * kk + hi) ^ (pi & 7)) * 16);
+    const uint32_t addr = (uint32_t)(pi * 128) + (uint32_t)(((2 * kk + hi) ^ slot_swizzle(pi)) * 16);
     return *(const bf16x8*)((const char*)&halo[0] + addr);
   };
   auto b_frag = [&](int st, int b, int kk) {

@@ -123,6 +123,8 @@ struct GemmArgs {
   // in registers).  Only when gemm_fuses_aggregate() says so.
   float* agg;
   float lam[DYNB_MAX_WORKERS];
+  const void* zeros;   // 16 bytes of zeros in device memory (set by launch_gemm): what copies
+                       // fetch for rows past a worker's last and taps outside an image
 };
 
 int launch_gemm(int dtype, const GemmArgs& a, const Segs& s, void* stream);

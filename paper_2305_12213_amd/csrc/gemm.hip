@@ -9,6 +9,7 @@
 #include <type_traits>
 
 #include "dynb_internal.h"
+#include "lds_async.h"
 
 namespace dynb {
 namespace {
@@ -78,22 +79,6 @@ __device__ inline void tile_of_block(int pid, int tiles_i, int tiles_j, int& ti,
   tj = r / rows;
 }
 
-// 16 bytes of zeros: lanes whose reduction row lies past a worker's rows (weight gradient), or
-// whose tap lies outside the image (gathered operand), fetch this
-// instead of a neighbour's data (an LDS-direct load cannot be predicated to zero).
-__device__ uint4 g_zero_granule[1];
-
-// Asynchronous global -> LDS copy of 64 x 16 bytes: lane l's 16 bytes at `src` land at LDS
-// byte address lds_base + 16*l (lds_base is wave-uniform).  Completion is tracked by vmcnt
-// only; the kernel waits for it explicitly before the barrier that publishes a stage.  It is
-// written as assembly so that the compiler does not order later LDS reads of the *other*
-// stage behind it.
-__device__ inline void async_copy_1k(const void* src, uint32_t lds_base) {
-  const uint32_t base = __builtin_amdgcn_readfirstlane(lds_base);
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(base), "v"(src)
-               : "memory", "m0");
-}
-
 // Staged operand tiles (forward / input gradient): rows of 64 bytes = four 16-byte granules;
 // logical granule g of row r sits at physical granule g ^ swizzle_of_row(r).  The LDS has 64
 // banks of 4 bytes, so a 16-byte fragment read serves 16 lanes per clock and four consecutive
@@ -154,6 +139,7 @@ struct PatchArea<0> {
 template <int BM, int BN, int WM, int WN, int MODE, bool GATHER, int S, bool AGG = false>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Segs segs) {
   constexpr bool RM = MODE == MODE_WGRAD;
+  constexpr bool WEAVE = !GATHER;   // copies placed between the MFMAs (see the stage pipeline)
   static_assert(!AGG || MODE == MODE_WGRAD, "aggregation belongs to the weight gradient");
   static_assert(!RM || (!GATHER && (BM == 256 || BM == 128) && (BN == 256 || BN == 128)),
                 "weight gradient: plain operands, 128 or 256 features per tile side");
@@ -295,13 +281,13 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
 #pragma unroll
       for (int u = 0; u < LA; ++u) {
         const void* src = (k0 + rkA[u] < c.depth && roA[u] != ~0u) ? (const void*)(Ab + rowA + roA[u])
-                                                                   : (const void*)g_zero_granule;
+                                                                   : p.zeros;
         async_copy_1k(src, ldsA + (uint32_t)((buf * BM * GPR + (wave + NW * u) * 64) * 16));
       }
 #pragma unroll
       for (int u = 0; u < LB; ++u) {
         const void* src = (k0 + rkB[u] < c.depth && roB[u] != ~0u) ? (const void*)(Bb + rowB + roB[u])
-                                                                   : (const void*)g_zero_granule;
+                                                                   : p.zeros;
         async_copy_1k(src, ldsB + (uint32_t)((buf * BN * GPR + (wave + NW * u) * 64) * 16));
       }
       return;
@@ -318,7 +304,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
 #pragma unroll
       for (int u = 0; u < LA; ++u) {
         const void* src = (gok[u] >> tap) & 1u ? (const void*)(Ab + (uint32_t)(goff[u] + dbyte))
-                                               : (const void*)g_zero_granule;
+                                               : p.zeros;
         async_copy_1k(src, ldsA + (uint32_t)((buf * BM * GPR + (wave + NW * u) * 64) * 16));
       }
     } else if (GATHER) {
@@ -348,7 +334,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
         }
         ok = ok && sy >= 0 && sy < p.src_h && sx >= 0 && sx < p.src_w;
         const int64_t pix = (int64_t)offA[u] + sy * p.src_w + sx;
-        src = ok ? (const void*)(Ab + (pix * p.lda + ch) * 2) : (const void*)g_zero_granule;
+        src = ok ? (const void*)(Ab + (pix * p.lda + ch) * 2) : p.zeros;
       } else {
         src = (const void*)(Ab + offA[u] + kbyte);
       }
@@ -359,6 +345,27 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
       const void* src = (const void*)(Bb + offB[u] + kbyte);
       async_copy_1k(src, ldsB + (uint32_t)((buf * BN * GPR + (wave + NW * u) * 64) * 16));
     }
+  };
+
+  // One copy of a stage (plain or row-major operands): idx < LA is copy idx of the A operand,
+  // else copy idx - LA of the B operand.  The hot loop places these between the MFMAs.
+  auto copy_one = [&](int buf, const StageCursor& c, int idx) {
+    const int k0 = c.kt * BK;
+    const bool isA = idx < LA;
+    const int u = isA ? idx : idx - LA;
+    const void* src;
+    if constexpr (RM) {
+      const int64_t ld = isA ? p.lda : p.ldb;
+      const uint32_t row = (uint32_t)((int64_t)(c.col0 + k0) * ld * 2);
+      const int rk = isA ? rkA[u] : rkB[u];
+      const uint32_t ro = isA ? roA[u] : roB[u];
+      src = (k0 + rk < c.depth && ro != ~0u) ? (const void*)((isA ? Ab : Bb) + row + ro) : p.zeros;
+    } else {
+      src = (const void*)((isA ? Ab + offA[u] : Bb + offB[u]) + (uint32_t)k0 * 2);
+    }
+    const uint32_t dst = isA ? ldsA + (uint32_t)((buf * BM * GPR + (wave + NW * u) * 64) * 16)
+                             : ldsB + (uint32_t)((buf * BN * GPR + (wave + NW * u) * 64) * 16);
+    async_copy_1k(src, dst);
   };
 
   // LDS -> MFMA fragments: lane reads row (lane & 31) of a 32-row block, granule 2*kk + lane/32
@@ -390,21 +397,22 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
     const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
     return __builtin_bit_cast(bf16x8, v);
   };
-  auto lfrag = [&](const uint4* sa, const uint4* sb, int kk, int set) {
+  // fragment f of k-step kk: f < TM is A fragment f, else B fragment f - TM
+  auto frag_one = [&](const uint4* sa, const uint4* sb, int kk, int set, int f) {
     if constexpr (RM) {
       const uint32_t la = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)sa;
       const uint32_t lb = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)sb;
-#pragma unroll
-      for (int a = 0; a < TM; ++a) fa[set][a] = tr_frag(la + trA[a] + (uint32_t)(kk * 16 * BM * 2), BM * 2);
-#pragma unroll
-      for (int b = 0; b < TN; ++b) fb[set][b] = tr_frag(lb + trB[b] + (uint32_t)(kk * 16 * BN * 2), BN * 2);
-      return;
+      if (f < TM) fa[set][f] = tr_frag(la + trA[f] + (uint32_t)(kk * 16 * BM * 2), BM * 2);
+      else fb[set][f - TM] = tr_frag(lb + trB[f - TM] + (uint32_t)(kk * 16 * BN * 2), BN * 2);
+    } else {
+      const int g = (kk * 2 + fhi) ^ fsw;
+      if (f < TM) fa[set][f] = *(const bf16x8*)&sa[frow_a + f * 32 * GPR + g];
+      else fb[set][f - TM] = *(const bf16x8*)&sb[frow_b + (f - TM) * 32 * GPR + g];
     }
-    const int g = (kk * 2 + fhi) ^ fsw;
+  };
+  auto lfrag = [&](const uint4* sa, const uint4* sb, int kk, int set) {
 #pragma unroll
-    for (int a = 0; a < TM; ++a) fa[set][a] = *(const bf16x8*)&sa[frow_a + a * 32 * GPR + g];
-#pragma unroll
-    for (int b = 0; b < TN; ++b) fb[set][b] = *(const bf16x8*)&sb[frow_b + b * 32 * GPR + g];
+    for (int f = 0; f < TM + TN; ++f) frag_one(sa, sb, kk, set, f);
   };
 
   f32x16 agg[AGG ? TM : 1][AGG ? TN : 1];   // weighted sum over the workers (AGG)
@@ -450,18 +458,17 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
         if (i < p.M) dst[i] = zeros ? 0.f : src[a][v];
       }
   };
-  auto mma = [&](int set) {
-#pragma unroll
-    for (int a = 0; a < TM; ++a)
-#pragma unroll
-      for (int b = 0; b < TN; ++b)
-        // The MFMA's first operand indexes the 4-consecutive-per-lane dimension of the result.
-        // Weight gradients are stored [j][i] with i contiguous; forward / activation-gradient
-        // results are stored [i][j] with j contiguous: feed the operands accordingly.
-        if (MODE == MODE_WGRAD)
-          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][a], fb[set][b], acc[a][b], 0, 0, 0);
-        else
-          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][b], fa[set][a], acc[a][b], 0, 0, 0);
+  // The MFMA's first operand indexes the 4-consecutive-per-lane dimension of the result.  Weight
+  // gradients are stored [j][i] with i contiguous; forward / activation-gradient results are
+  // stored [i][j] with j contiguous: feed the operands accordingly.
+  auto mma_one = [&](int set, int i) {
+    const int a = i / TN, b = i % TN;
+    if (MODE == MODE_WGRAD)
+      acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][a], fb[set][b], acc[a][b], 0, 0, 0);
+    else
+      acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][b], fa[set][a], acc[a][b], 0, 0, 0);
+  };
+  auto mma_sums = [&](int set) {
     if constexpr (RM) {
       if (sums_rows) {             // (uniform per wave) the bias gradient: dy against ones
 #pragma unroll
@@ -469,6 +476,11 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
           rsum[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][a], ones, rsum[a], 0, 0, 0);
       }
     }
+  };
+  auto mma = [&](int set) {
+#pragma unroll
+    for (int i = 0; i < TM * TN; ++i) mma_one(set, i);
+    mma_sums(set);
   };
 
   // Accumulator element v of lane l sits at (8*(v/4) + 4*(l/32) + v%4, l%32) of its 32x32 tile,
@@ -645,6 +657,47 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
       lfrag(sA[buf], sB[buf], 1, 1);
       mma(0);
       __builtin_amdgcn_sched_barrier(0);
+      if constexpr (WEAVE) {
+        // A wave issues in order: copies, fragment fetches and their address arithmetic placed
+        // behind the MFMAs would leave the matrix pipe idle for as long as they take to issue.
+        // They are placed *between* the MFMAs of the second k-step instead (32 clocks each):
+        // first the fragments of the next stage's first k-step (of a buffer nobody reads when
+        // this is the last stage), then the copies that refill the buffer this stage has just
+        // released.  While a stage is still to be issued, S - 1 stages are in flight beyond this
+        // one and the wait is a constant; the last S - 1 stages count down.
+        const bool issuing = ic.g < g_hi;
+        if (issuing)
+          asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * (LA + LB)) : "memory");
+        else
+          wait_copies<LA + LB>(ahead > 0 ? ahead - 1 : 0);
+        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+        constexpr int NM = TM * TN, NF = TM + TN, NI = NF + LA + LB;
+#pragma unroll
+        for (int i = 0; i < NM; ++i) {
+          mma_one(1, i);
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int it = i * NI / NM; it < (i + 1) * NI / NM; ++it) {
+            if (it < NF) {
+              frag_one(sA[nbuf], sB[nbuf], 0, 0, it);
+            } else if (issuing) {
+              copy_one(buf, ic, it - NF);
+            }
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        mma_sums(1);
+        __builtin_amdgcn_sched_barrier(0);
+        if (issuing) {             // (one stage issued, one consumed: `ahead` stays S - 1)
+          ++ic.kt;
+          settle(ic);
+        } else {
+          --ahead;
+        }
+        buf = nbuf;
+        continue;
+      }
       wait_copies<LA + LB>(ahead > 0 ? ahead - 1 : 0);   // my copies of the next stage landed
       __syncthreads();
       __builtin_amdgcn_sched_barrier(0);
@@ -932,7 +985,10 @@ bool gemm_fuses_aggregate(int dtype, const GemmArgs& a, const Segs& s) {
          tiles_of(a, AGG_SMALL, AGG_SMALL) >= 256 && s.K <= DYNB_MAX_WORKERS;
 }
 
-int launch_gemm(int dtype, const GemmArgs& a, const Segs& s, void* stream) {
+int launch_gemm(int dtype, const GemmArgs& args, const Segs& s, void* stream) {
+  GemmArgs a = args;
+  a.zeros = device_zero_granule();
+  if (!a.zeros) return fail(DYNB_ERR_HIP, "gemm: no address for the zero granule");
   if (a.M <= 0 || a.N <= 0) return DYNB_OK;
   if (a.agg && !gemm_fuses_aggregate(dtype, a, s))
     return fail(DYNB_ERR_UNSUPPORTED, "gemm: this weight gradient cannot fold the aggregation in");
