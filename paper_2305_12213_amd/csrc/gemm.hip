@@ -435,10 +435,15 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
   };
   clear_acc();
   // Weight gradient, optional: the bias gradient db_g[i] = sum over worker g's rows of dy[.][i]
-  // rides along as one more column of the product -- the waves that own the tile column j0 = 0
-  // multiply their dy fragments with ones.  Every column of rsum holds the same sums; lanes 0 and
+  // rides along as one more column of the product -- the waves of one tile column multiply
+  // their dy fragments with ones.  Every column of rsum holds the same sums; lanes 0 and
   // 32 (column 0) write them out.
-  const bool sums_rows = RM && p.bias_grad != nullptr && j0 == 0 && wn == 0;
+  // The tiles of a tile row all hold these dy fragments: worker g's sums are formed by the tile
+  // column g mod (tile columns), so that the extra work is spread over the workgroups instead of
+  // making the first tile column the last to finish.
+  const int bias_cols = (p.N + BN - 1) / BN;
+  auto owns_bias = [&](int g) { return RM && p.bias_grad != nullptr && wn == 0 && g % bias_cols == tj; };
+  bool sums_rows = false;           // does this wave sum the rows of the worker being computed?
   typedef short s16x8 __attribute__((ext_vector_type(8)));
   const s16x8 ones_bits = {0x3f80, 0x3f80, 0x3f80, 0x3f80, 0x3f80, 0x3f80, 0x3f80, 0x3f80};
   const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_bits);
@@ -590,7 +595,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
   // A worker without rows contributes a zero tile (not unrolled: it is rare and tiny).
   auto store_zero = [&](int g) {
     if constexpr (RM) {
-      if (sums_rows) store_row_sums(p.bias_grad + (int64_t)g * p.group_stride, rsum, true);
+      if (owns_bias(g)) store_row_sums(p.bias_grad + (int64_t)g * p.group_stride, rsum, true);
     }
     float* Cg = tile_base(g);
     const bool vec_ok = (p.ldcf & 3) == 0 && (((uintptr_t)Cg) & 15) == 0;
@@ -652,6 +657,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
     enter(ng);
     settle(ng);
     const bool later = ng.g < g_hi;
+    sums_rows = owns_bias(gid(g));
     for (int kt = 0; kt < nst; ++kt) {   // the hot loop: all stages of worker g
       const int nbuf = buf + 1 == S ? 0 : buf + 1;
       lfrag(sA[buf], sB[buf], 1, 1);
