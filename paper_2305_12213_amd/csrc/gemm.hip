@@ -650,6 +650,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
     lfrag(sA[0], sB[0], 0, 0);
   }
   int buf = 0;
+  bool pend = false;            // second half of the previous refill still to be issued
+  int pbuf = 0;                 // ... into this buffer,
+  StageCursor pc = ic;          // ... of this stage
   while (cc.g < g_hi) {
     const int g = cc.g, nst = cc.nst;
     StageCursor ng;                // first stage of the next worker that has rows
@@ -660,31 +663,48 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
     sums_rows = owns_bias(gid(g));
     for (int kt = 0; kt < nst; ++kt) {   // the hot loop: all stages of worker g
       const int nbuf = buf + 1 == S ? 0 : buf + 1;
-      lfrag(sA[buf], sB[buf], 1, 1);
-      mma(0);
-      __builtin_amdgcn_sched_barrier(0);
       if constexpr (WEAVE) {
         // A wave issues in order: copies, fragment fetches and their address arithmetic placed
-        // behind the MFMAs would leave the matrix pipe idle for as long as they take to issue.
-        // They are placed *between* the MFMAs of the second k-step instead (32 clocks each):
-        // first the fragments of the next stage's first k-step (of a buffer nobody reads when
-        // this is the last stage), then the copies that refill the buffer this stage has just
-        // released.  While a stage is still to be issued, S - 1 stages are in flight beyond this
-        // one and the wait is a constant; the last S - 1 stages count down.
+        // behind a block of MFMAs would leave the matrix pipe idle for as long as they take to
+        // issue, and the copies of all four waves would reach the memory pipeline in one burst.
+        // They are placed *between* the MFMAs instead (32 clocks each).  First k-step: the
+        // fragments of the second k-step, then the second half of the copies that refill the
+        // buffer released by the previous stage.  Second k-step (behind the barrier that
+        // releases this stage's buffer): the fragments of the next stage's first k-step (of a
+        // buffer nobody reads when this is the last stage), then the first half of the copies
+        // that refill this buffer.  While a stage is still to be issued, S - 1 stages are in
+        // flight beyond this one and the wait is a constant; the last S - 1 stages count down.
+        constexpr int NM = TM * TN, NF = TM + TN, NC = LA + LB, NC1 = NC / 2;
+        constexpr int NI0 = NF + (NC - NC1), NI1 = NF + NC1;
+#pragma unroll
+        for (int i = 0; i < NM; ++i) {
+          mma_one(0, i);
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int it = i * NI0 / NM; it < (i + 1) * NI0 / NM; ++it) {
+            if (it < NF) {
+              frag_one(sA[buf], sB[buf], 1, 1, it);
+            } else if (pend) {
+              copy_one(pbuf, pc, NC1 + it - NF);
+            }
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        mma_sums(0);
+        __builtin_amdgcn_sched_barrier(0);
         const bool issuing = ic.g < g_hi;
         if (issuing)
-          asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * (LA + LB)) : "memory");
+          asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * NC) : "memory");
         else
-          wait_copies<LA + LB>(ahead > 0 ? ahead - 1 : 0);
+          wait_copies<NC>(ahead > 0 ? ahead - 1 : 0);
         __syncthreads();
         __builtin_amdgcn_sched_barrier(0);
-        constexpr int NM = TM * TN, NF = TM + TN, NI = NF + LA + LB;
 #pragma unroll
         for (int i = 0; i < NM; ++i) {
           mma_one(1, i);
           __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-          for (int it = i * NI / NM; it < (i + 1) * NI / NM; ++it) {
+          for (int it = i * NI1 / NM; it < (i + 1) * NI1 / NM; ++it) {
             if (it < NF) {
               frag_one(sA[nbuf], sB[nbuf], 0, 0, it);
             } else if (issuing) {
@@ -695,6 +715,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
         }
         mma_sums(1);
         __builtin_amdgcn_sched_barrier(0);
+        pend = issuing;
+        pbuf = buf;
+        pc = ic;
         if (issuing) {             // (one stage issued, one consumed: `ahead` stays S - 1)
           ++ic.kt;
           settle(ic);
@@ -704,6 +727,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
         buf = nbuf;
         continue;
       }
+      lfrag(sA[buf], sB[buf], 1, 1);
+      mma(0);
+      __builtin_amdgcn_sched_barrier(0);
       wait_copies<LA + LB>(ahead > 0 ? ahead - 1 : 0);   // my copies of the next stage landed
       __syncthreads();
       __builtin_amdgcn_sched_barrier(0);
