@@ -6,11 +6,11 @@
 // weight/bias gradients are per worker.  A "row" is a sample for dense layers and a pixel
 // (sample, y, x) for convolutions (NHWC with the channel pitch padded to 64).
 //
-// Every operand of a per-worker weight-gradient GEMM is kept transposed,
-// [features][padded rows], because its reduction runs over the worker's rows.  In these
-// copies worker k's rows sit at columns [poff_k, poff_k + rows_k), poff_k = sum_{j<k}
-// round_up(rows_j, 8), so that every worker's segment starts on a 16-byte boundary; the
-// padding columns are written as zero.
+// bf16 models: the per-worker weight-gradient kernels reduce over the rows of the row-major
+// activations and gradients themselves.  fp32 models: every operand of a per-worker
+// weight-gradient GEMM is kept transposed, [features][padded rows]; in these copies worker k's
+// rows sit at columns [poff_k, poff_k + rows_k), poff_k = sum_{j<k} round_up(rows_j, 8), so that
+// every worker's segment starts on a 16-byte boundary; the padding columns are written as zero.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
