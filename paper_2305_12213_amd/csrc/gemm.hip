@@ -922,31 +922,31 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs p, Segs segs) {
     }
 }
 
-template <int BM, int BN, int WM, int WN, int S_PLAIN, int S_WGRAD>
-void launch_bf16(GemmArgs a, const Segs& s, hipStream_t st) {
+// per-worker weight gradients (no aggregate)
+template <int BM, int BN, int WM, int WN, int S>
+void launch_bf16_wgrad(GemmArgs a, const Segs& s, hipStream_t st) {
   const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
-  int gy = 1;
+  // a workgroup streams through several workers; split the workers over more workgroups only
+  // when the tiles alone cannot occupy the 256 compute units
+  const int n_groups = s.K * (a.split > 1 ? a.split : 1);
+  int chunks = (256 + tiles - 1) / tiles;
+  if (chunks > n_groups) chunks = n_groups;
+  a.groups_per_block = (n_groups + chunks - 1) / chunks;
+  const int gy = (n_groups + a.groups_per_block - 1) / a.groups_per_block;
+  hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, MODE_WGRAD, false, S>), dim3(tiles, gy, 1),
+                     dim3(WM * WN * 64), 0, st, a, s);
+}
+
+// forward / input gradient
+template <int BM, int BN, int WM, int WN, int S>
+void launch_bf16_plain(GemmArgs a, const Segs& s, hipStream_t st) {
+  const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
   a.groups_per_block = 1;
-  if (a.mode == MODE_WGRAD) {
-    // a workgroup streams through several workers; split the workers over more workgroups only
-    // when the tiles alone cannot occupy the 256 compute units
-    const int n_groups = s.K * (a.split > 1 ? a.split : 1);
-    int chunks = (256 + tiles - 1) / tiles;
-    if (chunks > n_groups) chunks = n_groups;
-    a.groups_per_block = (n_groups + chunks - 1) / chunks;
-    gy = (n_groups + a.groups_per_block - 1) / a.groups_per_block;
-  }
-  dim3 grid(tiles, gy, 1), block(WM * WN * 64);
-  switch (a.mode) {
-    case MODE_FWD:
-      hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, MODE_FWD, false, S_PLAIN>), grid, block, 0, st, a, s);
-      break;
-    case MODE_DGRAD:
-      hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, MODE_DGRAD, false, S_PLAIN>), grid, block, 0, st, a, s);
-      break;
-    default:
-      hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, MODE_WGRAD, false, S_WGRAD>), grid, block, 0, st, a, s);
-  }
+  dim3 grid(tiles, 1, 1), block(WM * WN * 64);
+  if (a.mode == MODE_FWD)
+    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, MODE_FWD, false, S>), grid, block, 0, st, a, s);
+  else
+    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, MODE_DGRAD, false, S>), grid, block, 0, st, a, s);
 }
 
 // Weight gradient with the weighted aggregation folded in: 256 x 128 tiles leave room for a
@@ -1045,12 +1045,24 @@ int launch_gemm(int dtype, const GemmArgs& args, const Segs& s, void* stream) {
     launch_bf16_wgrad_agg(a, s, (hipStream_t)stream);
   } else if (dtype == DYNB_BF16) {
     // large tiles have the best LDS-traffic-to-MFMA ratio; small problems need more, smaller
-    // tiles to occupy 256 compute units
+    // tiles to occupy 256 compute units.  Forward / input gradient on 256 x 256 tiles run EIGHT
+    // waves (wave tile 128 x 64, at most 256 registers each): two waves per SIMD, so that one
+    // can issue MFMAs while the other waits for a copy instruction to be accepted (input
+    // gradient 112 -> 102 us, forward 126 -> 124 us per 4096^3 launch against four waves of
+    // 128 x 128).  The weight gradient keeps four waves: its 256 accumulators per lane leave no
+    // room for a second wave on a SIMD.
     const int64_t big = (int64_t)((a.M + 255) / 256) * ((a.N + 255) / 256);
-    if (big >= 192)
-      launch_bf16<256, 256, 2, 2, 5, 4>(a, s, (hipStream_t)stream);   // 160 KB / 128 + 18 KB of LDS
-    else
-      launch_bf16<128, 128, 2, 2, 8, 8>(a, s, (hipStream_t)stream);
+    const hipStream_t st = (hipStream_t)stream;
+    if (a.mode == MODE_WGRAD) {
+      if (big >= 192)
+        launch_bf16_wgrad<256, 256, 2, 2, 4>(a, s, st);   // 128 + 18 KB of LDS
+      else
+        launch_bf16_wgrad<128, 128, 2, 2, 8>(a, s, st);
+    } else if (big >= 192) {
+      launch_bf16_plain<256, 256, 2, 4, 5>(a, s, st);     // all 160 KB of LDS
+    } else {
+      launch_bf16_plain<128, 128, 2, 2, 8>(a, s, st);
+    }
   } else
     launch_f32(a, s, groups, (hipStream_t)stream);
   return hipGetLastError() == hipSuccess ? DYNB_OK : fail(DYNB_ERR_HIP, "gemm launch failed");
