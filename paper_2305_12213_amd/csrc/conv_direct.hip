@@ -48,7 +48,7 @@ struct ConvDirectArgs {
   const void* zeros;                 // 16 bytes of zeros in device memory
 };
 
-__global__ __launch_bounds__(256) void conv_direct_kernel(ConvDirectArgs p) {
+__global__ __launch_bounds__(256, 2) void conv_direct_kernel(ConvDirectArgs p) {
   __shared__ uint4 halo[HALO_COPIES * 64];
   __shared__ uint4 wring[WSTAGES][512];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -130,11 +130,15 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(ConvDirectArgs p) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-  // ---- pipeline: the halo of a channel block, then its nine taps; weights two stages ahead ----
+  // ---- pipeline: the halo of a channel block, then its nine taps; weights two stages ahead.
+  // Within a tap the operands of k-step kk+1 are fetched between the MFMAs of k-step kk (a wave
+  // issues in order: fetches in front of the MFMAs that need them expose the LDS latency four
+  // times per tap); across taps only the first k-step's fetches follow the barrier. ----
   issue_halo(0);
   issue_w(0);
   if (total > 1) issue_w(1);
   int s = 0;
+  bf16x8 fa[2][2], fb[2][2];         // [register set][fragment]
   for (int blk = 0; blk < nblk; ++blk) {
 #pragma unroll
     for (int tap = 0; tap < 9; ++tap, ++s) {
@@ -149,14 +153,23 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(ConvDirectArgs p) {
       const int kh = tap / 3, kw = tap - 3 * kh;
       const int dy_ = p.flip ? 2 - kh : kh, dx_ = p.flip ? 2 - kw : kw;
       const int st = s % WSTAGES;
+      fa[0][0] = a_frag(0, dy_, dx_, 0); fb[0][0] = b_frag(st, 0, 0);
+      fa[0][1] = a_frag(1, dy_, dx_, 0); fb[0][1] = b_frag(st, 1, 0);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
-        const bf16x8 a0 = a_frag(0, dy_, dx_, kk), a1 = a_frag(1, dy_, dx_, kk);
-        const bf16x8 b0 = b_frag(st, 0, kk), b1 = b_frag(st, 1, kk);
-        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b0, a0, acc[0][0], 0, 0, 0);
-        acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b1, a0, acc[0][1], 0, 0, 0);
-        acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b0, a1, acc[1][0], 0, 0, 0);
-        acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b1, a1, acc[1][1], 0, 0, 0);
+        const int c = kk & 1, n = c ^ 1;
+        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[c][0], fa[c][0], acc[0][0], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (kk < 3) { fa[n][0] = a_frag(0, dy_, dx_, kk + 1); fb[n][0] = b_frag(st, 0, kk + 1); }
+        __builtin_amdgcn_sched_barrier(0);
+        acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[c][1], fa[c][0], acc[0][1], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (kk < 3) { fa[n][1] = a_frag(1, dy_, dx_, kk + 1); fb[n][1] = b_frag(st, 1, kk + 1); }
+        __builtin_amdgcn_sched_barrier(0);
+        acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[c][0], fa[c][1], acc[1][0], 0, 0, 0);
+        acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[c][1], fa[c][1], acc[1][1], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
     __syncthreads();                 // every wave is done with this block's halo
@@ -167,13 +180,13 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(ConvDirectArgs p) {
   // patch in the (now free) halo area: 4 consecutive channels per lane become 8, and bias /
   // ReLU / addend / mask, the bf16 conversion and the stores run on whole 128-byte rows.
   float* patch = (float*)&halo[0] + wave * 32 * EP;
+  // the mask and addend rows of the whole strip are fetched up front (one round trip to
+  // memory instead of eight)
   const int hi4 = 4 * hi;
   const int rrow = lane >> 3, rcol = (lane & 7) * 8;
   const int jcol = j0 + rcol;
   const bool col_ok = jcol + 7 < p.N;
   const int64_t row0 = (int64_t)(img * p.H + y0 + 2 * wave) * 32;   // first pixel of the wave's strip
-  // the mask and addend rows of the whole strip are fetched up front (one round trip to
-  // memory instead of eight)
   bf16x8 mk[2][4], ad[2][4];
   if (col_ok) {
 #pragma unroll
@@ -185,6 +198,7 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(ConvDirectArgs p) {
         if (p.addend) ad[a][t] = *(const bf16x8*)(p.addend + i * p.ldadd + jcol);
       }
   }
+
 #pragma unroll
   for (int a = 0; a < 2; ++a) {
 #pragma unroll
@@ -195,12 +209,17 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(ConvDirectArgs p) {
         *(f32x4*)&patch[x * EP + b * 32 + 8 * q + hi4] = o;
       }
     __builtin_amdgcn_wave_barrier();
+    f32x4 plo[4], phi[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      plo[t] = *(const f32x4*)&patch[(rrow + 8 * t) * EP + rcol];
+      phi[t] = *(const f32x4*)&patch[(rrow + 8 * t) * EP + rcol + 4];
+    }
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
       const int r = rrow + 8 * t;
       const int64_t i = row0 + a * 32 + r;
-      const f32x4 lo = *(const f32x4*)&patch[r * EP + rcol];
-      const f32x4 hi_ = *(const f32x4*)&patch[r * EP + rcol + 4];
+      const f32x4 lo = plo[t], hi_ = phi[t];
       if (jcol >= p.N) continue;
       float v[8] = {lo[0], lo[1], lo[2], lo[3], hi_[0], hi_[1], hi_[2], hi_[3]};
 #pragma unroll
