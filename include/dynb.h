@@ -150,11 +150,14 @@ int dynb_forward_backward(dynb_model* m, const float* x, const int32_t* y, const
                           int32_t K, float* grads, void* stream);
 
 /* dynb_forward_backward that also returns the weighted average of Eq. 2,
- * out[p] = sum_k (b_k / sum_i b_i) * grads[k][p] (ascending k, fp32; device fp32 [P_pad],
- * 16-byte aligned): the same values as dynb_weighted_aggregate(grads, b, K, P_pad, out) would
- * give, but for large dense layers the sum is formed in the weight-gradient kernel while each
- * worker's tile is still in registers, so the K*P_pad floats are written once and not read
- * again.  grads is written in full as before.  sum(b) must be > 0. */
+ * out[p] = sum_k (b_k / sum_i b_i) * grads[k][p] (fp32; device fp32 [P_pad], 16-byte aligned):
+ * what dynb_weighted_aggregate(grads, b, K, P_pad, out) would give, but for large dense layers
+ * the sum is formed in the weight-gradient kernel while each worker's tile is still in
+ * registers, so the K*P_pad floats are written once and not read again.  There the K terms of
+ * an element are added in a fixed order that depends on the element's tile (a rotation of
+ * 0..K-1, so that the compute units do not all write a worker's tile at the same moment):
+ * reproducible from run to run, equal to the ascending-k sum up to fp32 rounding.  grads is
+ * written in full as before.  sum(b) must be > 0. */
 int dynb_forward_backward_aggregate(dynb_model* m, const float* x, const int32_t* y,
                                     const int32_t* b, int32_t K, float* grads, float* out,
                                     void* stream);

@@ -119,8 +119,8 @@ struct GemmArgs {
   float* partial;
   int64_t partial_stride;
   // WGRAD, bf16 kernel, optional: also write agg[j*ldcf + i] = sum_g lam[g] * (tile of worker g),
-  // summed in ascending g (the weighted aggregation of Eq. 2 while the per-worker tiles are still
-  // in registers).  Only when gemm_fuses_aggregate() says so.
+  // summed in a fixed, tile-dependent rotation of ascending g (the weighted aggregation of Eq. 2
+  // while the per-worker tiles are still in registers).  Only when gemm_fuses_aggregate() says so.
   float* agg;
   float lam[DYNB_MAX_WORKERS];
   const void* zeros;   // 16 bytes of zeros in device memory (set by launch_gemm): what copies

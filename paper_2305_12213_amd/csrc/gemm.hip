@@ -130,7 +130,7 @@ struct PatchArea<0> {
 
 // S = number of LDS stage buffers (ring).
 // AGG (weight gradient only): the workgroup also accumulates sum_g lam[g] * tile_g in registers
-// and writes it to p.agg; it then owns all workers of its tile and walks them in ascending order.
+// and writes it to p.agg; it then owns all workers of its tile.
 // Weight gradient (RM below): the operands are the row-major tensors themselves, A = dy
 // [rows][lda] and B = the layer input [rows][ldb], the reduction runs over their ROWS (worker g
 // owns rows [off[g], off[g+1])), and a stage holds 32 rows x BM (BN) features as they lie in
@@ -186,7 +186,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
   // finish a worker at the same moment and all 256 tiles (64 MB) would hit the memory system
   // together while the MFMAs wait; rotated, the tile stores of some units overlap the MFMAs of
   // the others.  Position c.g in the walk is group gid(c.g).
-  const int rot = !AGG && (g_hi - g_lo) > 1 ? (int)((blockIdx.x * 7u) % (unsigned)(g_hi - g_lo)) : 0;
+  const int rot = (g_hi - g_lo) > 1 ? (int)((blockIdx.x * 7u) % (unsigned)(g_hi - g_lo)) : 0;
   auto gid = [&](int pos) {
     const int r = pos - g_lo + rot, span = g_hi - g_lo;
     return g_lo + (r >= span ? r - span : r);

@@ -151,7 +151,7 @@ def test_forward_backward_aggregate_equals_the_two_call_form():
         assert np.all(np.isfinite(o1)) and np.all(o1[one.P:] == 0.0)
         # per-worker gradients: same arithmetic up to the tile shape of the large case
         assert relerr(g1, g2) < 1e-6
-        # the aggregate: the same products summed in the same (ascending k) order
+        # the aggregate: the same products, summed in a rotation of the ascending-k order
         assert relerr(o1, o2) < 1e-6, spec["layers"][0]
         # and against the checker's definition, given the gradients the GPU wrote
         ref = np.zeros(one.Pp)
