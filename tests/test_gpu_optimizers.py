@@ -135,7 +135,10 @@ def test_forward_backward_aggregate_equals_the_two_call_form():
              (synth.mlp_spec([200, 136, 10], "bf16"), [5, 60, 0, 31]),
              (SPECS[3][1](), [3, 9, 0, 4]),
              (synth.mlp_spec([2500, 4200, 16], "bf16"), [700, 1, 0, 257, 66]),
-             (synth.mlp_spec([4100, 1000, 16], "bf16"), [300, 2, 0, 129, 40])]
+             (synth.mlp_spec([4100, 1000, 16], "bf16"), [300, 2, 0, 129, 40]),
+             # 64 workers, several of them idle: both aggregating kernels at the largest K
+             (synth.mlp_spec([2500, 4200, 16], "bf16"), [(i * 37) % 23 for i in range(64)]),
+             (synth.mlp_spec([2100, 2100, 16], "bf16"), [(i * 29) % 19 for i in range(64)])]
     for spec, b in cases:
         G, K = sum(b), len(b)
         p0 = synth.init_params(spec, "he", 11)
