@@ -802,6 +802,20 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
     }
 #pragma unroll
     for (int a = 0; a < TM; ++a) {
+      // input gradient: the mask and addend rows of this 32-row block are asked for now, all of
+      // them at once (rows past the matrix clamped), and travel while the accumulators pass
+      // through the patch -- fetched row by row where they are used, every row costs a trip to
+      // memory of its own
+      bf16x8 mkv[32 / RPI], adv[32 / RPI];
+      if (MODE == MODE_DGRAD && col_ok) {
+#pragma unroll
+        for (int t = 0; t < 32 / RPI; ++t) {
+          int i = i0 + wm * (BM / WM) + a * 32 + rrow + RPI * t;
+          i = i < p.M ? i : p.M - 1;
+          if (p.mask) mkv[t] = *(const bf16x8*)((const bf16*)p.mask + (int64_t)i * p.ldmask + jcol);
+          if (p.addend) adv[t] = *(const bf16x8*)((const bf16*)p.addend + (int64_t)i * p.ldadd + jcol);
+        }
+      }
 #pragma unroll
       for (int b = 0; b < TN; ++b)
 #pragma unroll
@@ -829,15 +843,13 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
         }
         if (col_ok) {
           if (MODE == MODE_DGRAD && p.addend) {
-            const bf16x8 ad = *(const bf16x8*)((const bf16*)p.addend + (int64_t)i * p.ldadd + jcol);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = (float)(bf16)v[e] + (float)ad[e];
+            for (int e = 0; e < 8; ++e) v[e] = (float)(bf16)v[e] + (float)adv[t][e];
           }
           if (MODE == MODE_DGRAD && p.mask) {
-            const bf16x8 mk = *(const bf16x8*)((const bf16*)p.mask + (int64_t)i * p.ldmask + jcol);
 #pragma unroll
             for (int e = 0; e < 8; ++e)
-              if (!((float)mk[e] > 0.f)) v[e] = 0.f;
+              if (!((float)mkv[t][e] > 0.f)) v[e] = 0.f;
           }
           if (MODE == MODE_FWD && p.Cf) {
             float* dst = p.Cf + (int64_t)i * p.ldcf + jcol;
