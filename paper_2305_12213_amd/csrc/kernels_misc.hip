@@ -143,6 +143,51 @@ __global__ __launch_bounds__(256) void softmax_xent_kernel(const float* __restri
   const float* zr = z + (int64_t)row * ldz;
   int label = y[row];
   label = label < 0 ? 0 : (label >= C ? C - 1 : label);   // keeps the read in bounds
+  if (ld_cols <= 1024 && (ldz & 3) == 0 && (ldd & 3) == 0) {
+    // the whole row in registers: 16-byte loads, one exponential per element
+    typedef T vec4T __attribute__((ext_vector_type(4)));
+    float4 v[4];
+    float m = -INFINITY;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int c0 = 4 * (lane + 64 * u);
+      v[u] = c0 < ld_cols ? *(const float4*)(zr + c0) : make_float4(0.f, 0.f, 0.f, 0.f);
+      float* e = (float*)&v[u];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if (c0 + q >= C) e[q] = -INFINITY;
+        m = fmaxf(m, e[q]);
+      }
+    }
+    m = wave_max(m);
+    float sum = 0.f;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      float* e = (float*)&v[u];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        e[q] = expf(e[q] - m);          // (exp(-inf) = 0 in the pad columns)
+        sum += e[q];
+      }
+    }
+    sum = wave_sum(sum);
+    const float inv = 1.f / sum, scale = 1.f / (float)bk;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int c0 = 4 * (lane + 64 * u);
+      if (c0 >= ld_cols) continue;
+      const float* e = (const float*)&v[u];
+      vec4T o;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int c = c0 + q;
+        o[q] = from_float<T>(c < C ? (e[q] * inv - (c == label ? 1.f : 0.f)) * scale : 0.f);
+      }
+      *(vec4T*)(drow + c0) = o;
+    }
+    if (lane == 0) rowloss[row] = logf(sum) - (zr[label] - m);
+    return;
+  }
   float m = -INFINITY;
   for (int c = lane; c < C; c += 64) m = fmaxf(m, zr[c]);
   m = wave_max(m);
@@ -191,8 +236,14 @@ __global__ __launch_bounds__(64) void finalize_kernel(const float* __restrict__ 
                                                       int64_t P_pad, Segs s) {
   const int g = blockIdx.x, lane = threadIdx.x;
   const int bk = s.off[g + 1] - s.off[g];
-  float acc = 0.f;
-  for (int i = lane; i < bk; i += 64) acc += rowloss[s.off[g] + i];
+  // eight independent partial sums per lane: the loads of a round are in flight together
+  float part[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int i = lane; i < bk; i += 512) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (i + 64 * u < bk) part[u] += rowloss[s.off[g] + i + 64 * u];
+  }
+  float acc = ((part[0] + part[1]) + (part[2] + part[3])) + ((part[4] + part[5]) + (part[6] + part[7]));
   acc = wave_sum(acc);
   if (lane == 0) loss[g] = bk > 0 ? acc / (float)bk : 0.f;
   if (grads)
