@@ -58,6 +58,8 @@ def check_worker_gradients(spec, params, x, y, b, run=None, label=""):
     ([256, 192, 10], [63, 65, 127, 129]),          # several tiles and ragged tails
     ([200, 300, 5], [255, 257, 1]),
     ([96, 64, 12], [0, 0, 9]),
+    ([48, 1100], [3, 5]),                          # more classes than the softmax keeps in registers
+    ([48, 1000], [2, 7]),                          # ... and just below that
 ])
 def test_worker_gradients_on_ragged_splits(dtype, dims, b):
     spec = synth.mlp_spec(dims, dtype)
