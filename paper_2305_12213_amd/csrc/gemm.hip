@@ -273,80 +273,6 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
       roB[u] = f < p.ldb ? (uint32_t)(((int64_t)k * p.ldb + f) * 2) : ~0u;
     }
   }
-  auto issue = [&](int buf, const StageCursor& c) {
-    const int k0 = c.kt * BK;
-    if constexpr (RM) {
-      const uint32_t rowA = (uint32_t)((int64_t)(c.col0 + k0) * p.lda * 2);
-      const uint32_t rowB = (uint32_t)((int64_t)(c.col0 + k0) * p.ldb * 2);
-#pragma unroll
-      for (int u = 0; u < LA; ++u) {
-        const void* src = (k0 + rkA[u] < c.depth && roA[u] != ~0u) ? (const void*)(Ab + rowA + roA[u])
-                                                                   : p.zeros;
-        async_copy_1k(src, ldsA + (uint32_t)((buf * BM * GPR + (wave + NW * u) * 64) * 16));
-      }
-#pragma unroll
-      for (int u = 0; u < LB; ++u) {
-        const void* src = (k0 + rkB[u] < c.depth && roB[u] != ~0u) ? (const void*)(Bb + rowB + roB[u])
-                                                                   : p.zeros;
-        async_copy_1k(src, ldsB + (uint32_t)((buf * BN * GPR + (wave + NW * u) * 64) * 16));
-      }
-      return;
-    }
-    const uint32_t kbyte = (uint32_t)k0 * 2;
-    int kh = 0, kw = 0, ch = 0;
-    bool tap_ok = false;
-    if (gfast) {
-      // the whole stage lies in tap k0 >> log2(cp): one signed byte offset for every row
-      const int tap = k0 >> p.gather_log2cp, kc = k0 & (p.cp - 1);
-      const int th = (tap * 11) >> 5, tw = tap - 3 * th;          // tap / 3, tap % 3 (tap <= 9)
-      const int dpix = (th - 1) * p.src_w + (tw - 1);
-      const uint32_t dbyte = (uint32_t)(((p.conv == 1 ? dpix : -dpix) * (int)p.lda + kc) * 2);
-#pragma unroll
-      for (int u = 0; u < LA; ++u) {
-        const void* src = (gok[u] >> tap) & 1u ? (const void*)(Ab + (uint32_t)(goff[u] + dbyte))
-                                               : p.zeros;
-        async_copy_1k(src, ldsA + (uint32_t)((buf * BM * GPR + (wave + NW * u) * 64) * 16));
-      }
-    } else if (GATHER) {
-      const int k = k0 + lgran * 8;
-      const int tap = k / p.cp;
-      ch = k - tap * p.cp;
-      kh = tap / 3;
-      kw = tap - kh * 3;
-      tap_ok = tap < 9;
-    }
-#pragma unroll
-    for (int u = 0; u < LA; ++u) {
-      if (gfast) break;                              // (copied above)
-      const void* src;
-      if (GATHER) {
-        int sy, sx;
-        bool ok = tap_ok;
-        if (p.conv == 1) {
-          sy = gy[u] * p.stride + kh - 1;
-          sx = gx[u] * p.stride + kw - 1;
-        } else {
-          // (stride is 1 or 2: a shift instead of a division in the hot loop)
-          const int ty = gy[u] + 1 - kh, tx = gx[u] + 1 - kw, sh = p.stride - 1;
-          sy = ty >> sh;
-          sx = tx >> sh;
-          ok = ok && ty >= 0 && tx >= 0 && (sy << sh) == ty && (sx << sh) == tx;
-        }
-        ok = ok && sy >= 0 && sy < p.src_h && sx >= 0 && sx < p.src_w;
-        const int64_t pix = (int64_t)offA[u] + sy * p.src_w + sx;
-        src = ok ? (const void*)(Ab + (pix * p.lda + ch) * 2) : p.zeros;
-      } else {
-        src = (const void*)(Ab + offA[u] + kbyte);
-      }
-      async_copy_1k(src, ldsA + (uint32_t)((buf * BM * GPR + (wave + NW * u) * 64) * 16));
-    }
-#pragma unroll
-    for (int u = 0; u < LB; ++u) {
-      const void* src = (const void*)(Bb + offB[u] + kbyte);
-      async_copy_1k(src, ldsB + (uint32_t)((buf * BN * GPR + (wave + NW * u) * 64) * 16));
-    }
-  };
-
   // One copy of a stage (plain or row-major operands): idx < LA is copy idx of the A operand,
   // else copy idx - LA of the B operand.  The hot loop places these between the MFMAs.
   auto copy_one = [&](int buf, const StageCursor& c, int idx) {
@@ -366,6 +292,60 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
     const uint32_t dst = isA ? ldsA + (uint32_t)((buf * BM * GPR + (wave + NW * u) * 64) * 16)
                              : ldsB + (uint32_t)((buf * BN * GPR + (wave + NW * u) * 64) * 16);
     async_copy_1k(src, dst);
+  };
+
+  // All copies of a stage at once (the prologue; every stage of the gathered-operand kernels).
+  auto issue = [&](int buf, const StageCursor& c) {
+    if constexpr (!GATHER) {
+#pragma unroll
+      for (int idx = 0; idx < LA + LB; ++idx) copy_one(buf, c, idx);
+      return;
+    }
+    const int k0 = c.kt * BK;
+    const uint32_t kbyte = (uint32_t)k0 * 2;
+    if (gfast) {
+      // the whole stage lies in tap k0 >> log2(cp): one signed byte offset for every row
+      const int tap = k0 >> p.gather_log2cp, kc = k0 & (p.cp - 1);
+      const int th = (tap * 11) >> 5, tw = tap - 3 * th;          // tap / 3, tap % 3 (tap <= 9)
+      const int dpix = (th - 1) * p.src_w + (tw - 1);
+      const uint32_t dbyte = (uint32_t)(((p.conv == 1 ? dpix : -dpix) * (int)p.lda + kc) * 2);
+#pragma unroll
+      for (int u = 0; u < LA; ++u) {
+        const void* src = (gok[u] >> tap) & 1u ? (const void*)(Ab + (uint32_t)(goff[u] + dbyte))
+                                               : p.zeros;
+        async_copy_1k(src, ldsA + (uint32_t)((buf * BM * GPR + (wave + NW * u) * 64) * 16));
+      }
+    } else {
+      const int k = k0 + lgran * 8;
+      const int tap = k / p.cp;
+      const int ch = k - tap * p.cp;
+      const int kh = tap / 3, kw = tap - kh * 3;
+      const bool tap_ok = tap < 9;
+#pragma unroll
+      for (int u = 0; u < LA; ++u) {
+        int sy, sx;
+        bool ok = tap_ok;
+        if (p.conv == 1) {
+          sy = gy[u] * p.stride + kh - 1;
+          sx = gx[u] * p.stride + kw - 1;
+        } else {
+          // (stride is 1 or 2: a shift instead of a division in the hot loop)
+          const int ty = gy[u] + 1 - kh, tx = gx[u] + 1 - kw, sh = p.stride - 1;
+          sy = ty >> sh;
+          sx = tx >> sh;
+          ok = ok && ty >= 0 && tx >= 0 && (sy << sh) == ty && (sx << sh) == tx;
+        }
+        ok = ok && sy >= 0 && sy < p.src_h && sx >= 0 && sx < p.src_w;
+        const int64_t pix = (int64_t)offA[u] + sy * p.src_w + sx;
+        const void* src = ok ? (const void*)(Ab + (pix * p.lda + ch) * 2) : p.zeros;
+        async_copy_1k(src, ldsA + (uint32_t)((buf * BM * GPR + (wave + NW * u) * 64) * 16));
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < LB; ++u) {
+      const void* src = (const void*)(Bb + offB[u] + kbyte);
+      async_copy_1k(src, ldsB + (uint32_t)((buf * BN * GPR + (wave + NW * u) * 64) * 16));
+    }
   };
 
   // LDS -> MFMA fragments: lane reads row (lane & 31) of a 32-row block, granule 2*kk + lane/32
