@@ -168,65 +168,162 @@ def forward(spec, params, x, emulate_bf16=False):
     return a, stored
 
 
-def ambiguous_relu_units(spec, params, x, emulate_bf16=False, band=8.0):
+# A sum of K products accumulated in fp32 differs from the exact sum by a random amount; the
+# scale 2^-24 sqrt(K) sqrt(sum_j a_j^2 w_j^2) is called one noise unit below.  Measured on the
+# CPU (tests/test_oracle_network.py emulates it): strictly sequential fp32 accumulation has a
+# standard deviation of 0.16 noise units, blocked or pairwise orders less.  0.25 is taken.
+ACCUMULATION_NOISE = 0.25
+
+
+def _storage_ulp(v, emulate_bf16):
+    """Spacing of the storage format (bfloat16 when emulated, else fp32) at magnitude |v|."""
+    v = np.abs(np.asarray(v, np.float64))
+    out = np.zeros_like(v)
+    nz = v > 0
+    out[nz] = 2.0 ** (np.floor(np.log2(v[nz])) - (7 if emulate_bf16 else 23))
+    return out
+
+
+def _largest_single_term(jump, absW, top=16):
+    """Upper bound of max_j jump[i, j] * absW[j, k] for every (i, k): exact over each row's `top`
+    largest jumps, and (largest remaining jump of the row) * (largest |w| of the column) for the
+    rest.  jump >= 0, mostly zero."""
+    n, J = jump.shape
+    t = min(top, J)
+    idx = np.argpartition(-jump, t - 1, axis=1)[:, :t] if t < J else np.tile(np.arange(J), (n, 1))
+    best = np.zeros((n, absW.shape[1]))
+    rest = jump.copy()
+    for c in range(t):
+        jc = idx[:, c]
+        vals = jump[np.arange(n), jc]
+        live = vals > 0
+        if live.any():
+            best[live] = np.maximum(best[live], vals[live, None] * absW[jc[live]])
+        rest[np.arange(n), jc] = 0.0
+    return np.maximum(best, rest.max(axis=1)[:, None] * absW.max(axis=0)[None, :])
+
+
+def _largest_single_term_conv(jump, absW, stride):
+    """The same bound for a 3x3 convolution (zero padding 1): rows are the output pixels'
+    3 x 3 x Cin patches of `jump`, taken a few samples at a time."""
+    n, H, Wd, C = jump.shape
+    Ho = (H + 2 - 3) // stride + 1
+    Wo = (Wd + 2 - 3) // stride + 1
+    out = np.zeros((n, Ho, Wo, absW.shape[3]))
+    Wm = absW.reshape(9 * C, -1)
+    step = max(1, (1 << 22) // max(1, Ho * Wo * 9 * C))
+    for i0 in range(0, n, step):
+        jp = np.pad(jump[i0:i0 + step], ((0, 0), (1, 1), (1, 1), (0, 0)))
+        if not jp.any():
+            continue
+        taps = [jp[:, kh:kh + stride * (Ho - 1) + 1:stride, kw:kw + stride * (Wo - 1) + 1:stride, :]
+                for kh in range(3) for kw in range(3)]
+        rows = np.stack(taps, axis=3).reshape(-1, 9 * C)
+        out[i0:i0 + step] = _largest_single_term(rows, Wm).reshape(-1, Ho, Wo, Wm.shape[1])
+    return out
+
+
+def ambiguous_relu_units(spec, params, x, emulate_bf16=False, band=6.0):
     """ReLU units whose 0/1 derivative two correct implementations may decide differently.
 
-    relu'(z) is a decision on a computed number.  An fp32 accumulation of K products a_j w_j
-    is uncertain by about 2^-24 sqrt(K) sqrt(sum_j a_j^2 w_j^2) (one "noise unit"); `band`
-    noise units are taken as the uncertainty dz of a first-layer pre-activation.  A stored
-    activation can then differ between implementations by da = q(relu(z+dz)) - q(relu(z-dz)),
-    where q is the storage rounding (bfloat16 when emulated: one unit in the last place
-    whenever a rounding boundary lies inside the interval); the next layer's uncertainty is
-    dz' = band * noise' + da @ |W'|, and so on.  A unit is ambiguous when |z| <= dz.
+    relu'(z) is a decision on a computed number.  Two implementations' values of a
+    pre-activation differ by a random dz.  For every stored tensor two things are carried along:
+
+    * var and mad: the variance and the mean absolute value of the difference of the two
+      implementations' STORED values.  A pre-activation that differs by dz (standard deviation
+      s, mean absolute value e <= 0.8 s), stored in a format whose spacing at that magnitude is
+      u, is rounded to different neighbours with probability E|dz| / u (a rounding boundary lies
+      between the two values) and then differs by u: the stored values differ by e on average
+      again, and var = s^2 + min(e u, u^2).  Mean absolute values add through a layer
+      (triangle inequality), e' <= 0.8 (accumulation noise) + mad @ |W|; next to e' <= 0.8 s' this
+      matters where upstream differences are rare, so that s' overstates the typical dz'.
+    * jump: the largest difference the storage rounding alone can cause with a probability
+      worth counting, q(z + band s) - q(z - band s) (zero unless a rounding boundary lies
+      inside; always zero for fp32 storage, whose differences are the continuous part already
+      counted in var).
+
+    A layer z' = a W + b then has s'^2 = (ACCUMULATION_NOISE noise units)^2 + var @ W^2
+    (independent contributions add in variance), and its half-width is
+        h' = band * s' + max_j jump_j |W_jk|
+    -- `band` standard deviations for the many small contributions, plus, in full, the largest
+    single rounding jump: upstream differences are rare (a handful per row) and one of them alone
+    can be several standard deviations, which a variance cannot bound.  A unit is ambiguous when
+    |z| <= h.  Normalisation, addition and pooling propagate (var, jump) by the same rules.
 
     Returns {layer index: boolean array shaped like that layer's output}.  Everything outside
     these sets is decided identically by any implementation within the noise model.
     """
     P = _f64_params(params, emulate_bf16)
     a = _q(np.asarray(x, np.float64), emulate_bf16)
-    da = np.zeros_like(a)
+    var = np.zeros_like(a)
+    mad = np.zeros_like(a)
+    jump = np.zeros_like(a)
     n = a.shape[0]
     out, pi = {}, 0
-    kept = {}                                   # layer index -> (stored output, its uncertainty)
+    kept = {}                                   # layer index -> (stored output, var, mad, jump)
     n_layers = len(spec["layers"])
     for li, L in enumerate(spec["layers"]):
         if L["kind"] == "dense":
             W, b = P[pi]; pi += 1
-            a2, da2 = a.reshape(n, -1), da.reshape(n, -1)
+            a2, v2, j2 = a.reshape(n, -1), var.reshape(n, -1), jump.reshape(n, -1)
             z = a2 @ W + b
-            noise = np.sqrt((a2 * a2) @ (W * W)) * np.sqrt(W.shape[0])
-            dz = band * 2.0 ** -24 * noise + da2 @ np.abs(W)
+            unit = 2.0 ** -24 * np.sqrt(W.shape[0]) * np.sqrt((a2 * a2) @ (W * W))
+            s = np.sqrt((ACCUMULATION_NOISE * unit) ** 2 + v2 @ (W * W))
+            e = 0.8 * ACCUMULATION_NOISE * unit + mad.reshape(n, -1) @ np.abs(W)
+            single = _largest_single_term(j2, np.abs(W)) if j2.any() else 0.0
         elif L["kind"] == "conv3x3":
             W, b = P[pi]; pi += 1
             z = conv3x3_forward(a, W, b, L["stride"])
-            noise = np.sqrt(conv3x3_forward(a * a, W * W, 0.0, L["stride"])) * np.sqrt(9 * W.shape[2])
-            dz = band * 2.0 ** -24 * noise + conv3x3_forward(da, np.abs(W), 0.0, L["stride"])
+            unit = 2.0 ** -24 * np.sqrt(9 * W.shape[2]) * \
+                np.sqrt(conv3x3_forward(a * a, W * W, 0.0, L["stride"]))
+            s = np.sqrt((ACCUMULATION_NOISE * unit) ** 2 + conv3x3_forward(var, W * W, 0.0, L["stride"]))
+            e = 0.8 * ACCUMULATION_NOISE * unit + conv3x3_forward(mad, np.abs(W), 0.0, L["stride"])
+            single = _largest_single_term_conv(jump, np.abs(W), L["stride"])
         elif L["kind"] == "bn":
-            # y = gamma (x - mu) rstd + beta.  An input uncertainty dx moves x - mu by at most
-            # dx + mean(dx) and the standard deviation by at most sqrt(mean(dx^2)); the fp32
-            # statistics of an implementation add a relative 2^-20.
+            # y = gamma (x - mu) rstd + beta over this mini-batch.  dx moves x - mu by dx - mean(dx)
+            # and the variance by mean(2 (x - mu) dx): relative to rstd that is a standard
+            # deviation of rstd sqrt(mean(var) / m) over the m rows, plus 2^-20 for the fp32
+            # statistics of an implementation.
             gamma, beta = P[pi]; pi += 1
             z, xhat, rstd = batchnorm_forward(a, gamma, beta, L["eps"])
             axes = tuple(range(a.ndim - 1))
-            rel = rstd * np.sqrt((da * da).mean(axis=axes)) + 2.0 ** -20
-            dz = np.abs(gamma) * (rstd * (da + da.mean(axis=axes)) + np.abs(xhat) * rel) \
-                + 2.0 ** -22 * np.abs(z)
+            m_rows = a.size // a.shape[-1]
+            mean_var = var.mean(axis=axes)
+            rel = rstd * np.sqrt(mean_var / m_rows) + 2.0 ** -20
+            s = np.sqrt((gamma * rstd) ** 2 * (var + mean_var / m_rows) + (gamma * xhat * rel) ** 2
+                        + (2.0 ** -22 * z) ** 2)
+            single = np.abs(gamma) * rstd * (jump + jump.max(axis=axes) / m_rows)
+            e = 0.8 * s
         elif L["kind"] == "add":
-            s_a, s_da = kept[L["skip_from"]]
+            s_a, s_var, s_mad, s_jump = kept[L["skip_from"]]
             z = a + s_a
-            dz = da + s_da + 2.0 ** -23 * np.abs(z)
-        else:                                   # global average pool
+            s = np.sqrt(var + s_var + (2.0 ** -23 * z) ** 2)
+            single = jump + s_jump
+            e = mad + s_mad + 2.0 ** -23 * np.abs(z)
+        else:                                   # global average pool over m pixels
+            m_pix = a.shape[1] * a.shape[2]
             z = a.mean(axis=(1, 2))
-            dz = da.mean(axis=(1, 2)) + 2.0 ** -22 * np.abs(z)
-        lo, hi = z - dz, z + dz
+            s = np.sqrt(var.mean(axis=(1, 2)) / m_pix + (2.0 ** -22 * z) ** 2)
+            single = jump.max(axis=(1, 2)) / m_pix
+            e = mad.mean(axis=(1, 2)) + 2.0 ** -22 * np.abs(z)
+        e = np.minimum(e, 0.8 * s)
+        h = band * s + single
         if L.get("relu"):
-            out[li] = np.abs(z) <= dz
-            z, lo, hi = np.maximum(z, 0.0), np.maximum(lo, 0.0), np.maximum(hi, 0.0)
+            out[li] = np.abs(z) <= h
         if li == n_layers - 1:
             break
-        a = _q(z, emulate_bf16)
-        da = _q(hi, emulate_bf16) - _q(lo, emulate_bf16)
-        kept[li] = (a, da)
+        relu = bool(L.get("relu"))
+        clip = (lambda t: np.maximum(t, 0.0)) if relu else (lambda t: t)
+        a = _q(clip(z), emulate_bf16)
+        u = _storage_ulp(clip(z + h) if relu else np.abs(z) + h, emulate_bf16)
+        var = s * s + np.minimum(e * u, u * u)
+        mad = e
+        if relu:                                    # where both implementations store zero
+            var = np.where(z + h > 0.0, var, 0.0)
+            mad = np.where(z + h > 0.0, mad, 0.0)
+        g = band * s          # (not h: a rare jump caused by a rare jump upstream is not counted)
+        jump = (_q(clip(z + g), True) - _q(clip(z - g), True)) if emulate_bf16 else np.zeros_like(z)
+        kept[li] = (a, var, mad, jump)
     return out
 
 

@@ -82,7 +82,7 @@ def _resolved_generic(spec, params, x, y, got, emulate_bf16, band):
     return final, loss, n_amb, flipped
 
 
-def resolved_reference(spec, params, x, y, got, emulate_bf16=False, band=8.0):
+def resolved_reference(spec, params, x, y, got, emulate_bf16=False, band=6.0):
     """(reference [(dW, db)], loss, #ambiguous units, #units decided differently from the checker).
 
     x, y: one worker's mini-batch; got: that worker's gradient under test as [(dW, db)].

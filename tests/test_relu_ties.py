@@ -135,3 +135,125 @@ def test_generic_route_does_not_explain_away_a_wrong_clear_cut_unit():
     _, got = on.loss_and_gradient(spec, params, x, y, True, relu_masks=wrong)
     ref, _, _, _ = resolved_reference(spec, params, x, y, got, True)
     assert maxdiff(got, ref) > 1e-6
+
+
+# ---- the band itself: pinned from below and from above by second implementations ----------
+def _fp32_library_masks(spec, params, x, bf16):
+    """ReLU decisions of an independent implementation: torch's fp32 CPU routines (their own
+    summation orders), bfloat16 storage at the points where the checker emulates it."""
+    import torch
+    import torch.nn.functional as F
+    q = (lambda t: t.bfloat16().float()) if bf16 else (lambda t: t)
+    f32 = lambda v: torch.from_numpy(np.ascontiguousarray(v, np.float32))
+    a = q(f32(x))
+    if a.ndim == 4:
+        a = a.permute(0, 3, 1, 2).contiguous()
+    stored, masks, pi = [], {}, 0
+    for li, L in enumerate(spec["layers"]):
+        stored.append(a)
+        if L["kind"] == "dense":
+            W, b = params[pi]; pi += 1
+            a = a.reshape(a.shape[0], -1) @ q(f32(W)) + f32(b)
+        elif L["kind"] == "conv3x3":
+            W, b = params[pi]; pi += 1
+            a = F.conv2d(a, q(f32(W)).permute(3, 2, 0, 1).contiguous(), f32(b), stride=L["stride"],
+                         padding=1)
+        elif L["kind"] == "bn":
+            g, b = params[pi]; pi += 1
+            a = F.batch_norm(a, None, None, f32(g), f32(b), True, 0.0, L["eps"])
+        elif L["kind"] == "add":
+            a = a + stored[L["skip_from"] + 1]
+        else:
+            a = a.mean(dim=(2, 3))
+        if L.get("relu"):
+            a = torch.relu(a)
+        if li < len(spec["layers"]) - 1:
+            a = q(a)
+        if L.get("relu"):
+            m = (a > 0).numpy()
+            masks[li] = m.transpose(0, 2, 3, 1) if m.ndim == 4 else m
+    return masks
+
+
+def _sequential_fp32_masks(spec, params, x):
+    """ReLU decisions of a dense bf16 model whose products are accumulated one by one in fp32,
+    in index order -- the least accurate order an implementation would use."""
+    P = [(on.round_bf16(W).astype(np.float32), np.asarray(b, np.float32)) for W, b in params]
+    a = on.round_bf16(x).astype(np.float32)
+    masks = {}
+    for li, (W, b) in enumerate(P[:-1]):
+        acc = np.zeros((a.shape[0], W.shape[1]), np.float32)
+        for k in range(W.shape[0]):
+            acc += a[:, k:k + 1] * W[k:k + 1, :]        # (float32 product, float32 sum)
+        a = on.round_bf16(np.maximum(acc + b, 0.0)).astype(np.float32)
+        masks[li] = a > 0
+    return masks
+
+
+def _varied_norm_params(params, seed):
+    rng = np.random.default_rng(seed)
+    return [(W, b) if np.ndim(W) > 1 else
+            ((1 + 0.2 * rng.standard_normal(W.shape)).astype(np.float32),
+             (0.2 * rng.standard_normal(b.shape)).astype(np.float32)) for W, b in params]
+
+
+BAND_CASES = {
+    "mlp bf16": (lambda: synth.mlp_spec([1024, 1024, 1024, 1024, 10], "bf16"), 256, "normal"),
+    "mlp fp32": (lambda: synth.mlp_spec([512, 512, 512, 10], "f32"), 256, "normal"),
+    "cnn bf16": (lambda: synth.cnn_spec("bf16"), 24, "uniform"),
+    "residual bf16 (normalisation, addition, pooling)":
+        (lambda: synth.resnet_block_spec(32, (16, 16, 3), 10, 2), 32, "uniform"),
+}
+
+
+@pytest.mark.parametrize("name", list(BAND_CASES))
+def test_band_contains_every_decision_of_an_fp32_library_implementation(name):
+    make, n, dist = BAND_CASES[name]
+    spec = make()
+    bf = spec["dtype"] == "bf16"
+    params = _varied_norm_params(synth.init_params(spec, "he", 5), 1)
+    x, _ = synth.make_batch(spec, dist, n, 5, 0)
+    theirs = _fp32_library_masks(spec, params, x, bf)
+    ours = on.relu_masks_of(spec, params, x, bf)
+    amb = on.ambiguous_relu_units(spec, params, x, bf)
+    assert sorted(amb) == sorted(ours)
+    for li in ours:
+        differ = theirs[li] != ours[li]
+        assert not (differ & ~amb[li]).any(), (name, li, int((differ & ~amb[li]).sum()))
+        # ... and the band is a band: a small part of the layer even behind two residual blocks
+        assert amb[li].mean() < (0.15 if "residual" in name else 2e-3), (name, li, amb[li].mean())
+
+
+def test_band_against_sequential_fp32_accumulation_from_below_and_above():
+    # the noisiest plausible implementation of the wide-MLP workload's layers: every decision it
+    # takes differently lies inside the band, and the band is not much larger than what it has
+    # to cover: a band of `band` = 6 standard deviations around zero holds about 2.5 * 6 times as
+    # many units as a noise of one standard deviation flips; the noise constant (taken 1.5 times
+    # the sequential sum's), the variance bound of rounded values and the single-jump term make
+    # up the rest.  (The interval-arithmetic band this replaced held 2400 times the flips.)
+    spec = synth.mlp_spec([2048, 2048, 2048, 2048, 10], "bf16")
+    params = synth.init_params(spec, "he", 6)
+    x, _ = synth.make_batch(spec, "normal", 1024, 6, 0)
+    theirs = _sequential_fp32_masks(spec, params, x)
+    ours = on.relu_masks_of(spec, params, x, True)
+    amb = on.ambiguous_relu_units(spec, params, x, True)
+    flips = sum(int((theirs[li] != ours[li]).sum()) for li in ours)
+    inside = sum(int(((theirs[li] != ours[li]) & amb[li]).sum()) for li in ours)
+    n_amb = sum(int(a.sum()) for a in amb.values())
+    assert flips >= 10, flips                        # the test bites
+    assert inside == flips
+    print("sequential fp32: %d decisions differ, %d units in the band" % (flips, n_amb))
+    assert n_amb <= 200 * flips, (n_amb, flips)
+
+
+def test_accumulation_noise_constant_covers_sequential_fp32_sums():
+    rng = np.random.default_rng(0)
+    K = 2048
+    a = on.round_bf16(rng.standard_normal((64, K)))
+    W = on.round_bf16(rng.standard_normal((K, 128)) * K ** -0.5)
+    acc = np.zeros((64, 128), np.float32)
+    for k in range(K):
+        acc += a[:, k:k + 1].astype(np.float32) * W[k:k + 1, :].astype(np.float32)
+    unit = 2.0 ** -24 * np.sqrt(K) * np.sqrt((a * a) @ (W * W))
+    sd = float(np.std((acc.astype(np.float64) - a @ W) / unit))
+    assert 0.08 < sd < on.ACCUMULATION_NOISE, sd
