@@ -52,6 +52,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the short runs of the four smaller workloads")
     ap.add_argument("--aggregate", choices=["gradient", "update", "pass"], default="gradient",
                     help="where the weighted aggregation runs: inside the weight-gradient kernel "
                          "(dynb_forward_backward_aggregate, default), inside the update kernel "
@@ -115,13 +117,22 @@ def main():
 
     for _ in range(args.warmup):
         one_step()
+    # K steps between two synchronisations (the wall-clock figure `value` is computed from), each
+    # step also bracketed by HIP events on the launch stream (torch's current stream is the one
+    # the binding hands to the library)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record()
+    for i in range(args.steps):
         one_step()
+        marks[i + 1].record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = 1e3 * elapsed / args.steps
+    step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
+    median_ms = step_ms[len(step_ms) // 2] if len(step_ms) % 2 else \
+        0.5 * (step_ms[len(step_ms) // 2 - 1] + step_ms[len(step_ms) // 2])
     timed_splits = state["trace"][args.warmup:]
 
     # the same step on two fixed splits: uniform (no raggedness) and an adversarial one whose
@@ -145,6 +156,26 @@ def main():
             torch.cuda.synchronize()
             dt = (time.perf_counter() - t1) / args.steps
             other[name] = {"b": bs, "ms_per_step": 1e3 * dt, "samples_per_s": G / dt}
+
+    # the weighted aggregation as a pass of its own over the gradients the last step wrote
+    # (dynb_weighted_aggregate: K reads + 1 write of P_pad floats), event-timed
+    agg_pass = None
+    if not args.copy_calibration:
+        b_last = timed_splits[-1]
+        reps = max(5, args.steps)
+        for _ in range(2):
+            binding.weighted_aggregate(grads, b_last, Pp, out)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+        ev[0].record()
+        for i in range(reps):
+            binding.weighted_aggregate(grads, b_last, Pp, out)
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        ts = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(reps))
+        ms = ts[len(ts) // 2]
+        nbytes_agg = (K + 1) * Pp * 4
+        agg_pass = {"ms": ms, "bytes": nbytes_agg, "gbps": nbytes_agg / ms / 1e6,
+                    "frac_of_hbm_peak": nbytes_agg / ms / 1e6 / PEAK["hbm"]}
 
     if args.copy_calibration:
         n = args.copy_calibration * (1 << 20) // 4
@@ -195,19 +226,87 @@ def main():
         "config": {"workload": "configs[%d]: %s" % (cfg["index"], cfg["name"]), "global_batch": G,
                    "workers": K, "b_timed_first": timed_splits[0], "b_timed_last": timed_splits[-1],
                    "params": P},
+        "ms_per_step_median_events": median_ms,
         "roofline": roofline,
         "other_splits": other,
         "kernels": kernels,
     }
+    # the HBM-bound parts against the 8 TB/s peak (algorithmic bytes / event-timed duration) and
+    # the matrix products against the bf16 MFMA peak
+    frac = {}
+    for name, peak_key, field in (("gemm_wgrad", "hbm", "gbps"), ("sgd_update", "hbm", "gbps"),
+                                  ("gemm_fwd", "mfma_bf16" if bf else "fp32", "tflops"),
+                                  ("gemm_dgrad", "mfma_bf16" if bf else "fp32", "tflops")):
+        if name in kernels:
+            frac[name] = {"achieved": kernels[name][field],
+                          "unit": "GB/s" if field == "gbps" else "TFLOP/s",
+                          "peak": PEAK[peak_key], "frac": kernels[name][field] / PEAK[peak_key]}
+    if agg_pass:
+        frac["weighted_aggregate_pass"] = {"achieved": agg_pass["gbps"], "unit": "GB/s",
+                                           "peak": PEAK["hbm"], "frac": agg_pass["frac_of_hbm_peak"],
+                                           "ms": agg_pass["ms"]}
+    result["fractions_of_peak"] = frac
+    if cfg["index"] == 4 and not args.copy_calibration and not args.no_other_workloads:
+        del xs, ys, grads, out
+        torch.cuda.empty_cache()
+        result["other_workloads"] = {"configs[%d]" % i: small_workload(i) for i in range(4)}
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, timed_splits[-1])
     print(json.dumps(result))
 
 
+def small_workload(ci, steps=30, warmup=5):
+    """Throughput of one of the other workloads: the same step (gradients with their aggregate,
+    update, controller) over the batch sizes its controller produces; event-timed median."""
+    import torch
+    from paper_2305_12213_amd import binding, synth
+    cfg = synth.config(ci)
+    spec, seed = cfg["spec"], synth.BASE_SEED + ci
+    G, K = cfg["global_batch"], cfg["K"]
+    model = binding.Model(spec)
+    Pp = model.padded_params()
+    params = torch.from_numpy(synth.flatten_params(synth.init_params(spec, cfg["init"], seed), 256)).cuda()
+    nbytes = model.workspace_bytes(G, K)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    model.bind(params, ws, nbytes, G, K)
+    grads = torch.empty(K, Pp, device="cuda"); out = torch.empty(Pp, device="cuda")
+    velocity = torch.zeros(Pp, device="cuda") if cfg["momentum"] else None
+    opt = binding.make_optimizer("momentum" if cfg["momentum"] else "sgd", lr=cfg["lr"],
+                                 momentum=cfg["momentum"])
+    batches = []
+    for s in range(4):
+        x, y = synth.make_batch(spec, cfg["x_dist"], G, seed, s)
+        batches.append((torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda()))
+    b = list(cfg["b0"])
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    torch.cuda.synchronize()
+    t0 = 0.0
+    for i in range(warmup + steps):
+        if i == warmup:
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            ev[0].record()
+        x, y = batches[i % len(batches)]
+        binding.forward_backward_aggregate(model, x, y, b, grads, out)
+        binding.model_update(model, out, opt, velocity)
+        b = binding.controller_step(synth.iteration_times(b, cfg["speeds"]), b, G, cfg["gains"])
+        if i >= warmup:
+            ev[i - warmup + 1].record()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) / steps
+    ts = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(steps))
+    med = ts[len(ts) // 2]
+    return {"workload": cfg["name"], "global_batch": G, "workers": K, "b_last": b,
+            "ms_per_step_median_events": med, "ms_per_step_wall": 1e3 * wall,
+            "samples_per_s": G / wall}
+
+
 def cpu_baseline(cfg, b):
-    """The CPU checker, as it stands, on a bounded sample of the same workload."""
+    """The CPU checker, as it stands (float64 numpy; its matrix products go to the BLAS numpy is
+    linked with), on the host cores this process may use: one whole step of the workload on all
+    of them, and a scaled-down step (the smallest workers of the same split) on one thread."""
     import numpy as np
-    from threadpoolctl import threadpool_info
+    from threadpoolctl import threadpool_limits
     from oracle import network as on
     from paper_2305_12213_amd import synth
 
@@ -216,6 +315,9 @@ def cpu_baseline(cfg, b):
     bf = spec["dtype"] == "bf16"
     params = synth.init_params(spec, cfg["init"], seed)
     x, y = synth.make_batch(spec, cfg["x_dist"], G, seed, 0)
+    cores = len(os.sched_getaffinity(0))
+    # (the box exports the thread count its share of the machine allows)
+    threads = min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)))
 
     def step(bs, xs, ys):
         t0 = time.perf_counter()
@@ -224,31 +326,28 @@ def cpu_baseline(cfg, b):
         on.sgd_update(params, agg, cfg["lr"])
         return time.perf_counter() - t0
 
-    # calibrate on the smallest workers, then take as many whole workers (largest last) as fit the budget
+    with threadpool_limits(limits=threads):
+        dt_all = step(list(b), x, y)
+    # one thread: the smallest workers of the split, about 1/64 of the batch
     order = sorted(range(len(b)), key=lambda k: b[k])
-    small = [k for k in order if b[k] > 0][:max(1, len(b) // 2)]
     off = np.concatenate([[0], np.cumsum(b)])
-    def rows(ks):
-        idx = np.concatenate([np.arange(off[k], off[k + 1]) for k in ks]) if ks else np.arange(0)
-        return x[idx], y[idx]
-    xs, ys = rows(small)
-    dt = step([b[k] for k in small], xs, ys)
-    per_sample = dt / max(1, sum(b[k] for k in small))
-    budget, chosen, used = 30.0, [], 0.0
+    chosen, n = [], 0
     for k in order:
         if b[k] == 0:
             continue
-        cost = per_sample * b[k]
-        if chosen and used + cost > budget:
+        if chosen and n + b[k] > max(1, G // 64):
             break
-        chosen.append(k); used += cost
-    xs, ys = rows(chosen)
-    bs = [b[k] for k in chosen]
-    dt = step(bs, xs, ys)
-    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    return {"value": sum(bs) / dt, "unit": "samples/s", "cores": threads, "kind": "oracle",
-            "sample": "one step (per-worker fwd+bwd, aggregate, update) over workers %s of the "
-                      "timed split, %d of %d samples, %.1f s" % (sorted(chosen), sum(bs), G, dt)}
+        chosen.append(k); n += b[k]
+    idx = np.concatenate([np.arange(off[k], off[k + 1]) for k in sorted(chosen)])
+    with threadpool_limits(limits=1):
+        dt_one = step([b[k] for k in sorted(chosen)], x[idx], y[idx])
+    return {"value": G / dt_all, "unit": "samples/s", "cores": threads,
+            "cores_available": cores, "kind": "oracle (numpy float64, BLAS matrix products)",
+            "sample": "one whole step (per-worker fwd+bwd, aggregate, update) of the timed split, "
+                      "%d samples in %.1f s on %d threads" % (G, dt_all, threads),
+            "one_thread": {"value": n / dt_one, "unit": "samples/s",
+                           "sample": "the same step over workers %s of the split, %d of %d "
+                                     "samples, %.1f s" % (sorted(chosen), n, G, dt_one)}}
 
 
 if __name__ == "__main__":

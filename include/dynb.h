@@ -300,6 +300,18 @@ int dynb_ewma_update(double* mu, const double* t, int32_t K, double alpha, int32
  * K * b0 kept ("Static Mini-batch Allocation Policy"), largest-remainder rounding. */
 int dynb_static_allocate(const double* X, int32_t K, int32_t b0, int32_t* b_out);
 
+/* Throughput estimates for dynb_static_allocate from the servers' resources (same section,
+ * paragraph "Estimating throughput"): X_k = number of CPU cores when the workers use only CPUs
+ * (no worker states a FLOPs figure: half_precision_flops == 0 for all), X_k = the server's
+ * half-precision FLOPs when CPU and GPU servers are mixed (stated, > 0, for all).  r: host [K];
+ * X_out: host [K].  DYNB_ERR_BADARG: null pointer, K out of range, FLOPs stated for some
+ * workers only, a negative or non-finite figure, no cores where cores are the estimate. */
+typedef struct {
+  int32_t cpu_cores;
+  double half_precision_flops;
+} dynb_worker_resources;
+int dynb_estimate_throughput(const dynb_worker_resources* r, int32_t K, double* X_out);
+
 /* ---- per-kernel timing (measurement aid) ---------------------------------------- */
 
 /* When enabled, every kernel launch is bracketed by HIP events on its stream and

@@ -196,6 +196,24 @@ def static_allocation(X, b0):
     return largest_remainder(q, G)
 
 
+def estimate_throughput(cpu_cores, half_precision_flops):
+    """Throughput estimates X_k from the servers' resources (Section "Static Mini-batch
+    Allocation Policy", paragraph "Estimating throughput"): the number of CPU cores when the
+    workers use only CPUs (no worker states a FLOPs figure), the half-precision FLOPs of each
+    server when CPU and GPU servers are mixed (every worker states one).  Only the ratios
+    matter to static_allocation()."""
+    flops = [float(v) for v in half_precision_flops]
+    if all(v == 0.0 for v in flops):
+        X = [float(c) for c in cpu_cores]
+    elif all(v > 0.0 for v in flops):
+        X = flops
+    else:
+        raise ValueError("either every worker or no worker states its half-precision FLOPs")
+    if any(not (v > 0.0) or not math.isfinite(v) for v in X):
+        raise ValueError("resources must be positive and finite")
+    return X
+
+
 class DynamicBatcher:
     """The controller with its state between iterations (subsection "Control stability"):
     the smoothed iteration times since the last readjustment, the current sizes, and the

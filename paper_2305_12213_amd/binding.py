@@ -30,6 +30,7 @@ SYMBOLS = [
     "dynb_controller_read",
     "dynb_profile_enable", "dynb_profile_reset", "dynb_profile_collect",
     "dynb_profile_num_classes", "dynb_profile_name", "dynb_profile_get",
+    "dynb_estimate_throughput",
 ]
 
 
@@ -68,6 +69,10 @@ class Optimizer(C.Structure):
 class ControllerConfig(C.Structure):
     _fields_ = [("gains", Gains), ("drop_tolerance", C.c_double),
                 ("min_observations", C.c_int32), ("adaptive_b_max", C.c_int32)]
+
+
+class WorkerResources(C.Structure):
+    _fields_ = [("cpu_cores", C.c_int32), ("half_precision_flops", C.c_double)]
 
 
 _lib = None
@@ -123,6 +128,7 @@ def load():
         "dynb_profile_num_classes": (i32, []),
         "dynb_profile_name": (C.c_char_p, [i32]),
         "dynb_profile_get": (C.c_int, [i32, pf64, C.POINTER(i64), pf64, pf64]),
+        "dynb_estimate_throughput": (C.c_int, [C.POINTER(WorkerResources), i32, pf64]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -321,6 +327,15 @@ def static_allocate(X, b0):
     out = (C.c_int32 * K)()
     _check(load().dynb_static_allocate(_f64(X), K, int(b0), out))
     return [int(v) for v in out]
+
+
+def estimate_throughput(cpu_cores, half_precision_flops):
+    K = len(cpu_cores)
+    r = (WorkerResources * K)(*[WorkerResources(int(c), float(f))
+                                for c, f in zip(cpu_cores, half_precision_flops)])
+    out = (C.c_double * K)()
+    _check(load().dynb_estimate_throughput(r, K, out))
+    return [float(v) for v in out]
 
 
 class Controller:

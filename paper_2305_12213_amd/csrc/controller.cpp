@@ -299,6 +299,26 @@ extern "C" int dynb_static_allocate(const double* X, int32_t K, int32_t b0, int3
   return DYNB_OK;
 }
 
+extern "C" int dynb_estimate_throughput(const dynb_worker_resources* r, int32_t K, double* X_out) {
+  if (!r || !X_out) return dynb::fail(DYNB_ERR_BADARG, "estimate_throughput: null pointer");
+  if (K < 1 || K > DYNB_MAX_WORKERS) return dynb::fail(DYNB_ERR_BADARG, "estimate_throughput: bad K");
+  int with_flops = 0;
+  for (int k = 0; k < K; ++k) {
+    if (!std::isfinite(r[k].half_precision_flops) || r[k].half_precision_flops < 0.0)
+      return dynb::fail(DYNB_ERR_BADARG, "estimate_throughput: FLOPs of worker %d not finite or negative", k);
+    if (r[k].half_precision_flops > 0.0) ++with_flops;
+  }
+  if (with_flops != 0 && with_flops != K)
+    return dynb::fail(DYNB_ERR_BADARG,
+                      "estimate_throughput: either every worker or no worker states its FLOPs");
+  for (int k = 0; k < K; ++k) {
+    if (with_flops == 0 && r[k].cpu_cores < 1)
+      return dynb::fail(DYNB_ERR_BADARG, "estimate_throughput: worker %d has no CPU cores", k);
+    X_out[k] = with_flops ? r[k].half_precision_flops : (double)r[k].cpu_cores;
+  }
+  return DYNB_OK;
+}
+
 extern "C" int dynb_lr_schedule(int64_t step, const int64_t* boundaries, const double* values,
                                 int32_t n_values, double* lr) {
   if (!values || !lr || (n_values > 1 && !boundaries))

@@ -108,6 +108,15 @@ def test_ewma_and_static_allocation_match_oracle():
         b0 = int(rng.integers(1, 600))
         assert binding.static_allocate(X, b0) == oc.static_allocation(X, b0)
     assert binding.static_allocate([0.813, 0.187], 500) == [813, 187]
+    # the estimators in front of it: core counts, or half-precision FLOPs when mixed
+    for cores, flops in (([3, 5, 12], [0, 0, 0]), ([8, 48], [0.813e14, 0.187e14]),
+                         ([1], [0]), ([64] * 7, [float(i + 1) for i in range(7)])):
+        assert binding.estimate_throughput(cores, flops) == oc.estimate_throughput(cores, flops)
+    assert binding.static_allocate(binding.estimate_throughput([3, 5, 12], [0, 0, 0]), 100) == [45, 75, 180]
+    for cores, flops in (([8, 48], [1e14, 0]), ([8, 0], [0, 0]), ([8, 8], [-1.0, 1.0]),
+                         ([8, 8], [float("nan"), 1.0])):
+        with pytest.raises(binding.DynbError):
+            binding.estimate_throughput(cores, flops)
 
 
 def test_model_description_is_validated_on_the_host():

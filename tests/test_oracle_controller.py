@@ -34,7 +34,23 @@ def test_static_allocation_reproduces_the_papers_gpu_cpu_ratio():
     for X, b0, want in read_rows("static_allocation_example.txt"):
         got = oc.static_allocation([float(v) for v in X], int(b0[0]))
         assert got == [int(v) for v in want]
-        assert abs(got[0] / got[1] - 4.3) < 0.1          # "only 4.3x faster"
+        if len(got) == 2:
+            assert abs(got[0] / got[1] - 4.3) < 0.1      # "only 4.3x faster"
+
+
+def test_throughput_estimates_from_cores_or_half_precision_flops():
+    # CPU-only workers: core counts (the paper's three workers with 3, 5 and 12 cores)
+    X = oc.estimate_throughput([3, 5, 12], [0, 0, 0])
+    assert X == [3.0, 5.0, 12.0]
+    assert oc.static_allocation(X, 100) == [45, 75, 180]
+    # mixed CPU / GPU servers: half-precision FLOPs, whatever the core counts say; the paper's
+    # GPU : CPU FLOPs ratio 0.813 : 0.187 gives its batch-size ratio
+    X = oc.estimate_throughput([8, 48], [0.813e14, 0.187e14])
+    assert oc.static_allocation(X, 500) == [813, 187]
+    with pytest.raises(ValueError):
+        oc.estimate_throughput([8, 48], [1e14, 0])          # stated for some workers only
+    with pytest.raises(ValueError):
+        oc.estimate_throughput([8, 0], [0, 0])
 
 
 def test_raw_step_equals_closed_form_b_tbar_over_t():
