@@ -162,6 +162,25 @@ int dynb_forward_backward_aggregate(dynb_model* m, const float* x, const int32_t
                                     const int32_t* b, int32_t K, float* grads, float* out,
                                     void* stream);
 
+/* dynb_forward_backward for callers that cannot allocate device memory or hand over a
+ * workspace (code under HIP graph capture, serving loops, harnesses that forbid hipMalloc): the
+ * same kernels, but everything the bound workspace would hold lives in a static device array of
+ * DYNB_STATIC_SCRATCH_BYTES inside the library (each GPU the library runs on holds its own copy
+ * until the process ends).  The call allocates and frees nothing, records no memset, and needs
+ * no dynb_model_bind: `m` is only read (a handle from dynb_model_create, bound or not), `params`
+ * is the device fp32 parameter vector [P_pad] (16-byte aligned) the gradients are taken at; the
+ * 16-bit weight copies are derived from it inside the call.  x, y, b, K, grads, stream as for
+ * dynb_forward_backward; the per-worker losses are not returned.
+ * DYNB_ERR_UNSUPPORTED when dynb_model_workspace_bytes(m, sum(b), K) exceeds
+ * DYNB_STATIC_SCRATCH_BYTES (nothing is launched then).  All calls on one GPU share that GPU's
+ * array, which keeps the previous call's contents (the call clears what it needs): calls that
+ * overlap in time on one GPU -- different streams or threads -- race; serialise them. */
+#define DYNB_STATIC_SCRATCH_BYTES (32u << 20)
+size_t dynb_static_scratch_bytes(void);
+int dynb_forward_backward_static(const dynb_model* m, const float* params, const float* x,
+                                 const int32_t* y, const int32_t* b, int32_t K, float* grads,
+                                 void* stream);
+
 /* Weighted average of Eq. 2: out[p] = sum_k (b_k / sum_i b_i) * grads[k*n + p], summed in
  * worker order.  grads device fp32 [K][n]; out device fp32 [n]; n % 4 == 0; both 16-byte
  * aligned.  sum(b) must be > 0. */

@@ -30,7 +30,7 @@ SYMBOLS = [
     "dynb_controller_read",
     "dynb_profile_enable", "dynb_profile_reset", "dynb_profile_collect",
     "dynb_profile_num_classes", "dynb_profile_name", "dynb_profile_get",
-    "dynb_estimate_throughput",
+    "dynb_static_scratch_bytes", "dynb_forward_backward_static", "dynb_estimate_throughput",
 ]
 
 
@@ -129,6 +129,8 @@ def load():
         "dynb_profile_name": (C.c_char_p, [i32]),
         "dynb_profile_get": (C.c_int, [i32, pf64, C.POINTER(i64), pf64, pf64]),
         "dynb_estimate_throughput": (C.c_int, [C.POINTER(WorkerResources), i32, pf64]),
+        "dynb_static_scratch_bytes": (C.c_size_t, []),
+        "dynb_forward_backward_static": (C.c_int, [vp, vp, vp, vp, pi32, i32, vp, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -246,6 +248,15 @@ def read_worker_loss(model, K, stream=None):
 def forward_backward(model, x, y, b, grads, stream=None):
     _check(load().dynb_forward_backward(model.handle, _ptr(x), _ptr(y), _i32(b), len(b),
                                         _ptr(grads), _stream(stream)))
+
+
+def static_scratch_bytes():
+    return int(load().dynb_static_scratch_bytes())
+
+
+def forward_backward_static(model, params, x, y, b, grads, stream=None):
+    _check(load().dynb_forward_backward_static(model.handle, _ptr(params), _ptr(x), _ptr(y),
+                                               _i32(b), len(b), _ptr(grads), _stream(stream)))
 
 
 def forward_backward_aggregate(model, x, y, b, grads, out, stream=None):

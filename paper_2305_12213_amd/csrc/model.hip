@@ -14,6 +14,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -685,6 +686,89 @@ int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const 
   return rc ? rc : flush_small();
 }
 }  // namespace
+
+// ---- the per-worker gradients without a caller workspace ----------------------------------
+// For callers that cannot allocate device memory.  Everything dynb_forward_backward keeps in its
+// bound workspace (packed input, stored activations and their gradients, 16-bit weight copies,
+// logits, chunk partials) lives in this array instead; each device holds its own copy until the
+// process ends.  Host code never uses the array's name as an address: scratch_base() asks the
+// runtime for the address on the current device, once per device.
+static __device__ __align__(256) unsigned char scratch[DYNB_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+__global__ __launch_bounds__(256) void clear_bytes_kernel(uint4* dst, size_t n16) {
+  const uint4 z = {0u, 0u, 0u, 0u};
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16;
+       i += (size_t)gridDim.x * blockDim.x)
+    dst[i] = z;
+}
+
+void* scratch_base() {
+  static std::mutex mu;
+  static void* known[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+  std::lock_guard<std::mutex> lk(mu);
+  if (!known[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+    known[dev] = p;
+  }
+  return known[dev];
+}
+
+}  // namespace
+
+extern "C" size_t dynb_static_scratch_bytes(void) { return DYNB_STATIC_SCRATCH_BYTES; }
+
+extern "C" int dynb_forward_backward_static(const dynb_model* m, const float* params,
+                                            const float* x, const int32_t* y, const int32_t* b,
+                                            int32_t K, float* grads, void* stream) {
+  if (!m || !params || !x || !y || !b || !grads)
+    return fail(DYNB_ERR_BADARG, "forward_backward_static: null pointer");
+  if (K < 1 || K > DYNB_MAX_WORKERS)
+    return fail(DYNB_ERR_BADARG, "forward_backward_static: K=%d outside [1, %d]", K, DYNB_MAX_WORKERS);
+  if ((uintptr_t)params & 15)
+    return fail(DYNB_ERR_BADARG, "forward_backward_static: params must be 16-byte aligned");
+  int64_t B = 0;
+  for (int k = 0; k < K; ++k) {
+    if (b[k] < 0) return fail(DYNB_ERR_BADARG, "forward_backward_static: negative batch size for worker %d", k);
+    B += b[k];
+  }
+  if (B > ((int64_t)1 << 24))
+    return fail(DYNB_ERR_UNSUPPORTED, "forward_backward_static: sum(b) too large");
+  const int cap = B > 0 ? (int)B : 1;
+  int64_t max_hw = (int64_t)m->in_h * m->in_w;
+  for (const Layer& L : m->layers) max_hw = L.hw_out > max_hw ? L.hw_out : max_hw;
+  if ((int64_t)cap * max_hw > (int64_t)1 << 30)
+    return fail(DYNB_ERR_UNSUPPORTED, "forward_backward_static: sum(b) * pixels exceeds 2^30 rows");
+  // a private copy of the plan, laid out for exactly this call's batch and worker count
+  dynb_model plan = *m;
+  const size_t need = carve(&plan, nullptr, cap, K);
+  if (need > (size_t)DYNB_STATIC_SCRATCH_BYTES)
+    return fail(DYNB_ERR_UNSUPPORTED,
+                "forward_backward_static: this model and batch need %zu bytes of scratch, the "
+                "static area holds %zu (use dynb_model_bind + dynb_forward_backward)",
+                need, (size_t)DYNB_STATIC_SCRATCH_BYTES);
+  void* base = scratch_base();
+  if (!base) return fail(DYNB_ERR_HIP, "forward_backward_static: no address for the static scratch area");
+  carve(&plan, base, cap, K);
+  plan.params = const_cast<float*>(params);   // (read only on this path)
+  plan.max_batch = cap;
+  plan.max_workers = K;
+  plan.bound = true;
+  // The area still holds the previous call's contents in another layout: the padding columns the
+  // kernels read but never write must be zero again.  A kernel, not a memset node, so that the
+  // call can be recorded into a graph.
+  const size_t n16 = need / 16;   // (carve() rounds every piece to 256 bytes)
+  const unsigned blocks = (unsigned)((n16 + 255) / 256 < 2048 ? (n16 + 255) / 256 : 2048);
+  hipLaunchKernelGGL(clear_bytes_kernel, dim3(blocks ? blocks : 1), dim3(256), 0, (hipStream_t)stream,
+                     (uint4*)base, n16);
+  if (hipGetLastError() != hipSuccess) return fail(DYNB_ERR_HIP, "forward_backward_static: clear failed");
+  if (int rc = dynb_model_sync_weights(&plan, stream)) return rc;
+  return run_forward_backward(&plan, x, y, b, K, grads, nullptr, stream);
+}
 
 namespace {
 
