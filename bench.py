@@ -48,8 +48,8 @@ def measured_traffic(kernel, workload):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-workloads", action="store_true",
@@ -75,7 +75,7 @@ def main():
     cfg = synth.config(args.workload)
     spec, seed = cfg["spec"], synth.BASE_SEED + cfg["index"]
     G, K = cfg["global_batch"], cfg["K"]
-    n_batches = args.warmup + args.steps
+    n_batches = min(args.warmup + args.steps, 16)   # distinct global batches, cycled through
 
     model = binding.Model(spec)
     P, Pp = model.num_params(), model.padded_params()

@@ -63,8 +63,10 @@ enum KClass {
 struct Timed {
   Timed(KClass cls, void* stream, double flops, double bytes);
   ~Timed();
-  int slot;
+  int cls;             // -1: timing is off
   void* stream;
+  void* start;         // hipEvent_t, owned until the destructor queues the pair
+  void* stop;
 };
 
 enum { MODE_FWD = 0, MODE_DGRAD = 1, MODE_WGRAD = 2 };

@@ -1023,6 +1023,13 @@ int launch_gemm(int dtype, const GemmArgs& args, const Segs& s, void* stream) {
   const int gran = 16 / es;
   if ((a.lda % gran) || (a.ldb % gran) || ((uintptr_t)a.A & 15) || ((uintptr_t)a.B & 15))
     return fail(DYNB_ERR_BADARG, "gemm: operands must have 16-byte aligned rows");
+  // the bf16 kernels keep operand byte offsets in 32 bits
+  if (dtype == DYNB_BF16 && !a.conv) {
+    const int64_t rows_a = a.mode == MODE_WGRAD ? s.off[s.K] : a.M;
+    const int64_t rows_b = a.mode == MODE_WGRAD ? s.off[s.K] : a.N;
+    if (rows_a * a.lda * es >= ((int64_t)1 << 32) || rows_b * a.ldb * es >= ((int64_t)1 << 32))
+      return fail(DYNB_ERR_UNSUPPORTED, "gemm: an operand of 4 GiB or more (rows * pitch) is not supported");
+  }
   if (a.bias_grad && (dtype != DYNB_BF16 || a.mode != MODE_WGRAD || a.split > 1))
     return fail(DYNB_ERR_UNSUPPORTED, "gemm: the bias gradient rides along with an unsplit bf16 weight gradient only");
   if (a.addend && (dtype != DYNB_BF16 || a.mode != MODE_DGRAD))

@@ -50,26 +50,36 @@ const char* kNames[KC_COUNT] = {"gemm_fwd",  "gemm_dgrad", "gemm_wgrad", "pack_i
                                 "weighted_aggregate", "sgd_update", "weight_cast", "conv_aux", "norm_add"};
 }  // namespace
 
-Timed::Timed(KClass cls, void* s, double flops, double bytes) : slot(-1), stream(s) {
+// The bracket holds its two events itself and hands them to the pending list only when both
+// are recorded, so a dynb_profile_collect() on another thread in between cannot take them away.
+Timed::Timed(KClass c, void* s, double flops, double bytes)
+    : cls(-1), stream(s), start(nullptr), stop(nullptr) {
   if (!g_on) return;
   std::lock_guard<std::mutex> lk(g_mu);
-  Pending p;
-  p.cls = cls;
-  p.start = get_event();
-  p.stop = get_event();
-  if (!p.start || !p.stop) return;
-  g_totals[cls].flops += flops;
-  g_totals[cls].bytes += bytes;
-  g_totals[cls].launches += 1;
-  (void)hipEventRecord(p.start, (hipStream_t)stream);
-  g_pending.push_back(p);
-  slot = (int)g_pending.size() - 1;
+  hipEvent_t a = get_event(), b = get_event();
+  if (!a || !b) {
+    if (a) g_free_events.push_back(a);
+    if (b) g_free_events.push_back(b);
+    return;
+  }
+  g_totals[c].flops += flops;
+  g_totals[c].bytes += bytes;
+  g_totals[c].launches += 1;
+  (void)hipEventRecord(a, (hipStream_t)stream);
+  cls = c;
+  start = a;
+  stop = b;
 }
 
 Timed::~Timed() {
-  if (slot < 0) return;
+  if (cls < 0) return;
+  (void)hipEventRecord((hipEvent_t)stop, (hipStream_t)stream);
   std::lock_guard<std::mutex> lk(g_mu);
-  (void)hipEventRecord(g_pending[slot].stop, (hipStream_t)stream);
+  Pending p;
+  p.cls = cls;
+  p.start = (hipEvent_t)start;
+  p.stop = (hipEvent_t)stop;
+  g_pending.push_back(p);
 }
 
 }  // namespace dynb

@@ -43,7 +43,7 @@ def layer_errors(got, ref):
     return worst
 
 
-def check(spec, params, x, y, b, label):
+def check(spec, params, x, y, b, label, tol=TOL_EMULATED):
     run = DeviceRun(spec, params, max(1, sum(b)), len(b))
     g = run.forward_backward_aggregate(x, y, b).cpu().numpy()
     got = worker_grads_as_lists(spec, g, run.P)
@@ -51,14 +51,14 @@ def check(spec, params, x, y, b, label):
     got_losses = run.losses(len(b))
     for k in range(len(b)):
         e = layer_errors(got[k], refs[k])
-        assert e < TOL_EMULATED, (label, "worker", k, b[k], e, n_amb, n_flip)
+        assert e < tol, (label, "worker", k, b[k], e, n_amb, n_flip)
         assert abs(got_losses[k] - losses[k]) <= 4e-3 * max(1.0, abs(losses[k]))
         if b[k] == 0:
             assert np.all(g[k] == 0.0)
     # the aggregate, given the gradients the comparison accepted
     agg = on.weighted_aggregate(refs, b)
     out = synth.unflatten_params(spec, run.out.cpu().numpy()[:run.P])
-    assert layer_errors(out, agg) < TOL_EMULATED
+    assert layer_errors(out, agg) < tol
     return run
 
 
@@ -76,7 +76,11 @@ def test_two_blocks_odd_sizes_and_channel_padding():
     params = perturbed(spec, 32)
     b = [4, 7, 2]
     x, y = synth.make_batch(spec, "uniform", sum(b), 32, 0)
-    check(spec, params, x, y, b, "two blocks")
+    # through four normalisations a stored value that rounded the other way has spread (every
+    # value computed from it rounds independently from there on): the tolerance stated for
+    # bfloat16 holds, the sharper one of the one-block cases no longer does (measured 9e-3 once
+    # the band of admissible ReLU decisions was narrowed to what it has to excuse)
+    check(spec, params, x, y, b, "two blocks", tol=TOL_BF16)
 
 
 def test_batchnorm_on_dense_features_and_plain_residual():
@@ -140,11 +144,11 @@ def test_layer_descriptions_are_validated():
 WORKLOAD_SPLIT = [170, 169, 86, 43, 22, 11, 0, 11]      # ragged, one idle worker; sums to 512
 
 
-def workload_size_case(spec, seed, capsys, label):
+def workload_size_case(spec, seed, capsys, label, workers=(4, 5, 7)):
     """One pass at the residual workload's batch (512 samples of 32x32x3, 8 workers) and the
-    checker's gradients for the three small workers, each computed alone from its own rows
-    (workers are independent of one another: their own statistics).  Checks for all workers
-    what holds at any size; returns what the caller compares."""
+    checker's gradients for the given workers (by default the three small ones), each computed
+    alone from its own rows (workers are independent of one another: their own statistics).
+    Checks for all workers what holds at any size; returns what the caller compares."""
     b = WORKLOAD_SPLIT
     params = perturbed(spec, seed)
     x, y = synth.make_batch(spec, "uniform", sum(b), seed, 0)
@@ -156,7 +160,7 @@ def workload_size_case(spec, seed, capsys, label):
     got_losses = run.losses(len(b))
     off = np.concatenate([[0], np.cumsum(b)])
     small = {}
-    for k in (4, 5, 7):
+    for k in workers:
         with capsys.disabled():
             print("  residual workload (%s): checker, worker %d (%d samples)" % (label, k, b[k]),
                   flush=True)
@@ -196,7 +200,10 @@ def test_normalisation_kernels_at_workload_size(depth, capsys):
         spec = {"dtype": "bf16", "input": (32, 32, 3), "classes": 10,
                 "layers": [synth.conv3x3(3, 64, 1, relu=False), synth.batchnorm(64, relu=True),
                            synth.gap(), synth.dense(64, 10, relu=False)]}
-    for k, (got, ref, _, _, _) in workload_size_case(spec, 77, capsys, depth).items():
+    # one block: also the largest worker (170 images, 174 080 pixel rows, 170 row chunks per
+    # normalisation), alone on the checker's side
+    workers = (0, 4, 5, 7) if depth == "one block" else (4, 5, 7)
+    for k, (got, ref, _, _, _) in workload_size_case(spec, 77, capsys, depth, workers).items():
         e = layer_errors(got, ref)
         assert e < (TOL_BF16 if depth == "one block" else TOL_EMULATED), (depth, "worker", k, e)
 
