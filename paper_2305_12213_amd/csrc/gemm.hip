@@ -884,15 +884,23 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs p, Segs segs) {
 #pragma unroll
     for (int b = 0; b < 4; ++b) acc[a][b] = 0.f;
 
-  for (int k0 = 0; k0 < gv.depth; k0 += TK) {
-    float4 va = make_float4(0.f, 0.f, 0.f, 0.f), vb = va;
+  // the operands of stage k0 + TK are asked for before stage k0 is computed, so that their
+  // trip to memory overlaps the arithmetic instead of preceding it
+  auto fetch = [&](int k0, float4& va, float4& vb) {
+    va = make_float4(0.f, 0.f, 0.f, 0.f);
+    vb = va;
     const int k = k0 + lk;
     if (i0 + lrow < p.M && k < gv.depth) va = *(const float4*)(A + (int64_t)(i0 + lrow) * p.lda + k);
     if (j0 + lrow < p.N && k < gv.depth) vb = *(const float4*)(B + (int64_t)(j0 + lrow) * p.ldb + k);
+  };
+  float4 va, vb;
+  fetch(0, va, vb);
+  for (int k0 = 0; k0 < gv.depth; k0 += TK) {
     __syncthreads();
     sA[lk + 0][lrow] = va.x; sA[lk + 1][lrow] = va.y; sA[lk + 2][lrow] = va.z; sA[lk + 3][lrow] = va.w;
     sB[lk + 0][lrow] = vb.x; sB[lk + 1][lrow] = vb.y; sB[lk + 2][lrow] = vb.z; sB[lk + 3][lrow] = vb.w;
     __syncthreads();
+    if (k0 + TK < gv.depth) fetch(k0 + TK, va, vb);
 #pragma unroll
     for (int kk = 0; kk < TK; ++kk) {
       const float4 a4 = *(const float4*)&sA[kk][ti];
