@@ -165,7 +165,11 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
   int ti, tj;
   tile_of_block(blockIdx.x, (p.M + BM - 1) / BM, (p.N + BN - 1) / BN, ti, tj);
   const int i0 = ti * BM, j0 = tj * BN;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // (the wave index as a scalar: everything derived from it -- LDS block addresses, which wave
+  // sums the bias gradient -- then stays in scalar registers and uniform branches; a wave issues
+  // at most one instruction every four clocks, so with two waves per SIMD every instruction
+  // saved in the stage loop is time the MFMA pipe does not wait)
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave % WM, wn = wave / WM;
 
   auto col0_of = [&](int g) {   // first reduction row of a group (weight gradient)
@@ -250,8 +254,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
   const uint32_t ldsA = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)&sA[0][0];
   const uint32_t ldsB = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)&sB[0][0];
   // RM: a copy moves 512/BM (512/BN) whole reduction rows of BM (BN) features; this lane's
-  // row within the stage and its byte offset from the stage's first row (~0u: past the row
-  // pitch, zeros).  Granule g of reduction row k sits at slot g ^ ((k & 3) << 2): the
+  // row within the stage and its byte offset from the stage's first row (0x80000000: past the
+  // row pitch -- out of the buffer's range whatever the stage, zeros).  Granule g of reduction row k sits at slot g ^ ((k & 3) << 2): the
   // transpose reads of 4 neighbouring rows and of the two 16-feature halves of a 32-feature
   // block then fall into 8 different 32-byte bank ranges.
   int rkA[RM ? LA : 1], rkB[RM ? LB : 1];
@@ -263,15 +267,29 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
       const int k = (wave + NW * u) * (64 / GA) + lane / GA;
       const int f = i0 + (((lane % GA) ^ ((k & 3) << 2)) * 8);
       rkA[u] = k;
-      roA[u] = f < p.lda ? (uint32_t)(((int64_t)k * p.lda + f) * 2) : ~0u;
+      roA[u] = f < p.lda ? (uint32_t)(((int64_t)k * p.lda + f) * 2) : 0x80000000u;
     }
 #pragma unroll
     for (int u = 0; u < LB; ++u) {
       const int k = (wave + NW * u) * (64 / GB) + lane / GB;
       const int f = j0 + (((lane % GB) ^ ((k & 3) << 2)) * 8);
       rkB[u] = k;
-      roB[u] = f < p.ldb ? (uint32_t)(((int64_t)k * p.ldb + f) * 2) : ~0u;
+      roB[u] = f < p.ldb ? (uint32_t)(((int64_t)k * p.ldb + f) * 2) : 0x80000000u;
     }
+  }
+  // Row pitches in bytes (the launch checks that an operand stays below 4 GiB).  Made opaque to
+  // the compiler: it otherwise prefers to re-read lda / ldb from the kernel arguments inside the
+  // hot loop when scalar registers run short, and the wait for such a scalar load also waits
+  // for every outstanding LDS fragment fetch (they share a counter) -- twice per stage.
+  uint32_t pitchA = (uint32_t)(p.lda * 2), pitchB = (uint32_t)(p.ldb * 2);
+  asm volatile("" : "+s"(pitchA), "+s"(pitchB));
+  // Buffer resources of the two operands (plain and row-major operands; the gathered operand
+  // keeps 64-bit addresses).  Plain operands: the whole matrix.  Row-major: the size is set per
+  // copy to the end of the worker's rows.
+  i32x4 rsA = {0, 0, 0, 0}, rsB = {0, 0, 0, 0};
+  if constexpr (!GATHER) {
+    rsA = buffer_resource(p.A, RM ? 0u : (uint32_t)((int64_t)p.M * p.lda * 2));
+    rsB = buffer_resource(p.B, RM ? 0u : (uint32_t)((int64_t)p.N * p.ldb * 2));
   }
   // One copy of a stage (plain or row-major operands): idx < LA is copy idx of the A operand,
   // else copy idx - LA of the B operand.  The hot loop places these between the MFMAs.
@@ -281,11 +299,23 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
     const int u = isA ? idx : idx - LA;
     const void* src;
     if constexpr (RM) {
-      const int64_t ld = isA ? p.lda : p.ldb;
-      const uint32_t row = (uint32_t)((int64_t)(c.col0 + k0) * ld * 2);
-      const int rk = isA ? rkA[u] : rkB[u];
-      const uint32_t ro = isA ? roA[u] : roB[u];
-      src = (k0 + rk < c.depth && ro != ~0u) ? (const void*)((isA ? Ab : Bb) + row + ro) : p.zeros;
+      // through a buffer resource that ends with the worker's last row: lanes on rows past it
+      // (the last, partly filled stage; every lane once the workgroup is past its last stage)
+      // and lanes past the row pitch read zeros by the hardware's range check
+      const uint32_t pitch = isA ? pitchA : pitchB;
+      i32x4 rs = isA ? rsA : rsB;
+      rs[2] = (int)((uint32_t)(c.col0 + c.depth) * pitch);
+      const uint32_t dst = isA ? ldsA + (uint32_t)((buf * BM * GPR + (wave + NW * u) * 64) * 16)
+                               : ldsB + (uint32_t)((buf * BN * GPR + (wave + NW * u) * 64) * 16);
+      async_copy_1k_buffer(rs, (isA ? roA[u] : roB[u]) + (uint32_t)(c.col0 + k0) * pitch, dst);
+      return;
+    } else if constexpr (!GATHER) {
+      // (a workgroup past its last stage keeps copying, see the stage loop: whatever such a
+      // copy reads -- the rows again from their start, zeros past the matrix -- is never used)
+      const uint32_t dst = isA ? ldsA + (uint32_t)((buf * BM * GPR + (wave + NW * u) * 64) * 16)
+                               : ldsB + (uint32_t)((buf * BN * GPR + (wave + NW * u) * 64) * 16);
+      async_copy_1k_buffer(isA ? rsA : rsB, (isA ? offA[u] : offB[u]) + (uint32_t)k0 * 2, dst);
+      return;
     } else {
       src = (const void*)((isA ? Ab + offA[u] : Bb + offB[u]) + (uint32_t)k0 * 2);
     }
@@ -618,7 +648,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
   int ahead = -1;               // stages issued beyond the one being computed
 #pragma unroll
   for (int f = 0; f < S; ++f)
-    if (ic.g < g_hi) {
+    if (WEAVE || ic.g < g_hi) {
       issue(f, ic);
       ++ic.kt;
       settle(ic);
@@ -654,7 +684,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
         // buffer nobody reads when this is the last stage), then the first half of the copies
         // that refill this buffer.  While a stage is still to be issued, S - 1 stages are in
         // flight beyond this one and the wait is a constant; the last S - 1 stages count down.
-        constexpr int NM = TM * TN, NF = TM + TN, NC = LA + LB, NC1 = NC / 2;
+        // (weight gradient: all copies of a refill in the second k-step -- the state that
+        // carries a half-issued refill into the next iteration costs more scalar instructions
+        // per stage than spreading three copies gains)
+        constexpr int NM = TM * TN, NF = TM + TN, NC = LA + LB, NC1 = RM ? NC : NC / 2;
         constexpr int NI0 = NF + (NC - NC1), NI1 = NF + NC1;
 #pragma unroll
         for (int i = 0; i < NM; ++i) {
@@ -672,7 +705,11 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
         }
         mma_sums(0);
         __builtin_amdgcn_sched_barrier(0);
-        const bool issuing = ic.g < g_hi;
+        // (past its last stage a workgroup keeps issuing copies -- weight gradient: a stage of
+        // depth 0, all zeros; otherwise the rows from their start again -- so that the number in
+        // flight, and with it this wait, is the same constant in every iteration and no branch
+        // asks whether stages are left)
+        const bool issuing = true;   // (this path: plain and row-major operands)
         if (issuing)
           asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * NC) : "memory");
         else
@@ -747,6 +784,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
       for (stored = g + 1; stored < (later ? ng.g : g_hi); ++stored) store_zero(gid(stored));
     }
     cc = ng;
+  }
+  // (the copies issued past the end land in this workgroup's LDS: wait for them before the ring
+  // is reused by the epilogue or given back)
+  if constexpr (WEAVE) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if constexpr (!RM) __syncthreads();   // ... all waves' copies, before any wave's patch
   }
   if constexpr (AGG) store_tile(p.agg, agg);
 
@@ -1035,8 +1078,10 @@ int launch_gemm(int dtype, const GemmArgs& args, const Segs& s, void* stream) {
   if (dtype == DYNB_BF16 && !a.conv) {
     const int64_t rows_a = a.mode == MODE_WGRAD ? s.off[s.K] : a.M;
     const int64_t rows_b = a.mode == MODE_WGRAD ? s.off[s.K] : a.N;
-    if (rows_a * a.lda * es >= ((int64_t)1 << 32) || rows_b * a.ldb * es >= ((int64_t)1 << 32))
-      return fail(DYNB_ERR_UNSUPPORTED, "gemm: an operand of 4 GiB or more (rows * pitch) is not supported");
+    const int64_t lim = (int64_t)1 << (a.mode == MODE_WGRAD ? 31 : 32);   // (see async_copy_1k_buffer)
+    if (rows_a * a.lda * es >= lim || rows_b * a.ldb * es >= lim)
+      return fail(DYNB_ERR_UNSUPPORTED, "gemm: an operand of %d GiB or more (rows * pitch) is not supported",
+                  a.mode == MODE_WGRAD ? 2 : 4);
   }
   if (a.bias_grad && (dtype != DYNB_BF16 || a.mode != MODE_WGRAD || a.split > 1))
     return fail(DYNB_ERR_UNSUPPORTED, "gemm: the bias gradient rides along with an unsplit bf16 weight gradient only");

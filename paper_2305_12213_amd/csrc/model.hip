@@ -350,15 +350,15 @@ extern "C" int dynb_model_bind(dynb_model* m, float* params, void* ws, size_t ws
   for (const Layer& L : m->layers) max_hw = L.hw_out > max_hw ? L.hw_out : max_hw;
   if ((int64_t)max_batch * max_hw > (int64_t)1 << 30)
     return fail(DYNB_ERR_UNSUPPORTED, "bind: max_global_batch * pixels exceeds 2^30 rows");
-  if (m->dtype == DYNB_BF16) {   // the bf16 kernels keep byte offsets into an activation in 32 bits
+  if (m->dtype == DYNB_BF16) {   // the bf16 kernels keep byte offsets into an activation in 31 bits
     int64_t largest = (int64_t)max_batch * m->in_h * m->in_w * m->ld0 * 2;
     for (const Layer& L : m->layers) {
       const int64_t bytes = (int64_t)max_batch * L.hw_out * L.ld_out * 2;
       largest = bytes > largest ? bytes : largest;
     }
-    if (largest >= (int64_t)1 << 32)
+    if (largest >= (int64_t)1 << 31)
       return fail(DYNB_ERR_UNSUPPORTED,
-                  "bind: an activation tensor of %lld bytes (4 GiB or more) is not supported; "
+                  "bind: an activation tensor of %lld bytes (2 GiB or more) is not supported; "
                   "lower max_global_batch", (long long)largest);
   }
   const size_t need = dynb_model_workspace_bytes(m, max_batch, max_workers);

@@ -120,15 +120,14 @@ def test_ewma_and_static_allocation_match_oracle():
 
 
 def test_bind_rejects_activations_beyond_32_bit_offsets_before_touching_the_device():
-    # 32768 images of 32x32 pixels at 64 channels in bf16 are 4 GiB: the kernels' 32-bit byte
-    # offsets would wrap.  The check runs before any device call (the pointers are never used).
+    # 16384 images of 32x32 pixels at 64 channels in bf16 are 2 GiB: the kernels' byte offsets
+    # into an activation (31 bits) would wrap.  The check runs before any device call (the pointers are never used).
     spec = {"dtype": "bf16", "input": (32, 32, 3), "classes": 10,
             "layers": [synth.conv3x3(3, 64, 1), synth.gap(), synth.dense(64, 10, relu=False)]}
     m = binding.Model(spec)
     with pytest.raises(binding.DynbError) as e:
-        binding.load().dynb_model_bind.restype
-        m.bind(0x10000, 0x100000, 1 << 62, 32768, 4, stream=0)
-    assert e.value.code == -2 and "4 GiB" in str(e.value)
+        m.bind(0x10000, 0x100000, 1 << 62, 16384, 4, stream=0)
+    assert e.value.code == -2 and "2 GiB" in str(e.value)
 
 
 def test_model_description_is_validated_on_the_host():
