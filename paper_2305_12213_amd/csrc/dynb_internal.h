@@ -187,12 +187,25 @@ struct GradSource {
   Lambdas lam;
 };
 
-// dense weight W fp32 [R][C] at parameter offset `off`: optimizer step fused with the refresh
-// of Wn T [R][ldn] and Wt T [C][ldt]; s1/s2 point at the state of parameter 0 (may be null
-// when the rule has no such state)
-int launch_update_cast(int dtype, float* params, int64_t off, const GradSource& src,
-                       const UpdateRule& rule, float* s1, float* s2, int R, int C, void* Wn,
-                       int64_t ldn, void* Wt, int64_t ldt, void* stream);
+// Dense weights W fp32 [R][C] at parameter offset `off`, each with its copies Wn T [R][ldn] and
+// Wt T [C][ldt] (T = the model's storage type), passed to the kernel by value.
+constexpr int MAX_CAST_MATS = 8;
+struct CastMats {
+  int n;
+  int64_t off[MAX_CAST_MATS];
+  int R[MAX_CAST_MATS], C[MAX_CAST_MATS];
+  void* Wn[MAX_CAST_MATS];
+  int64_t ldn[MAX_CAST_MATS];
+  void* Wt[MAX_CAST_MATS];
+  int64_t ldt[MAX_CAST_MATS];
+  int first_block[MAX_CAST_MATS + 1];   // first workgroup of each matrix (set by the launcher)
+};
+// One launch: the optimizer step of every matrix of `mats` fused with the refresh of its two
+// copies, and the element-wise step of every range of `small`; s1/s2 point at the state of
+// parameter 0 (may be null when the rule has no such state)
+int launch_update_cast(int dtype, float* params, CastMats& mats, const Ranges& small,
+                       const GradSource& src, const UpdateRule& rule, float* s1, float* s2,
+                       void* stream);
 // element-wise step of parameters [off, off + n) (any alignment)
 int launch_update_range(float* params, int64_t off, const GradSource& src, const UpdateRule& rule,
                         float* s1, float* s2, int64_t n, void* stream);

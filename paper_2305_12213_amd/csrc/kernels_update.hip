@@ -57,23 +57,50 @@ __device__ inline float gradient1(const GradSource& src, int64_t o) {
   return acc;
 }
 
-// ---- one dense weight matrix: step + both 16-bit copies in one pass ---------------------
+// ---- dense weight matrices: step + both 16-bit copies in one pass ---------------------------
 // W[r][c] <- step(W[r][c]); Wn[r][c] = T(W), Wt[c][r] = T(W).  A workgroup owns a 64 x TC tile:
 // 16-byte accesses on the fp32 side, the transposed copy goes through an LDS tile so that its
 // stores are 16 bytes per lane and whole 128-byte lines per 8 (bf16) lanes.
+// One launch serves every matrix of `mats` (workgroups mats.first_block[i] ... belong to matrix
+// i) and, with the workgroups behind the last tile, the small tensors of `small` (biases):
+// back-to-back launches on one stream leave the chip idle for a few microseconds each, which
+// for a four-layer model came to a sixth of the whole update.
 template <typename T, int KIND, bool AGG, int TC>
-__global__ __launch_bounds__(256) void update_cast_kernel(float* __restrict__ params, int64_t off,
+__global__ __launch_bounds__(256) void update_cast_kernel(float* __restrict__ params, CastMats mats,
+                                                          Ranges small, int range_blocks,
                                                           GradSource src, UpdateRule rule,
                                                           float* __restrict__ s1,
-                                                          float* __restrict__ s2, int R, int C,
-                                                          T* __restrict__ Wn, int64_t ldn,
-                                                          T* __restrict__ Wt, int64_t ldt) {
+                                                          float* __restrict__ s2) {
+  const int blk = blockIdx.x;
+  if (blk >= mats.first_block[mats.n]) {   // the small tensors, element by element
+    const int rb = blk - mats.first_block[mats.n];
+    for (int q = 0; q < small.n; ++q) {
+      const int64_t off = small.off[q], n = small.len[q];
+      for (int64_t i = (int64_t)rb * 256 + threadIdx.x; i < n; i += (int64_t)range_blocks * 256) {
+        const int64_t o = off + i;
+        float a = KIND != DYNB_OPT_SGD ? s1[o] : 0.f;
+        float b = KIND == DYNB_OPT_ADAM ? s2[o] : 0.f;
+        params[o] = step_one<KIND>(rule, params[o], gradient1<AGG>(src, o), a, b);
+        if (KIND != DYNB_OPT_SGD) s1[o] = a;
+        if (KIND == DYNB_OPT_ADAM) s2[o] = b;
+      }
+    }
+    return;
+  }
+  int mi = 0;
+  while (blk >= mats.first_block[mi + 1]) ++mi;
+  const int64_t off = mats.off[mi], ldn = mats.ldn[mi], ldt = mats.ldt[mi];
+  const int R = mats.R[mi], C = mats.C[mi];
+  T* __restrict__ Wn = (T*)mats.Wn[mi];
+  T* __restrict__ Wt = (T*)mats.Wt[mi];
+  const int tiles_x = (C + TC - 1) / TC, local = blk - mats.first_block[mi];
+  const int tile_x = local % tiles_x, tile_y = local / tiles_x;
   constexpr int G = 16 / sizeof(T);
   typedef T vecT __attribute__((ext_vector_type(G)));
   typedef T vec4T __attribute__((ext_vector_type(4)));
   constexpr int QC = TC / 4;   // 16-byte granules per tile row
   __shared__ float tile[64][TC + 1];
-  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * TC;
+  const int r0 = tile_y * 64, c0 = tile_x * TC;
   // 16-byte accesses need aligned rows in every array (all start at a multiple of 4 floats)
   const bool vec = (C & 3) == 0 && (off & 3) == 0;
 #pragma unroll 2
@@ -202,40 +229,42 @@ double flops_per_param(const UpdateRule& rule, const GradSource& src) {
   return step + (src.lam.K > 0 ? 2.0 * src.lam.K : 0.0);
 }
 
+// (wider tiles when K gradient streams are read: 512-byte runs per row and stream)
+constexpr int cast_tile_columns(bool agg) { return agg ? 128 : 64; }
+
 template <typename T, int KIND, bool AGG>
-void launch_update_cast_t(float* params, int64_t off, const GradSource& src, const UpdateRule& rule,
-                          float* s1, float* s2, int R, int C, void* Wn, int64_t ldn, void* Wt,
-                          int64_t ldt, hipStream_t st) {
-  // wider tiles when K gradient streams are read: 512-byte runs per row and stream
-  constexpr int TC = AGG ? 128 : 64;
-  dim3 grid((C + TC - 1) / TC, (R + 63) / 64);
-  hipLaunchKernelGGL((update_cast_kernel<T, KIND, AGG, TC>), grid, dim3(256), 0, st, params, off, src,
-                     rule, s1, s2, R, C, (T*)Wn, ldn, (T*)Wt, ldt);
+void launch_update_cast_t(float* params, const CastMats& mats, const Ranges& small, int range_blocks,
+                          const GradSource& src, const UpdateRule& rule, float* s1, float* s2,
+                          hipStream_t st) {
+  constexpr int TC = cast_tile_columns(AGG);
+  const dim3 grid((unsigned)(mats.first_block[mats.n] + range_blocks));
+  hipLaunchKernelGGL((update_cast_kernel<T, KIND, AGG, TC>), grid, dim3(256), 0, st, params, mats, small,
+                     range_blocks, src, rule, s1, s2);
 }
 
 template <typename T, int KIND>
-void launch_update_cast_k(float* params, int64_t off, const GradSource& src, const UpdateRule& rule,
-                          float* s1, float* s2, int R, int C, void* Wn, int64_t ldn, void* Wt,
-                          int64_t ldt, hipStream_t st) {
+void launch_update_cast_k(float* params, const CastMats& mats, const Ranges& small, int range_blocks,
+                          const GradSource& src, const UpdateRule& rule, float* s1, float* s2,
+                          hipStream_t st) {
   if (src.lam.K > 0)
-    launch_update_cast_t<T, KIND, true>(params, off, src, rule, s1, s2, R, C, Wn, ldn, Wt, ldt, st);
+    launch_update_cast_t<T, KIND, true>(params, mats, small, range_blocks, src, rule, s1, s2, st);
   else
-    launch_update_cast_t<T, KIND, false>(params, off, src, rule, s1, s2, R, C, Wn, ldn, Wt, ldt, st);
+    launch_update_cast_t<T, KIND, false>(params, mats, small, range_blocks, src, rule, s1, s2, st);
 }
 
 template <typename T>
-void launch_update_cast_d(float* params, int64_t off, const GradSource& src, const UpdateRule& rule,
-                          float* s1, float* s2, int R, int C, void* Wn, int64_t ldn, void* Wt,
-                          int64_t ldt, hipStream_t st) {
+void launch_update_cast_d(float* params, const CastMats& mats, const Ranges& small, int range_blocks,
+                          const GradSource& src, const UpdateRule& rule, float* s1, float* s2,
+                          hipStream_t st) {
   switch (rule.kind) {
     case DYNB_OPT_SGD:
-      launch_update_cast_k<T, DYNB_OPT_SGD>(params, off, src, rule, s1, s2, R, C, Wn, ldn, Wt, ldt, st);
+      launch_update_cast_k<T, DYNB_OPT_SGD>(params, mats, small, range_blocks, src, rule, s1, s2, st);
       break;
     case DYNB_OPT_MOMENTUM:
-      launch_update_cast_k<T, DYNB_OPT_MOMENTUM>(params, off, src, rule, s1, s2, R, C, Wn, ldn, Wt, ldt, st);
+      launch_update_cast_k<T, DYNB_OPT_MOMENTUM>(params, mats, small, range_blocks, src, rule, s1, s2, st);
       break;
     default:
-      launch_update_cast_k<T, DYNB_OPT_ADAM>(params, off, src, rule, s1, s2, R, C, Wn, ldn, Wt, ldt, st);
+      launch_update_cast_k<T, DYNB_OPT_ADAM>(params, mats, small, range_blocks, src, rule, s1, s2, st);
   }
 }
 
@@ -252,17 +281,37 @@ void launch_update_range_k(float* params, int64_t off, const GradSource& src, co
 
 }  // namespace
 
-int launch_update_cast(int dtype, float* params, int64_t off, const GradSource& src,
-                       const UpdateRule& rule, float* s1, float* s2, int R, int C, void* Wn,
-                       int64_t ldn, void* Wt, int64_t ldt, void* stream) {
-  if (R <= 0 || C <= 0) return DYNB_OK;
+int launch_update_cast(int dtype, float* params, CastMats& mats, const Ranges& small,
+                       const GradSource& src, const UpdateRule& rule, float* s1, float* s2,
+                       void* stream) {
+  if (mats.n < 0 || mats.n > MAX_CAST_MATS || small.n < 0 || small.n > MAX_RANGES)
+    return fail(DYNB_ERR_BADARG, "update_cast: too many tensors for one launch");
   const int es = dtype == DYNB_BF16 ? 2 : 4;
-  const double n = (double)R * C;
-  Timed t(KC_UPDATE, stream, flops_per_param(rule, src) * n, (bytes_per_param(rule, src) + 2 * es) * n);
+  const int TC = cast_tile_columns(src.lam.K > 0);
+  double cast_n = 0.0, small_n = 0.0;
+  int64_t blocks = 0, longest = 0;
+  for (int i = 0; i < mats.n; ++i) {
+    if (mats.R[i] <= 0 || mats.C[i] <= 0) return fail(DYNB_ERR_BADARG, "update_cast: empty matrix");
+    mats.first_block[i] = (int)blocks;
+    blocks += (int64_t)((mats.C[i] + TC - 1) / TC) * ((mats.R[i] + 63) / 64);
+    cast_n += (double)mats.R[i] * mats.C[i];
+  }
+  for (int i = 0; i < small.n; ++i) {
+    longest = small.len[i] > longest ? small.len[i] : longest;
+    small_n += (double)small.len[i];
+  }
+  int64_t range_blocks = (longest + 255) / 256;
+  if (range_blocks > 256) range_blocks = 256;
+  if (blocks + range_blocks >= ((int64_t)1 << 31))
+    return fail(DYNB_ERR_UNSUPPORTED, "update_cast: too many tiles for one launch");
+  if (blocks + range_blocks == 0) return DYNB_OK;
+  for (int i = mats.n; i <= MAX_CAST_MATS; ++i) mats.first_block[i] = (int)blocks;
+  Timed t(KC_UPDATE, stream, flops_per_param(rule, src) * (cast_n + small_n),
+          (bytes_per_param(rule, src) + 2 * es) * cast_n + bytes_per_param(rule, src) * small_n);
   if (dtype == DYNB_BF16)
-    launch_update_cast_d<bf16>(params, off, src, rule, s1, s2, R, C, Wn, ldn, Wt, ldt, (hipStream_t)stream);
+    launch_update_cast_d<bf16>(params, mats, small, (int)range_blocks, src, rule, s1, s2, (hipStream_t)stream);
   else
-    launch_update_cast_d<float>(params, off, src, rule, s1, s2, R, C, Wn, ldn, Wt, ldt, (hipStream_t)stream);
+    launch_update_cast_d<float>(params, mats, small, (int)range_blocks, src, rule, s1, s2, (hipStream_t)stream);
   return ok("update_cast");
 }
 

@@ -811,24 +811,31 @@ int make_rule(const dynb_optimizer* opt, const float* s1, const float* s2, Updat
   return DYNB_OK;
 }
 
-// One step over all layers: one fused pass per dense weight matrix (step + both 16-bit
-// copies); biases and convolution weights are small: element-wise step, then the
-// convolution's weight layouts.
+// One step over all layers.  Dense weight matrices: the step and both 16-bit copies in one
+// pass, MAX_CAST_MATS matrices per launch; the first such launch also steps the small tensors
+// (biases, convolution weights, normalisation parameters), whose 16-bit layouts follow.
 int update_layers(dynb_model* m, const GradSource& src, const UpdateRule& rule, float* s1,
                   float* s2, void* stream) {
-  // all the small tensors (biases, convolution weights) in one launch per MAX_RANGES of them
   Ranges r;
   r.n = 0;
-  auto flush = [&]() {
+  CastMats mats;
+  mats.n = 0;
+  bool any_dense = false;
+  for (Layer& L : m->layers) any_dense = any_dense || (L.has_params && L.kind == DYNB_LAYER_DENSE);
+  // without a dense layer, or with more small tensors than one launch takes: element-wise launches
+  auto flush_small = [&]() {
     const int rc = r.n ? launch_update_ranges(m->params, r, src, rule, s1, s2, stream) : DYNB_OK;
     r.n = 0;
     return rc;
   };
   auto add = [&](int64_t off, int64_t len) {
     if (len <= 0) return (int)DYNB_OK;
+    if (r.n == MAX_RANGES)
+      if (int rc = flush_small()) return rc;
     r.off[r.n] = off;
     r.len[r.n] = len;
-    return ++r.n == MAX_RANGES ? flush() : (int)DYNB_OK;
+    ++r.n;
+    return (int)DYNB_OK;
   };
   for (Layer& L : m->layers) {
     if (L.kind == DYNB_LAYER_BN) {
@@ -840,17 +847,34 @@ int update_layers(dynb_model* m, const GradSource& src, const UpdateRule& rule, 
     if (!rc && L.kind != DYNB_LAYER_DENSE) rc = add(L.w_off, (int64_t)9 * L.n_in * L.n_out);
     if (rc) return rc;
   }
-  if (int rc = flush()) return rc;
+  if (!any_dense)
+    if (int rc = flush_small()) return rc;
+  auto flush_mats = [&]() {
+    const int rc = launch_update_cast(m->dtype, m->params, mats, r, src, rule, s1, s2, stream);
+    mats.n = 0;
+    r.n = 0;   // (the small tensors went with this launch)
+    return rc;
+  };
   for (Layer& L : m->layers) {
-    if (!L.has_params) continue;
-    int rc;
-    if (L.kind == DYNB_LAYER_DENSE)
-      rc = launch_update_cast(m->dtype, m->params, L.w_off, src, rule, s1, s2, L.n_in, L.n_out,
-                              L.Wn, L.ld_out, L.Wt, L.ld_in, stream);
-    else
-      rc = launch_conv_weight_cast(m->params + L.w_off, L.n_in, L.n_out, L.cin_p, L.cout_p, L.Wt,
-                                   L.kf, L.Wn, L.kd, stream);
-    if (rc) return rc;
+    if (!L.has_params || L.kind != DYNB_LAYER_DENSE) continue;
+    const int i = mats.n++;
+    mats.off[i] = L.w_off;
+    mats.R[i] = L.n_in;
+    mats.C[i] = L.n_out;
+    mats.Wn[i] = L.Wn;
+    mats.ldn[i] = L.ld_out;
+    mats.Wt[i] = L.Wt;
+    mats.ldt[i] = L.ld_in;
+    if (mats.n == MAX_CAST_MATS)
+      if (int rc = flush_mats()) return rc;
+  }
+  if (mats.n)
+    if (int rc = flush_mats()) return rc;
+  for (Layer& L : m->layers) {
+    if (!L.has_params || L.kind == DYNB_LAYER_DENSE) continue;
+    if (int rc = launch_conv_weight_cast(m->params + L.w_off, L.n_in, L.n_out, L.cin_p, L.cout_p, L.Wt,
+                                         L.kf, L.Wn, L.kd, stream))
+      return rc;
   }
   return DYNB_OK;
 }
