@@ -38,6 +38,9 @@ SPECS = [
     ("mlp f32 vector rows", lambda: synth.mlp_spec([96, 80, 12], "f32")),
     ("mlp f32 odd widths", lambda: synth.mlp_spec([33, 30, 10], "f32")),
     ("mlp bf16", lambda: synth.mlp_spec([200, 136, 10], "bf16")),
+    # more dense matrices than one update launch takes (eight): two launches, the second without
+    # the small tensors
+    ("mlp f32 eleven layers", lambda: synth.mlp_spec([40, 36, 36, 36, 33, 36, 36, 36, 36, 36, 36, 7], "f32")),
     ("cnn bf16", lambda: {"dtype": "bf16", "input": (8, 8, 3), "classes": 5,
                           "layers": [synth.conv3x3(3, 8, 1), synth.conv3x3(8, 16, 2), synth.gap(),
                                      synth.dense(16, 5, relu=False)]}),
