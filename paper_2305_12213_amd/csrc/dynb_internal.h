@@ -158,6 +158,9 @@ int launch_bias_grad_rows(const void* dy, int64_t ld, int N, float* grads, int64
 int launch_bias_grad(int dtype, const void* dyT, int64_t ld, int N, float* grads,
                      int64_t group_stride, const Segs& s, void* stream);
 // loss[g] = mean of rowloss over worker g's rows; grads[g][P..P_pad) = 0
+// Reads `bytes` (a multiple of 16, 16-byte aligned) and discards them: what a launch is about to
+// fetch several times over, brought into the last-level cache by one sequential pass.
+int launch_touch(const void* p, int64_t bytes, void* stream);
 int launch_finalize(const float* rowloss, float* loss, float* grads, int64_t P, int64_t P_pad,
                     const Segs& s, void* stream);
 int launch_aggregate(const float* grads, const Lambdas& lam, int64_t n, float* out, void* stream);

@@ -250,6 +250,17 @@ __global__ __launch_bounds__(64) void finalize_kernel(const float* __restrict__ 
     for (int64_t p = P + lane; p < P_pad; p += 64) grads[(int64_t)g * P_pad + p] = 0.f;
 }
 
+// ---- read and discard (see launch_touch) -------------------------------------------------
+__global__ __launch_bounds__(256) void touch_kernel(const uint4* __restrict__ p, int64_t n,
+                                                    uint32_t* sink) {
+  uint32_t acc = 0;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const uint4 v = p[i];
+    acc |= v.x ^ v.y ^ v.z ^ v.w;
+  }
+  if (sink) *sink = acc;   // (sink is always null: the condition only keeps the loads alive)
+}
+
 // ---- weight copies: Wn[r][c] = T(W[r][c]),  Wt[c][r] = T(W[r][c]) ----------------------
 template <typename T>
 __global__ __launch_bounds__(256) void weight_cast_kernel(const float* __restrict__ W, int R, int C,
@@ -391,6 +402,16 @@ int launch_bias_grad(int dtype, const void* dyT, int64_t ld, int N, float* grads
                                        (hipStream_t)stream, (const T*)dyT, ld, N, grads,
                                        group_stride, s));
   return ok("bias_grad");
+}
+
+int launch_touch(const void* p, int64_t bytes, void* stream) {
+  if (bytes < 16) return DYNB_OK;
+  Timed t(KC_GEMM_WGRAD, stream, 0, 0);   // (its time counts towards the launch it prepares)
+  int64_t bx = (bytes / 16 + 255) / 256;
+  if (bx > 2048) bx = 2048;
+  hipLaunchKernelGGL(touch_kernel, dim3((unsigned)bx), dim3(256), 0, (hipStream_t)stream,
+                     (const uint4*)p, bytes / 16, (uint32_t*)nullptr);
+  return ok("touch");
 }
 
 int launch_finalize(const float* rowloss, float* loss, float* grads, int64_t P, int64_t P_pad,

@@ -426,6 +426,127 @@ int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const 
   // over the residual branch; the input-gradient kernel of the layer above adds it.
   std::vector<const void*> dyv(nL), skip_grad(nL, nullptr);
   for (size_t l = 0; l < nL; ++l) dyv[l] = m->layers[l].dy;
+  // ---- per-worker weight and bias gradients ----
+  Lambdas lam;                  // Eq. 2: lambda_k = b_k / sum_i b_i
+  lam.K = K;
+  for (int k = 0; k < K; ++k) lam.w[k] = B > 0 ? (float)((double)b[k] / (double)B) : 0.f;
+  if (agg && B <= 0) return fail(DYNB_ERR_BADARG, "forward_backward_aggregate: sum(b) must be positive");
+  // aggregates of the small tensors (biases, small weights, padding): one launch for all
+  Ranges small;
+  small.n = 0;
+  auto flush_small = [&]() {
+    const int r = small.n ? launch_aggregate_ranges(grads, m->P_pad, lam, small, agg, stream) : DYNB_OK;
+    small.n = 0;
+    return r;
+  };
+  auto add_small = [&](int64_t off, int64_t len) {
+    if (len <= 0) return (int)DYNB_OK;
+    small.off[small.n] = off;
+    small.len[small.n] = len;
+    return ++small.n == MAX_RANGES ? flush_small() : (int)DYNB_OK;
+  };
+  // Per-worker weight and bias gradients of layer l (and, with `agg`, their aggregate).  Needs
+  // the layer's input and the finished gradient wrt its output.
+  std::vector<char> wgrad_done(nL, 0);
+  auto weight_gradient = [&](size_t l) -> int {
+    wgrad_done[l] = 1;
+    Layer& L = m->layers[l];
+    if (L.kind == DYNB_LAYER_BN) {
+      if (B == 0) {   // no backward pass ran: the scale / shift gradients of idle workers are zero
+        rc = launch_bn_backward(L.dy, L.ld_out, in_act(l), L.ld_in, L.n_out, m->params + L.w_off,
+                                L.bn_mean, L.bn_rstd, m->row_scratch, grads + L.w_off,
+                                grads + L.b_off, m->P_pad, 0, 0, nullptr, 0, segs[l], stream);
+        if (rc) return rc;
+      }
+      if (agg) {
+        rc = add_small(L.w_off, 2 * (int64_t)L.n_out);
+        if (rc) return rc;
+      }
+      return (int)DYNB_OK;
+    }
+    if (!L.has_params) return (int)DYNB_OK;
+    if (L.kind == DYNB_LAYER_CONV3X3) {
+      rc = launch_conv_wgrad(in_act(l), L.ld_in, L.n_in, L.h_in, L.w_in, dyv[l], L.ld_out, L.n_out,
+                             L.h_out, L.w_out, L.stride, L.conv_chunk, m->partial, m->partial_floats,
+                             grads + L.w_off, grads + L.b_off, m->P_pad, segs[l],
+                             2.0 * B * L.hw_out * L.wg_rows * L.n_out,
+                             (double)K * L.wg_rows * L.n_out * 4 +
+                                 (double)B * (L.hw_in * L.n_in + L.hw_out * L.n_out) * es,
+                             stream);
+      if (rc) return rc;
+      if (agg) {
+        rc = add_small(L.w_off, (int64_t)L.wg_rows * L.n_out);
+        if (!rc) rc = add_small(L.b_off, L.n_out);
+        if (rc) return rc;
+      }
+      return (int)DYNB_OK;
+    }
+    GemmArgs g = {};
+    g.mode = MODE_WGRAD;
+    if (dt == DYNB_BF16) {   // the row-major tensors themselves, reduced over each worker's rows
+      g.A = dyv[l]; g.lda = L.ld_out;
+      g.B = in_act(l); g.ldb = L.ld_in;
+    } else {
+      g.A = L.dyT; g.lda = L.capT;
+      g.B = L.inT; g.ldb = L.capT;
+    }
+    g.M = L.n_out; g.N = L.wg_rows;
+    g.Cf = grads + L.w_off; g.ldcf = L.n_out;
+    g.group_stride = m->P_pad;
+    g.alg_flops = 2.0 * B * L.hw_out * L.wg_rows * L.n_out;
+    g.alg_bytes = (double)K * L.wg_rows * L.n_out * 4 + (double)B * L.hw_out * (L.wg_rows + L.n_out) * es;
+    int deepest = 0;
+    for (int k = 0; k < K; ++k) {
+      const int d = dt == DYNB_BF16 ? segs[l].off[k + 1] - segs[l].off[k] : segs[l].poff[k + 1] - segs[l].poff[k];
+      deepest = d > deepest ? d : deepest;
+    }
+    int split = (deepest + 255) / 256;               // chunks of at least eight 32-deep stages
+    split = split > L.max_split ? L.max_split : split;
+    if (split > 1) {
+      g.split = split;
+      g.chunk = (int)round_up((deepest + split - 1) / split, 64);
+      g.partial = m->partial;
+      g.partial_stride = round_up((int64_t)L.wg_rows * L.n_out, 64);
+    }
+    // the aggregate of this weight: in the same kernel while the per-worker tiles are in
+    // registers where the launch shape allows it, else by a pass over what was written
+    const bool fold = agg && gemm_fuses_aggregate(dt, g, segs[l]);
+    if (fold) {
+      g.alg_bytes += (double)L.wg_rows * L.n_out * 4;   // the aggregated tile is written too
+      g.agg = agg + L.w_off;
+      for (int k = 0; k < K; ++k) g.lam[k] = lam.w[k];
+    }
+    // bf16, unsplit: the bias gradient is formed by the same kernel
+    const bool bias_inside = dt == DYNB_BF16 && split <= 1;
+    if (bias_inside) g.bias_grad = grads + L.b_off;
+    rc = launch_gemm(dt, g, segs[l], stream);
+    if (rc) return rc;
+    if (split > 1) {
+      rc = launch_wgrad_reduce(m->partial, split, g.partial_stride, (int64_t)L.wg_rows * L.n_out,
+                               grads + L.w_off, m->P_pad, K, stream);
+      if (rc) return rc;
+    }
+    if (bias_inside)
+      rc = DYNB_OK;
+    else if (dt == DYNB_BF16)
+      rc = launch_bias_grad_rows(dyv[l], L.ld_out, L.n_out, grads + L.b_off, m->P_pad, segs[l], stream);
+    else
+      rc = launch_bias_grad(dt, L.dyT, L.capT, L.n_out, grads + L.b_off, m->P_pad, segs[l], stream);
+    if (rc) return rc;
+    if (agg) {
+      const int64_t nw = (int64_t)L.wg_rows * L.n_out;
+      if (!fold && nw >= 65536) {
+        rc = launch_aggregate_range(grads + L.w_off, m->P_pad, lam, nw, agg + L.w_off, stream);
+        if (rc) return rc;
+      } else if (!fold) {
+        rc = add_small(L.w_off, nw);
+        if (rc) return rc;
+      }
+      rc = add_small(L.b_off, L.n_out);
+      if (rc) return rc;
+    }
+    return (int)DYNB_OK;
+  };
   if (B > 0) {
     // ---- forward ----
     rc = launch_pack_rows(dt, x, B * m->in_h * m->in_w, m->in_c, m->act0, m->ld0, stream);
@@ -572,124 +693,34 @@ int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const 
       }
       rc = launch_gemm(dt, g, s1, stream);
       if (rc) return rc;
+      // A dense layer's weight gradient right behind its input gradient.  That launch has just
+      // read both of the weight gradient's operands in full -- the gradient wrt the layer's
+      // output as its own operand, the layer's input as the ReLU mask of its epilogue -- so they
+      // sit in the 256 MB last-level cache, from which the eight L2s then re-fetch their panels
+      // (five to six times the operands' size per launch).  After the whole chain of input
+      // gradients, and after other weight gradients have streamed gigabytes past that cache,
+      // those re-fetches come from HBM and compete with the tile stores: 0.29 - 0.31 ms per
+      // 4096 x 4096 launch instead of 0.24 - 0.28.
+      if (L.kind == DYNB_LAYER_DENSE && dt == DYNB_BF16) {
+        rc = weight_gradient(l);
+        if (rc) return rc;
+      }
     }
   }
-  // ---- per-worker weight and bias gradients ----
-  Lambdas lam;                  // Eq. 2: lambda_k = b_k / sum_i b_i
-  lam.K = K;
-  for (int k = 0; k < K; ++k) lam.w[k] = B > 0 ? (float)((double)b[k] / (double)B) : 0.f;
-  if (agg && B <= 0) return fail(DYNB_ERR_BADARG, "forward_backward_aggregate: sum(b) must be positive");
-  // aggregates of the small tensors (biases, small weights, padding): one launch for all
-  Ranges small;
-  small.n = 0;
-  auto flush_small = [&]() {
-    const int r = small.n ? launch_aggregate_ranges(grads, m->P_pad, lam, small, agg, stream) : DYNB_OK;
-    small.n = 0;
-    return r;
-  };
-  auto add_small = [&](int64_t off, int64_t len) {
-    if (len <= 0) return (int)DYNB_OK;
-    small.off[small.n] = off;
-    small.len[small.n] = len;
-    return ++small.n == MAX_RANGES ? flush_small() : (int)DYNB_OK;
-  };
-  for (size_t l = 0; l < nL; ++l) {
-    Layer& L = m->layers[l];
-    if (L.kind == DYNB_LAYER_BN) {
-      if (B == 0) {   // no backward pass ran: the scale / shift gradients of idle workers are zero
-        rc = launch_bn_backward(L.dy, L.ld_out, in_act(l), L.ld_in, L.n_out, m->params + L.w_off,
-                                L.bn_mean, L.bn_rstd, m->row_scratch, grads + L.w_off,
-                                grads + L.b_off, m->P_pad, 0, 0, nullptr, 0, segs[l], stream);
+  // ---- per-worker weight and bias gradients (of the layers the backward pass has not done) ----
+  for (size_t l = 0; l < nL; ++l)
+    if (!wgrad_done[l]) {
+      // (a large first dense layer: no input gradient has read its input, so one sequential
+      // pass brings it into the last-level cache first -- 8 us for 32 MB, 50 us off the launch)
+      const Layer& L = m->layers[l];
+      const int64_t in_bytes = (int64_t)B * L.hw_in * L.ld_in * es;
+      if (L.kind == DYNB_LAYER_DENSE && dt == DYNB_BF16 && in_bytes >= ((int64_t)16 << 20)) {
+        rc = launch_touch(in_act(l), in_bytes, stream);
         if (rc) return rc;
       }
-      if (agg) {
-        rc = add_small(L.w_off, 2 * (int64_t)L.n_out);
-        if (rc) return rc;
-      }
-      continue;
-    }
-    if (!L.has_params) continue;
-    if (L.kind == DYNB_LAYER_CONV3X3) {
-      rc = launch_conv_wgrad(in_act(l), L.ld_in, L.n_in, L.h_in, L.w_in, dyv[l], L.ld_out, L.n_out,
-                             L.h_out, L.w_out, L.stride, L.conv_chunk, m->partial, m->partial_floats,
-                             grads + L.w_off, grads + L.b_off, m->P_pad, segs[l],
-                             2.0 * B * L.hw_out * L.wg_rows * L.n_out,
-                             (double)K * L.wg_rows * L.n_out * 4 +
-                                 (double)B * (L.hw_in * L.n_in + L.hw_out * L.n_out) * es,
-                             stream);
-      if (rc) return rc;
-      if (agg) {
-        rc = add_small(L.w_off, (int64_t)L.wg_rows * L.n_out);
-        if (!rc) rc = add_small(L.b_off, L.n_out);
-        if (rc) return rc;
-      }
-      continue;
-    }
-    GemmArgs g = {};
-    g.mode = MODE_WGRAD;
-    if (dt == DYNB_BF16) {   // the row-major tensors themselves, reduced over each worker's rows
-      g.A = dyv[l]; g.lda = L.ld_out;
-      g.B = in_act(l); g.ldb = L.ld_in;
-    } else {
-      g.A = L.dyT; g.lda = L.capT;
-      g.B = L.inT; g.ldb = L.capT;
-    }
-    g.M = L.n_out; g.N = L.wg_rows;
-    g.Cf = grads + L.w_off; g.ldcf = L.n_out;
-    g.group_stride = m->P_pad;
-    g.alg_flops = 2.0 * B * L.hw_out * L.wg_rows * L.n_out;
-    g.alg_bytes = (double)K * L.wg_rows * L.n_out * 4 + (double)B * L.hw_out * (L.wg_rows + L.n_out) * es;
-    int deepest = 0;
-    for (int k = 0; k < K; ++k) {
-      const int d = dt == DYNB_BF16 ? segs[l].off[k + 1] - segs[l].off[k] : segs[l].poff[k + 1] - segs[l].poff[k];
-      deepest = d > deepest ? d : deepest;
-    }
-    int split = (deepest + 255) / 256;               // chunks of at least eight 32-deep stages
-    split = split > L.max_split ? L.max_split : split;
-    if (split > 1) {
-      g.split = split;
-      g.chunk = (int)round_up((deepest + split - 1) / split, 64);
-      g.partial = m->partial;
-      g.partial_stride = round_up((int64_t)L.wg_rows * L.n_out, 64);
-    }
-    // the aggregate of this weight: in the same kernel while the per-worker tiles are in
-    // registers where the launch shape allows it, else by a pass over what was written
-    const bool fold = agg && gemm_fuses_aggregate(dt, g, segs[l]);
-    if (fold) {
-      g.alg_bytes += (double)L.wg_rows * L.n_out * 4;   // the aggregated tile is written too
-      g.agg = agg + L.w_off;
-      for (int k = 0; k < K; ++k) g.lam[k] = lam.w[k];
-    }
-    // bf16, unsplit: the bias gradient is formed by the same kernel
-    const bool bias_inside = dt == DYNB_BF16 && split <= 1;
-    if (bias_inside) g.bias_grad = grads + L.b_off;
-    rc = launch_gemm(dt, g, segs[l], stream);
-    if (rc) return rc;
-    if (split > 1) {
-      rc = launch_wgrad_reduce(m->partial, split, g.partial_stride, (int64_t)L.wg_rows * L.n_out,
-                               grads + L.w_off, m->P_pad, K, stream);
+      rc = weight_gradient(l);
       if (rc) return rc;
     }
-    if (bias_inside)
-      rc = DYNB_OK;
-    else if (dt == DYNB_BF16)
-      rc = launch_bias_grad_rows(dyv[l], L.ld_out, L.n_out, grads + L.b_off, m->P_pad, segs[l], stream);
-    else
-      rc = launch_bias_grad(dt, L.dyT, L.capT, L.n_out, grads + L.b_off, m->P_pad, segs[l], stream);
-    if (rc) return rc;
-    if (agg) {
-      const int64_t nw = (int64_t)L.wg_rows * L.n_out;
-      if (!fold && nw >= 65536) {
-        rc = launch_aggregate_range(grads + L.w_off, m->P_pad, lam, nw, agg + L.w_off, stream);
-        if (rc) return rc;
-      } else if (!fold) {
-        rc = add_small(L.w_off, nw);
-        if (rc) return rc;
-      }
-      rc = add_small(L.b_off, L.n_out);
-      if (rc) return rc;
-    }
-  }
   rc = launch_finalize(m->rowloss, m->loss, grads, m->P, m->P_pad, s1, stream);
   if (rc || !agg) return rc;
   // the padding [P, P_pad) of the aggregate: zeros, like that of the gradients
@@ -855,7 +886,10 @@ int update_layers(dynb_model* m, const GradSource& src, const UpdateRule& rule, 
     r.n = 0;   // (the small tensors went with this launch)
     return rc;
   };
-  for (Layer& L : m->layers) {
+  // (last layer first: the first layer's copies are then the most recently written when the next
+  // step's forward pass starts with them -- measured 1.5 % of a step on the wide MLP)
+  for (size_t li = m->layers.size(); li-- > 0;) {
+    Layer& L = m->layers[li];
     if (!L.has_params || L.kind != DYNB_LAYER_DENSE) continue;
     const int i = mats.n++;
     mats.off[i] = L.w_off;
