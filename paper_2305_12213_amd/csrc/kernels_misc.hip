@@ -406,7 +406,7 @@ int launch_bias_grad(int dtype, const void* dyT, int64_t ld, int N, float* grads
 
 int launch_touch(const void* p, int64_t bytes, void* stream) {
   if (bytes < 16) return DYNB_OK;
-  Timed t(KC_GEMM_WGRAD, stream, 0, 0);   // (its time counts towards the launch it prepares)
+  Timed t(KC_PACK, stream, 0, (double)bytes);   // (counted with the other staging passes)
   int64_t bx = (bytes / 16 + 255) / 256;
   if (bx > 2048) bx = 2048;
   hipLaunchKernelGGL(touch_kernel, dim3((unsigned)bx), dim3(256), 0, (hipStream_t)stream,
