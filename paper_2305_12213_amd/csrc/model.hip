@@ -702,6 +702,13 @@ int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const 
       // those re-fetches come from HBM and compete with the tile stores: 0.29 - 0.31 ms per
       // 4096 x 4096 launch instead of 0.24 - 0.28.
       if (L.kind == DYNB_LAYER_DENSE && dt == DYNB_BF16) {
+        // (no ReLU below: the input gradient had no mask to read, so the layer's input gets its
+        // own sequential read, as the first layer's does further down)
+        const int64_t in_bytes = (int64_t)rows_in * L.ld_in * es;
+        if (!Lp.relu && in_bytes >= ((int64_t)16 << 20)) {
+          rc = launch_touch(in_act(l), in_bytes, stream);
+          if (rc) return rc;
+        }
         rc = weight_gradient(l);
         if (rc) return rc;
       }

@@ -159,6 +159,17 @@ def test_large_tile_kernels_on_ragged_edges(capsys):
     check_worker_gradients(spec, params, x, y, b, label="256-tile ragged")
 
 
+def test_linear_hidden_layer_with_a_large_input():
+    # no ReLU under the second layer: its input gradient reads no mask, so the schedule gives the
+    # layer's 17 MB input a sequential read of its own before the weight gradient re-fetches it
+    spec = {"dtype": "bf16", "input": (512,), "classes": 24,
+            "layers": [synth.dense(512, 4096, relu=False), synth.dense(4096, 24, relu=False)]}
+    params = synth.init_params(spec, "he", 47)
+    b = [1000, 600, 0, 512]
+    x, y = synth.make_batch(spec, "normal", sum(b), 47, 0)
+    check_worker_gradients(spec, params, x, y, b, label="linear hidden layer")
+
+
 def test_same_handle_serves_changing_batch_splits():
     # batch sizes change every step; nothing is rebuilt per size and stale padding is harmless
     spec = synth.mlp_spec([128, 96, 10], "bf16")
