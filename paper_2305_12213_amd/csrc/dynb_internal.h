@@ -157,12 +157,14 @@ int launch_bias_grad_rows(const void* dy, int64_t ld, int N, float* grads, int64
                           const Segs& s, void* stream);
 int launch_bias_grad(int dtype, const void* dyT, int64_t ld, int N, float* grads,
                      int64_t group_stride, const Segs& s, void* stream);
-// loss[g] = mean of rowloss over worker g's rows; grads[g][P..P_pad) = 0
 // Reads `bytes` (a multiple of 16, 16-byte aligned) and discards them: what a launch is about to
 // fetch several times over, brought into the last-level cache by one sequential pass.
 int launch_touch(const void* p, int64_t bytes, void* stream);
+// loss[g] = mean of rowloss over worker g's rows; grads[g][P..P_pad) = 0.  With `out` (and lam,
+// small): also out[range] = sum_k lam_k grads[k][range] for every range of `small`, and
+// out[P..P_pad) = 0, in the same launch.
 int launch_finalize(const float* rowloss, float* loss, float* grads, int64_t P, int64_t P_pad,
-                    const Segs& s, void* stream);
+                    const Segs& s, const Lambdas* lam, const Ranges* small, float* out, void* stream);
 int launch_aggregate(const float* grads, const Lambdas& lam, int64_t n, float* out, void* stream);
 int launch_sgd(float* params, const float* g, int64_t n, float lr, void* stream);
 int launch_momentum(float* params, float* v, const float* g, int64_t n, float lr, float mu,

@@ -229,12 +229,26 @@ __global__ __launch_bounds__(256) void bias_grad_kernel(const T* __restrict__ dy
   if (lane == 0) grads[(int64_t)g * group_stride + n] = acc;
 }
 
-// ---- per-worker mean loss, and zero tail of each worker's gradient vector ----------------
+// ---- per-worker mean loss, zero tail of each worker's gradient vector, and (workgroups behind
+// the first K) the weighted aggregate, Eq. 2, of the small tensors listed in r -- one launch
+// for what used to be two tiny ones at the end of every step ---------------------------------
 __global__ __launch_bounds__(64) void finalize_kernel(const float* __restrict__ rowloss,
                                                       float* __restrict__ loss,
                                                       float* __restrict__ grads, int64_t P,
-                                                      int64_t P_pad, Segs s) {
-  const int g = blockIdx.x, lane = threadIdx.x;
+                                                      int64_t P_pad, Segs s, Lambdas lam, Ranges r,
+                                                      float* __restrict__ out, int range_bx) {
+  const int lane = threadIdx.x;
+  if ((int)blockIdx.x >= s.K) {
+    const int q = blockIdx.x - s.K, ri = q / range_bx, bx = q % range_bx;
+    const int64_t off = r.off[ri], n = r.len[ri];
+    for (int64_t i = (int64_t)bx * 64 + lane; i < n; i += (int64_t)range_bx * 64) {
+      float acc = 0.f;
+      for (int k = 0; k < lam.K; ++k) acc += lam.w[k] * grads[(int64_t)k * P_pad + off + i];
+      out[off + i] = acc;
+    }
+    return;
+  }
+  const int g = blockIdx.x;
   const int bk = s.off[g + 1] - s.off[g];
   // eight independent partial sums per lane: the loads of a round are in flight together
   float part[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -248,6 +262,10 @@ __global__ __launch_bounds__(64) void finalize_kernel(const float* __restrict__ 
   if (lane == 0) loss[g] = bk > 0 ? acc / (float)bk : 0.f;
   if (grads)
     for (int64_t p = P + lane; p < P_pad; p += 64) grads[(int64_t)g * P_pad + p] = 0.f;
+  // (the aggregate's padding is written here, not summed from the tails above: workgroups of
+  // one launch run in no particular order)
+  if (out && g == 0)
+    for (int64_t p = P + lane; p < P_pad; p += 64) out[p] = 0.f;
 }
 
 // ---- read and discard (see launch_touch) -------------------------------------------------
@@ -415,10 +433,27 @@ int launch_touch(const void* p, int64_t bytes, void* stream) {
 }
 
 int launch_finalize(const float* rowloss, float* loss, float* grads, int64_t P, int64_t P_pad,
-                    const Segs& s, void* stream) {
-  Timed t(KC_FINALIZE, stream, 0, 0);
-  hipLaunchKernelGGL(finalize_kernel, dim3(s.K), dim3(64), 0, (hipStream_t)stream, rowloss, loss,
-                     grads, P, P_pad, s);
+                    const Segs& s, const Lambdas* lam, const Ranges* small, float* out, void* stream) {
+  Lambdas l;
+  l.K = 0;
+  Ranges r;
+  r.n = 0;
+  int64_t longest = 0, total = 0;
+  if (out && lam && small) {
+    l = *lam;
+    r = *small;
+    for (int i = 0; i < r.n; ++i) {
+      longest = r.len[i] > longest ? r.len[i] : longest;
+      total += r.len[i];
+    }
+  }
+  int64_t bx = (longest + 63) / 64;
+  if (bx > 256) bx = 256;
+  if (bx < 1) bx = 1;
+  const int extra = longest > 0 ? (int)bx * r.n : 0;
+  Timed t(KC_FINALIZE, stream, 2.0 * l.K * total, 4.0 * (l.K + 1) * total);
+  hipLaunchKernelGGL(finalize_kernel, dim3(s.K + extra), dim3(64), 0, (hipStream_t)stream, rowloss, loss,
+                     grads, P, P_pad, s, l, r, out, (int)bx);
   return ok("finalize");
 }
 

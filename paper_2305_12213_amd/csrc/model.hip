@@ -728,11 +728,10 @@ int run_forward_backward(dynb_model* m, const float* x, const int32_t* y, const 
       rc = weight_gradient(l);
       if (rc) return rc;
     }
-  rc = launch_finalize(m->rowloss, m->loss, grads, m->P, m->P_pad, s1, stream);
-  if (rc || !agg) return rc;
-  // the padding [P, P_pad) of the aggregate: zeros, like that of the gradients
-  rc = add_small(m->P, m->P_pad - m->P);
-  return rc ? rc : flush_small();
+  // per-worker losses and zero padding; with an aggregate: the small tensors still on the list
+  // and the aggregate's padding [P, P_pad) in the same launch
+  return launch_finalize(m->rowloss, m->loss, grads, m->P, m->P_pad, s1, agg ? &lam : nullptr,
+                         agg ? &small : nullptr, agg, stream);
 }
 }  // namespace
 
