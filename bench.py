@@ -6,7 +6,8 @@ the ragged split b[K], weighted aggregation, SGD update (with the 16-bit weight 
 the host controller that resizes b[K] from the synthetic iteration times.  Inputs are resident
 in HBM before the timed region.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps 20] [--warmup 3] [--workload 4] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps 200] [--warmup 20] [--workload 4] [--no-cpu-baseline]
+                    [--no-other-workloads]
 """
 import argparse
 import json
