@@ -55,6 +55,7 @@ enum KClass {
   KC_WEIGHT_CAST,
   KC_CONV_AUX,
   KC_NORM,
+  KC_GEMM_WGRAD_SMALL,   // bf16 weight gradients that run on the 128 x 128-tile kernels
   KC_COUNT
 };
 

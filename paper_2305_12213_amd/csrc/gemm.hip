@@ -1088,8 +1088,15 @@ int launch_gemm(int dtype, const GemmArgs& args, const Segs& s, void* stream) {
   if (a.addend && (dtype != DYNB_BF16 || a.mode != MODE_DGRAD))
     return fail(DYNB_ERR_UNSUPPORTED, "gemm: an addend belongs to a bf16 input gradient");
   const int groups = a.mode == MODE_WGRAD ? s.K : 1;
-  const KClass cls = a.mode == MODE_FWD ? KC_GEMM_FWD : a.mode == MODE_DGRAD ? KC_GEMM_DGRAD
-                                                                              : KC_GEMM_WGRAD;
+  KClass cls = a.mode == MODE_FWD ? KC_GEMM_FWD : a.mode == MODE_DGRAD ? KC_GEMM_DGRAD
+                                                                        : KC_GEMM_WGRAD;
+  // (the two tile sizes of the bf16 weight gradient are different kernels with different
+  // bounds: timed apart, so that a class's average launch is one kernel's)
+  if (a.mode == MODE_WGRAD && dtype == DYNB_BF16 && !a.conv) {
+    const bool large = a.agg ? tiles_of(a, AGG_BM, AGG_BN) >= 256
+                             : (int64_t)((a.M + 255) / 256) * ((a.N + 255) / 256) >= 192;
+    if (!large) cls = KC_GEMM_WGRAD_SMALL;
+  }
   Timed t(cls, stream, a.alg_flops, a.alg_bytes);
   if (a.conv) {
     if (dtype != DYNB_BF16 || a.mode == MODE_WGRAD || (a.cp & 7) || (a.stride != 1 && a.stride != 2))
