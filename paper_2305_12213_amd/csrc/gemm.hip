@@ -152,7 +152,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
 
   __shared__ uint4 sA[S][BM * GPR];
   __shared__ uint4 sB[S][BN * GPR];
-  float* const sStage = PatchArea<MODE == MODE_WGRAD ? NW * 32 * SPITCH : 0>::get();
+  // (128 x 128 aggregating weight gradient: the waves of a tile share one staging area of the
+  // whole tile, see store_rows below; otherwise a private 32 x 32 patch per wave)
+  constexpr bool ROWS = AGG && BM == 128 && BN == 128 && TM == 1;
+  constexpr int RPITCH = BM + 4;                        // floats per row of the shared staging area
+  float* const sStage =
+      PatchArea<MODE != MODE_WGRAD ? 0 : ROWS ? BN * RPITCH : NW * 32 * SPITCH>::get();
 
   // groups of this workgroup: [g_lo, g_hi).  A group is a worker, or, when the reduction is
   // split, one chunk of a worker's rows (group id = worker * split + chunk).
@@ -507,7 +512,46 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
   // a private LDS patch so that one store instruction writes 8 rows x 128 contiguous bytes
   // (whole lines) instead of 32 rows x 32 bytes: these stores are the largest HBM stream of a
   // step.  LDS operations of one wave execute in order, so the patch needs no barrier.
+  // The same for the 128 x 128 aggregating kernel, whose matrices are the narrow ones (an output
+  // layer of 1000 columns: rows pitched 4000 bytes start on odd 32-byte boundaries, and every
+  // 128-byte run of a wave then ends in two partial lines -- the launch takes 120 us at 1000
+  // columns and 93 us at 1008).  All waves stage their sub-tiles in one area of the whole tile,
+  // and after a barrier each wave writes 16 rows as 2 rows x 512 contiguous bytes per instruction:
+  // two partial lines per tile row instead of eight.  The area is next written at the end of the
+  // next worker, at least one stage barrier later, by which time every wave has read it.
+  auto store_rows = [&](float* Cg, f32x16 (&src)[TM][TN]) {
+    if constexpr (ROWS) {
+      float* area = sStage;
+#pragma unroll
+      for (int b = 0; b < TN; ++b)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const f32x4 o = {src[0][b][4 * q], src[0][b][4 * q + 1], src[0][b][4 * q + 2], src[0][b][4 * q + 3]};
+          *(f32x4*)&area[(wn * (BN / WN) + 32 * b + l31) * RPITCH + wm * 32 + 8 * q + hi4] = o;
+        }
+      __syncthreads();
+      constexpr int RW = BN / NW;                      // rows per wave
+      const int r0 = wave * RW + (lane >> 5), c = (lane & 31) * 4;
+      const bool col_ok = i0 + c + 3 < p.M;            // (M is a multiple of 4 here)
+      f32x4 o[RW / 2];
+#pragma unroll
+      for (int t = 0; t < RW / 2; ++t) o[t] = *(const f32x4*)&area[(r0 + 2 * t) * RPITCH + c];
+#pragma unroll
+      for (int t = 0; t < RW / 2; ++t) {
+        const int j = j0 + r0 + 2 * t;
+        if (col_ok && j < p.N)
+          __builtin_nontemporal_store(o[t], (f32x4*)(Cg + (int64_t)j * p.ldcf + i0 + c));
+      }
+    }
+  };
   auto store_tile = [&](float* Cg, f32x16 (&src)[TM][TN]) {
+    if constexpr (ROWS) {
+      if ((p.ldcf & 3) == 0 && (p.M & 3) == 0 && (((uintptr_t)Cg) & 15) == 0) {   // (uniform)
+        store_rows(Cg, src);
+        return;
+      }
+      __syncthreads();   // (other waves may still be reading the shared area of a call that took the path above)
+    }
     float* patch = &sStage[wave * 32 * SPITCH];
     const bool vec_ok = (p.ldcf & 3) == 0 && (((uintptr_t)Cg) & 15) == 0;
     const bool interior = vec_ok && i0 + BM <= p.M && j0 + BN <= p.N;   // no edge checks needed
@@ -791,6 +835,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs p, Seg
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     if constexpr (!RM) __syncthreads();   // ... all waves' copies, before any wave's patch
   }
+  if constexpr (ROWS) __syncthreads();   // the last worker's tile has been read out of the shared area
   if constexpr (AGG) store_tile(p.agg, agg);
 
   if constexpr (MODE != MODE_WGRAD) {
@@ -1008,7 +1053,7 @@ void launch_bf16_wgrad_agg(GemmArgs a, const Segs& s, hipStream_t st) {
     hipLaunchKernelGGL((gemm_bf16_kernel<AGG_BM, AGG_BN, 4, 2, MODE_WGRAD, false, 5, true>),
                        dim3((unsigned)tiles_of(a, AGG_BM, AGG_BN)), dim3(512), 0, st, a, s);
   else
-    hipLaunchKernelGGL((gemm_bf16_kernel<AGG_SMALL, AGG_SMALL, 4, 2, MODE_WGRAD, false, 7, true>),
+    hipLaunchKernelGGL((gemm_bf16_kernel<AGG_SMALL, AGG_SMALL, 4, 2, MODE_WGRAD, false, 5, true>),
                        dim3((unsigned)tiles_of(a, AGG_SMALL, AGG_SMALL)), dim3(512), 0, st, a, s);
 }
 
