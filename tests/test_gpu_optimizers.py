@@ -139,6 +139,8 @@ def test_forward_backward_aggregate_equals_the_two_call_form():
              (SPECS[3][1](), [3, 9, 0, 4]),
              (synth.mlp_spec([2500, 4200, 16], "bf16"), [700, 1, 0, 257, 66]),
              (synth.mlp_spec([4100, 1000, 16], "bf16"), [300, 2, 0, 129, 40]),
+             # ... and with a width that rules out 16-byte stores (the same kernel's element-wise path)
+             (synth.mlp_spec([4100, 1001, 16], "bf16"), [300, 2, 0, 129, 40]),
              # 64 workers, several of them idle: both aggregating kernels at the largest K
              (synth.mlp_spec([2500, 4200, 16], "bf16"), [(i * 37) % 23 for i in range(64)]),
              (synth.mlp_spec([2100, 2100, 16], "bf16"), [(i * 29) % 19 for i in range(64)])]
