@@ -56,6 +56,7 @@ enum KClass {
   KC_CONV_AUX,
   KC_NORM,
   KC_GEMM_WGRAD_SMALL,   // bf16 weight gradients that run on the 128 x 128-tile kernels
+  KC_GEMM_SMALL,         // bf16 forward / input-gradient products on the 128 x 128-tile kernel
   KC_COUNT
 };
 

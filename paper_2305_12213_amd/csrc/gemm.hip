@@ -1141,6 +1141,9 @@ int launch_gemm(int dtype, const GemmArgs& args, const Segs& s, void* stream) {
     const bool large = a.agg ? tiles_of(a, AGG_BM, AGG_BN) >= 256
                              : (int64_t)((a.M + 255) / 256) * ((a.N + 255) / 256) >= 192;
     if (!large) cls = KC_GEMM_WGRAD_SMALL;
+  } else if (dtype == DYNB_BF16 && !a.conv &&
+             (int64_t)((a.M + 255) / 256) * ((a.N + 255) / 256) < 192) {
+    cls = KC_GEMM_SMALL;
   }
   Timed t(cls, stream, a.alg_flops, a.alg_bytes);
   if (a.conv) {

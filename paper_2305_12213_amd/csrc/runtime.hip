@@ -48,7 +48,7 @@ hipEvent_t get_event() {
 const char* kNames[KC_COUNT] = {"gemm_fwd",  "gemm_dgrad", "gemm_wgrad", "pack_input",
                                 "transpose", "softmax_xent", "bias_grad", "finalize",
                                 "weighted_aggregate", "sgd_update", "weight_cast", "conv_aux", "norm_add",
-                                "gemm_wgrad_small_tiles"};
+                                "gemm_wgrad_small_tiles", "gemm_small_tiles"};
 }  // namespace
 
 // The bracket holds its two events itself and hands them to the pending list only when both
